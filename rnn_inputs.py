@@ -1,0 +1,166 @@
+"""Seeded synthetic inputs for the Elman-RNN training path.
+
+This module only draws random numbers and shapes them; it contains none of the
+method's arithmetic (no recurrence, no softmax, no gradients).  Both the CPU
+oracle's tests and the GPU library's tests/bench import it so that the two sides
+see identical arrays.
+
+The paper's recurrent benchmark (its section on benchmarking recurrent networks)
+trains a simple recurrent language model with batch size 1 and equal input/output
+vocabulary; its corpus is not available, so token streams here are synthetic:
+Zipf-distributed ids over a finite vocabulary reproduce the skewed token
+frequencies that matter to the embedding gather/scatter.  Nothing else on the
+path depends on token identity.
+
+Layouts (all float32, row-major, time-major):
+  token input : x int32[T,B], y int32[T,B] (next-token targets)
+  dense input : X f32[T,B,D], Y f32[T,B,O]
+  Wx f32[NV,H] (token input; row v is token v's input vector) or f32[H,D] (dense)
+  Wh f32[H,H]  (pre-activation a[j] = sum_i Wh[j,i] * h_prev[i])
+  b  f32[H],  V f32[H,OUT] (z[k] = sum_i h[i] * V[i,k] + c[k]),  c f32[OUT]
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BASE_SEED = 12115590
+
+INPUT_TOKENS, INPUT_DENSE = 0, 1
+ACT_SIGMOID, ACT_TANH = 0, 1
+LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
+
+# The five benchmark configurations.  "windows" > 1 means a token stream cut into
+# consecutive truncated-BPTT windows of seq_len steps with the hidden state carried.
+CONFIGS = {
+    "C1": dict(in_dim=64, hidden=16, out_dim=64, seq_len=32, batch=1, windows=1,
+               input_kind=INPUT_TOKENS, act=ACT_SIGMOID, loss_kind=LOSS_SOFTMAX_CE,
+               tokens="uniform", wdist=("normal", 0.1), seed=BASE_SEED + 1000),
+    "C2": dict(in_dim=10000, hidden=100, out_dim=10000, seq_len=10, batch=1, windows=10000,
+               input_kind=INPUT_TOKENS, act=ACT_SIGMOID, loss_kind=LOSS_SOFTMAX_CE,
+               tokens="zipf", wdist=("normal", 0.1), seed=BASE_SEED + 2000),
+    "C3": dict(in_dim=10000, hidden=500, out_dim=10000, seq_len=100, batch=1, windows=1,
+               input_kind=INPUT_TOKENS, act=ACT_SIGMOID, loss_kind=LOSS_SOFTMAX_CE,
+               tokens="zipf", wdist=("uniform", 0.05), seed=BASE_SEED + 3000),
+    "C4": dict(in_dim=10000, hidden=1024, out_dim=10000, seq_len=256, batch=64, windows=1,
+               input_kind=INPUT_TOKENS, act=ACT_SIGMOID, loss_kind=LOSS_SOFTMAX_CE,
+               tokens="zipf", wdist=("normal_fan", None), seed=BASE_SEED + 4000),
+    "C5": dict(in_dim=128, hidden=256, out_dim=128, seq_len=4096, batch=128, windows=1,
+               input_kind=INPUT_DENSE, act=ACT_TANH, loss_kind=LOSS_LINEAR_MSE,
+               tokens=None, wdist=("normal_fan", None), seed=BASE_SEED + 5000),
+}
+
+ZIPF_S = 1.1
+
+
+def zipf_cdf(nv: int, s: float = ZIPF_S) -> np.ndarray:
+    """CDF of P(id = r) proportional to (r+1)^-s on r = 0..nv-1 (exact finite normalisation)."""
+    w = np.arange(1, nv + 1, dtype=np.float64) ** (-s)
+    cdf = np.cumsum(w)
+    return cdf / cdf[-1]
+
+
+def draw_tokens(rng: np.random.Generator, n: int, nv: int, kind: str) -> np.ndarray:
+    """n token ids in [0, nv): 'uniform', or 'zipf' by inverse CDF (id 0 most frequent)."""
+    if kind == "uniform":
+        return rng.integers(0, nv, size=n, dtype=np.int64).astype(np.int32)
+    if kind == "zipf":
+        u = rng.random(n)
+        ids = np.searchsorted(zipf_cdf(nv), u, side="left")
+        return np.minimum(ids, nv - 1).astype(np.int32)
+    raise ValueError(f"unknown token distribution {kind!r}")
+
+
+def _draw_weight(rng, shape, wdist, fan_in):
+    kind, scale = wdist
+    if kind == "normal":
+        w = rng.normal(0.0, scale, size=shape)
+    elif kind == "uniform":
+        w = rng.uniform(-scale, scale, size=shape)
+    elif kind == "normal_fan":  # standard deviation 1/sqrt(fan_in)
+        w = rng.normal(0.0, 1.0 / np.sqrt(fan_in), size=shape)
+    else:
+        raise ValueError(f"unknown weight distribution {kind!r}")
+    return np.ascontiguousarray(w, dtype=np.float32)
+
+
+def make_case(in_dim, hidden, out_dim, seq_len, batch, *, input_kind=INPUT_TOKENS,
+              act=ACT_SIGMOID, loss_kind=LOSS_SOFTMAX_CE, tokens="zipf",
+              wdist=("normal", 0.1), seed=BASE_SEED, windows=1, bias_std=0.0,
+              with_h0=False, with_dh_last=False, **_unused):
+    """Draw one problem instance.  Returns a dict of numpy arrays plus the sizes.
+
+    Token input: a stream of windows*seq_len+1 ids per batch row is drawn; x is the
+    first windows*seq_len of them and y the same stream shifted by one (next token),
+    both shaped [windows*seq_len, batch].  Window w of a stream uses rows
+    [w*seq_len, (w+1)*seq_len).
+    Dense input: X ~ N(0,1) of shape [T,B,D]; Y[0] = 0 and Y[t] = X[t-1] (needs O == D).
+    Sub-streams are spawned in the fixed order (inputs, Wx, Wh, V, extras).
+    """
+    ss = np.random.SeedSequence(seed)
+    s_in, s_wx, s_wh, s_v, s_extra = ss.spawn(5)
+    T_total = seq_len * windows
+    H = hidden
+    out = dict(in_dim=in_dim, hidden=hidden, out_dim=out_dim, seq_len=seq_len, batch=batch,
+               windows=windows, input_kind=input_kind, act=act, loss_kind=loss_kind)
+
+    if input_kind == INPUT_TOKENS:
+        rows = []
+        for s_row in s_in.spawn(batch):
+            rows.append(draw_tokens(np.random.default_rng(s_row), T_total + 1, in_dim, tokens))
+        ids = np.stack(rows, axis=1)                      # [T_total+1, B]
+        out["x"] = np.ascontiguousarray(ids[:-1])
+        if loss_kind == LOSS_SOFTMAX_CE:
+            if out_dim != in_dim:                         # targets must lie in [0, out_dim)
+                out["y"] = np.ascontiguousarray(ids[1:] % out_dim).astype(np.int32)
+            else:
+                out["y"] = np.ascontiguousarray(ids[1:])
+        wx_shape, wx_fan = (in_dim, H), in_dim
+    else:
+        rng = np.random.default_rng(s_in)
+        X = rng.standard_normal(size=(T_total, batch, in_dim), dtype=np.float32)
+        out["X"] = X
+        if loss_kind == LOSS_SOFTMAX_CE:
+            out["y"] = rng.integers(0, out_dim, size=(T_total, batch)).astype(np.int32)
+        wx_shape, wx_fan = (H, in_dim), in_dim
+    if loss_kind == LOSS_LINEAR_MSE:
+        if input_kind == INPUT_DENSE and out_dim == in_dim:
+            Y = np.zeros_like(out["X"])
+            Y[1:] = out["X"][:-1]
+        else:
+            Y = np.random.default_rng(s_extra.spawn(1)[0]).standard_normal(
+                size=(T_total, batch, out_dim), dtype=np.float32)
+        out["Y"] = Y
+
+    out["Wx"] = _draw_weight(np.random.default_rng(s_wx), wx_shape, wdist, wx_fan)
+    out["Wh"] = _draw_weight(np.random.default_rng(s_wh), (H, H), wdist, H)
+    out["V"] = _draw_weight(np.random.default_rng(s_v), (H, out_dim), wdist, H)
+    rng_e = np.random.default_rng(s_extra)
+    if bias_std > 0.0:
+        out["b"] = rng_e.normal(0.0, bias_std, size=H).astype(np.float32)
+        out["c"] = rng_e.normal(0.0, bias_std, size=out_dim).astype(np.float32)
+    else:
+        out["b"] = np.zeros(H, dtype=np.float32)
+        out["c"] = np.zeros(out_dim, dtype=np.float32)
+    lo, hi = (0.05, 0.95) if act == ACT_SIGMOID else (-0.9, 0.9)
+    out["h0"] = rng_e.uniform(lo, hi, size=(batch, H)).astype(np.float32) if with_h0 else None
+    out["dh_last"] = (rng_e.normal(0.0, 0.01, size=(batch, H)).astype(np.float32)
+                      if with_dh_last else None)
+    return out
+
+
+def make_config(name: str, **overrides):
+    """One of the five named configurations (C1..C5), optionally with sizes overridden."""
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    return make_case(**cfg)
+
+
+def window(case: dict, w: int) -> dict:
+    """View of truncated-BPTT window w of a multi-window token stream (no copies of weights)."""
+    T = case["seq_len"]
+    out = dict(case)
+    out["windows"] = 1
+    for k in ("x", "y", "X", "Y"):
+        if k in case and case[k] is not None:
+            out[k] = np.ascontiguousarray(case[k][w * T:(w + 1) * T])
+    return out
