@@ -1,0 +1,145 @@
+/*
+ * rnn.h -- C ABI of the MI355X (gfx950) Elman recurrent-network training path.
+ *
+ * The path is the one the paper's symbolic loop (its "Scan" section) compiles for a simple
+ * recurrent language model (its recurrent-network benchmark section): a forward loop over
+ * the leading (time) axis, an output layer with a loss, and backpropagation through time
+ * that keeps every hidden state (Scan property 1).  The paper prints no equations for the
+ * network; the ones used are the textbook Elman equations:
+ *
+ *     a_t = in_t + Wh h_{t-1} + b          in_t = Wx[x_t,:] (token ids) or Wx x_t (dense)
+ *     h_t = act(a_t)                       act  = sigmoid or tanh
+ *     z_t = V^T h_t + c
+ *     softmax-CE : loss = mean over the T*B rows of ( logsumexp(z) - z[y] )   (natural log)
+ *     linear-MSE : loss = mean over the T*B*O entries of (z - Y)^2            (no factor 1/2)
+ *
+ * Conventions shared by every entry point
+ *   - All tensors are float32, row-major and time-major ([T,B,...]); token ids and class
+ *     targets are int32.  Every data pointer is a DEVICE pointer unless it says "host";
+ *     rnn_dims / rnn_params / rnn_grads structs themselves live in HOST memory.
+ *   - Layouts:  Wx [in_dim,H] for token input (row v = input vector of token v) or [H,in_dim]
+ *     for dense input;  Wh [H,H] with a[j] = sum_i Wh[j,i] h[i];  b [H];
+ *     V [H,out_dim] with z[k] = sum_i h[i] V[i,k] + c[k];  c [out_dim].
+ *     Gradients have the layout of their parameter.
+ *   - Ownership: the caller owns every buffer including the workspace; the library never
+ *     allocates, frees or keeps device memory (the paper's garbage-collection-free linker
+ *     keeps buffers alive between calls for the same reason).
+ *   - Asynchrony: every call only enqueues kernels on `hip_stream` (a hipStream_t, NULL =
+ *     the default stream) and returns, as in the paper's section on asynchronous GPU calls;
+ *     flag RNN_FLAG_SYNC makes the call wait for the stream (for profiling).
+ *   - Trust: the hot calls do O(1) host-side argument checks and never read device data on
+ *     the host; out-of-range token ids are undefined behaviour unless rnn_check_tokens is
+ *     used first (the paper's trusted-input switch makes the same trade).
+ *   - Call order on one stream with one workspace: rnn_forward -> rnn_loss -> rnn_bptt.
+ *     rnn_loss leaves the logits and row statistics in the workspace for rnn_bptt; with
+ *     RNN_FLAG_BPTT_RECOMPUTE rnn_bptt recomputes them itself and needs no prior rnn_loss.
+ *   - Pointers must be 16-byte aligned.  No size needs to be a multiple of anything.
+ *   - Return value: RNN_OK or a negative RNN_E* code; nothing is printed, nothing aborts.
+ *     When a call returns an error nothing has been enqueued, except RNN_EHIP which reports
+ *     a failed launch.
+ */
+#ifndef RNN_MI355X_H
+#define RNN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RNN_OK            0
+#define RNN_EINVAL       (-1)  /* bad size, enum, or NULL required pointer            */
+#define RNN_EWORKSPACE   (-2)  /* workspace NULL, misaligned or smaller than required */
+#define RNN_EUNSUPPORTED (-3)  /* valid request this build has no kernel for          */
+#define RNN_EHIP         (-4)  /* a HIP launch or query failed                        */
+
+#define RNN_INPUT_TOKENS 0     /* x is int32 [T,B], values in [0,in_dim)              */
+#define RNN_INPUT_DENSE  1     /* x is float32 [T,B,in_dim]                           */
+#define RNN_ACT_SIGMOID  0
+#define RNN_ACT_TANH     1
+#define RNN_LOSS_SOFTMAX_CE 0  /* targets int32 [T,B], values in [0,out_dim)          */
+#define RNN_LOSS_LINEAR_MSE 1  /* targets float32 [T,B,out_dim]                       */
+
+#define RNN_FLAG_ACCUMULATE     1u /* gradients are added to the buffers instead of overwriting */
+#define RNN_FLAG_SYNC           2u /* hipStreamSynchronize before returning                     */
+#define RNN_FLAG_BPTT_RECOMPUTE 4u /* rnn_bptt recomputes logits; no prior rnn_loss needed      */
+#define RNN_FLAG_REFERENCE_KERNELS 8u /* use only the shape-agnostic kernels (A/B testing)      */
+
+typedef struct {
+    int32_t in_dim;     /* vocabulary size NV for token input, feature count D for dense input */
+    int32_t hidden;     /* H                                                                   */
+    int32_t out_dim;    /* NV for softmax-CE, O for linear-MSE                                 */
+    int32_t seq_len;    /* T, number of time steps of this call (one truncated-BPTT window)     */
+    int32_t batch;      /* B, independent sequences                                            */
+    int32_t input_kind; /* RNN_INPUT_*                                                         */
+    int32_t act;        /* RNN_ACT_*                                                           */
+    int32_t loss_kind;  /* RNN_LOSS_*                                                          */
+    uint32_t flags;     /* RNN_FLAG_* bits                                                     */
+} rnn_dims;
+
+typedef struct { const float *Wx, *Wh, *b, *V, *c; } rnn_params; /* device pointers */
+typedef struct { float *dWx, *dWh, *db, *dV, *dc; } rnn_grads;   /* device pointers */
+
+/* Bytes of workspace the three calls below need for these sizes (host-only, no GPU touched).
+ * The same workspace must be passed to forward, loss and bptt of one window. */
+int rnn_workspace_bytes(const rnn_dims *dims, size_t *bytes);
+
+/*
+ * Forward recurrence (the loop of the Scan section, run entirely on the device with no host
+ * work per step -- Scan properties 4 and 5; the input term is gathered/projected for all
+ * steps outside the loop -- property 8).
+ *   x       token ids int32[T,B] or inputs float32[T,B,in_dim]
+ *   h0      initial state [B,H], NULL = zeros
+ *   h_all   [T+1,B,H] receives h_all[0] = h0 and h_all[t+1] = h_t; NULL = keep no history
+ *           (Scan property 6: only a two-slot ring in the workspace is used)
+ *   h_last  [B,H] receives h_{T-1}; NULL = not wanted.  h_all and h_last may not both be NULL.
+ */
+int rnn_forward(const rnn_dims *dims, const rnn_params *params, const void *x,
+                const float *h0, float *h_all, float *h_last,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Output projection and loss over all T*B rows at once (matrix-matrix product hoisted out of
+ * the loop, Scan property 8), evaluated as a max-subtracted log-sum-exp (the numerically
+ * stable form the paper's graph optimiser rewrites to).
+ *   h_all    [T+1,B,H] as written by rnn_forward
+ *   targets  int32[T,B] (CE) or float32[T,B,out_dim] (MSE)
+ *   loss     device float32[1], overwritten
+ */
+int rnn_loss(const rnn_dims *dims, const rnn_params *params, const float *h_all,
+             const void *targets, float *loss,
+             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backpropagation through time (Scan property 1): gradients of the mean loss of this
+ * window, plus <dh_last, h_{T-1}> when dh_last is given, with respect to every parameter.
+ *   x, targets as above; h_all [T+1,B,H] from rnn_forward
+ *   dh_last  [B,H] gradient arriving at h_{T-1} from a later window, NULL = zeros
+ *   grads    all five device pointers required; overwritten, or added to with
+ *            RNN_FLAG_ACCUMULATE.  For token input in overwrite mode rows of dWx whose token
+ *            does not occur are set to exactly 0; in accumulate mode they are not written.
+ *   dh0      [B,H] receives the gradient w.r.t. the initial state; NULL = not wanted
+ * Weight-gradient sums are accumulated in float32 in a fixed order (run-to-run identical).
+ */
+int rnn_bptt(const rnn_dims *dims, const rnn_params *params, const void *x,
+             const void *targets, const float *h_all, const float *dh_last,
+             const rnn_grads *grads, float *dh0,
+             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Opt-in validation: counts ids outside [0,limit) among n int32 ids into bad_count (device
+ * int32[1], overwritten).  Asynchronous like the other calls. */
+int rnn_check_tokens(const void *ids, int64_t n, int32_t limit, int32_t *bad_count,
+                     void *hip_stream);
+
+/* Static description of an error code (host string, never NULL). */
+const char *rnn_strerror(int code);
+
+/* Name of the recurrence kernel family the dispatcher picks for these sizes (host-only; for
+ * reports and tests): "wg_resident", "grid_resident", "batch_mfma" or "reference". */
+const char *rnn_recurrence_variant(const rnn_dims *dims);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNN_MI355X_H */

@@ -1,0 +1,12 @@
+"""MI355X-native Elman-RNN training path (forward recurrence, output layer + loss, BPTT).
+
+Thin ctypes binding over the C ABI in include/rnn.h; every step of the path runs in the HIP
+kernels of librnn_mi355x.so.  There is no CPU fallback: loading fails loudly if the library
+is missing.
+"""
+from .binding import (  # noqa: F401
+    ACT_SIGMOID, ACT_TANH, FLAG_ACCUMULATE, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS, FLAG_SYNC,
+    INPUT_DENSE, INPUT_TOKENS, LOSS_LINEAR_MSE, LOSS_SOFTMAX_CE, Dims, Grads, Params, RnnError,
+    exported_symbols, lib, lib_path, rnn_bptt, rnn_check_tokens, rnn_forward, rnn_loss,
+    rnn_recurrence_variant, rnn_strerror, rnn_workspace_bytes,
+)

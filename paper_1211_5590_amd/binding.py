@@ -1,0 +1,174 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only).
+
+Tensors are torch CUDA tensors used purely as device memory; raw pointers and the current
+torch stream are handed to the library.  Nothing here computes anything.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "librnn_mi355x.so")
+
+INPUT_TOKENS, INPUT_DENSE = 0, 1
+ACT_SIGMOID, ACT_TANH = 0, 1
+LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
+FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 4, 8
+
+EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
+           "rnn_strerror", "rnn_recurrence_variant")
+
+
+class RnnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"rnn error {code}: {msg}")
+        self.code = code
+
+
+class Dims(ctypes.Structure):
+    _fields_ = [("in_dim", ctypes.c_int32), ("hidden", ctypes.c_int32), ("out_dim", ctypes.c_int32),
+                ("seq_len", ctypes.c_int32), ("batch", ctypes.c_int32), ("input_kind", ctypes.c_int32),
+                ("act", ctypes.c_int32), ("loss_kind", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+    @classmethod
+    def of(cls, case: dict, flags: int = 0) -> "Dims":
+        return cls(case["in_dim"], case["hidden"], case["out_dim"], case["seq_len"], case["batch"],
+                   case["input_kind"], case["act"], case["loss_kind"], flags)
+
+
+class Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("Wx", "Wh", "b", "V", "c")]
+
+
+class Grads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("dWx", "dWh", "db", "dV", "dc")]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Load librnn_mi355x.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.rnn_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
+        L.rnn_forward.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, sz, vp]
+        L.rnn_loss.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, sz, vp]
+        L.rnn_bptt.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp,
+                               ctypes.POINTER(Grads), vp, vp, sz, vp]
+        L.rnn_check_tokens.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, vp]
+        L.rnn_strerror.argtypes = [ctypes.c_int]
+        L.rnn_strerror.restype = ctypes.c_char_p
+        L.rnn_recurrence_variant.argtypes = [ctypes.POINTER(Dims)]
+        L.rnn_recurrence_variant.restype = ctypes.c_char_p
+        for name in ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def exported_symbols():
+    L = lib()
+    return [n for n in EXPORTS if hasattr(L, n)]
+
+
+def _p(t):
+    """Device (or host) address of a tensor-like, None -> NULL, int passes through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc):
+    if rc != 0:
+        raise RnnError(rc, rnn_strerror(rc))
+
+
+def rnn_strerror(code: int) -> str:
+    return lib().rnn_strerror(code).decode()
+
+
+def rnn_recurrence_variant(dims: Dims) -> str:
+    return lib().rnn_recurrence_variant(ctypes.byref(dims)).decode()
+
+
+def rnn_workspace_bytes(dims: Dims) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().rnn_workspace_bytes(ctypes.byref(dims), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _params(params) -> Params:
+    if isinstance(params, Params):
+        return params
+    return Params(*[_p(params[k]) for k in ("Wx", "Wh", "b", "V", "c")])
+
+
+def _grads(grads) -> Grads:
+    if isinstance(grads, Grads):
+        return grads
+    return Grads(*[_p(grads[k]) for k in ("dWx", "dWh", "db", "dV", "dc")])
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def rnn_forward(dims, params, x, h0, h_all, h_last, workspace, stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr = _params(params)
+    rc = lib().rnn_forward(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(h0), _p(h_all),
+                           _p(h_last), wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_loss(dims, params, h_all, targets, loss, workspace, stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr = _params(params)
+    rc = lib().rnn_loss(ctypes.byref(dims), ctypes.byref(pr), _p(h_all), _p(targets), _p(loss),
+                        wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_bptt(dims, params, x, targets, h_all, dh_last, grads, dh0, workspace, stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr, gr = _params(params), _grads(grads)
+    rc = lib().rnn_bptt(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(targets), _p(h_all),
+                        _p(dh_last), ctypes.byref(gr), _p(dh0), wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_check_tokens(ids, n, limit, bad_count, stream=None, check=True):
+    rc = lib().rnn_check_tokens(_p(ids), int(n), int(limit), _p(bad_count), _stream(stream))
+    if check:
+        _check(rc)
+    return rc

@@ -1,0 +1,329 @@
+// C ABI of the Elman-RNN training path: argument checks, workspace carving, kernel dispatch.
+// Every call only enqueues kernels on the caller's stream (the paper's section on
+// asynchronous GPU calls) into caller-owned buffers (its garbage-collection-free linker),
+// and does O(1) host work whatever the sequence length (its trusted-input switch).
+#include "../../include/rnn.h"
+
+#include "internal.hpp"
+
+namespace {
+
+using namespace rnn;
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, total;  // byte offsets
+};
+
+struct Sizes {
+    int NVin, H, O, T, B;
+    long long N;
+    bool tokens, ce;
+};
+
+bool dims_valid(const rnn_dims* d) {
+    if (!d) return false;
+    if (d->in_dim <= 0 || d->hidden <= 0 || d->out_dim <= 0 || d->seq_len <= 0 || d->batch <= 0)
+        return false;
+    if (d->input_kind != RNN_INPUT_TOKENS && d->input_kind != RNN_INPUT_DENSE) return false;
+    if (d->act != RNN_ACT_SIGMOID && d->act != RNN_ACT_TANH) return false;
+    if (d->loss_kind != RNN_LOSS_SOFTMAX_CE && d->loss_kind != RNN_LOSS_LINEAR_MSE) return false;
+    if (d->flags & ~(RNN_FLAG_ACCUMULATE | RNN_FLAG_SYNC | RNN_FLAG_BPTT_RECOMPUTE |
+                     RNN_FLAG_REFERENCE_KERNELS))
+        return false;
+    const long long N = (long long)d->seq_len * d->batch;
+    // keep every row index and every N*width product the kernels form inside int32 / size_t
+    if (N > (1LL << 30)) return false;
+    if (N * (long long)d->out_dim > (1LL << 40) || N * (long long)d->hidden > (1LL << 40))
+        return false;
+    return true;
+}
+
+Sizes sizes_of(const rnn_dims* d) {
+    Sizes s;
+    s.NVin = d->in_dim; s.H = d->hidden; s.O = d->out_dim; s.T = d->seq_len; s.B = d->batch;
+    s.N = (long long)d->seq_len * d->batch;
+    s.tokens = d->input_kind == RNN_INPUT_TOKENS;
+    s.ce = d->loss_kind == RNN_LOSS_SOFTMAX_CE;
+    return s;
+}
+
+size_t max_splitk_floats(const Sizes& s) {
+    const int N = (int)s.N, H = s.H, O = s.O, D = s.NVin;
+    size_t m = 0;
+    auto take = [&](size_t v) { if (v > m) m = v; };
+    take(gemm_splitk_floats(N, O, H));   // Z = Hs V
+    take(gemm_splitk_floats(H, O, N));   // dV = Hs^T dZ
+    take(gemm_splitk_floats(N, H, O));   // G = dZ V^T
+    take(gemm_splitk_floats(H, H, N));   // dWh = Delta^T Hprev
+    if (!s.tokens) {
+        take(gemm_splitk_floats(N, H, D));  // U = X Wx^T
+        take(gemm_splitk_floats(H, D, N));  // dWx = Delta^T X
+    }
+    return m;
+}
+
+Plan make_plan(const rnn_dims* d) {
+    const Sizes s = sizes_of(d);
+    const size_t N = (size_t)s.N, H = (size_t)s.H, O = (size_t)s.O, B = (size_t)s.B;
+    Plan p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up(bytes); return o; };
+    p.Z = take(N * O * 4);
+    p.lse = take(N * 4);
+    p.rowloss = take(N * 4);
+    p.U = take(s.tokens ? 0 : N * H * 4);
+    p.G = take(N * H * 4);
+    p.Delta = take(N * H * 4);
+    p.WhT = take(H * H * 4);
+    p.hring = take(2 * B * H * 4);
+    const size_t widest = O > H ? O : H;
+    p.part = take((size_t)colsum_chunks((int)N) * widest * 4);
+    p.splitk = take(max_splitk_floats(s) * 4);
+    p.scratch = take(256);
+    p.total = off;
+    return p;
+}
+
+int check_ws(const rnn_dims* d, void* ws, size_t ws_bytes, Plan* plan) {
+    *plan = make_plan(d);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 15u) || ws_bytes < plan->total)
+        return RNN_EWORKSPACE;
+    return RNN_OK;
+}
+
+template <typename T>
+T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); }
+
+int finish(const rnn_dims* d, hipStream_t s, hipError_t e) {
+    if (e != hipSuccess) return RNN_EHIP;
+    if (d->flags & RNN_FLAG_SYNC)
+        if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
+    return RNN_OK;
+}
+
+#define RNN_TRY(expr)                      \
+    do {                                   \
+        hipError_t e_ = (expr);            \
+        if (e_ != hipSuccess) return e_;   \
+    } while (0)
+
+// ---- stages ------------------------------------------------------------------------------
+
+hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, const float* h0,
+                       float* h_all, float* h_last, void* ws, const Plan& pl, hipStream_t s) {
+    const Sizes z = sizes_of(d);
+    RecFwdArgs a{};
+    a.Wh = P->Wh; a.Wx = P->Wx; a.b = P->b;
+    a.h0 = h0; a.h_last = h_last;
+    a.H = z.H; a.T = z.T; a.B = z.B; a.act = d->act;
+    a.ring = h_all ? 0 : 1;
+    a.hist = h_all ? h_all : at<float>(ws, pl.hring);
+    if (z.tokens) {
+        a.x = static_cast<const int32_t*>(x);
+        a.U = nullptr;
+    } else {
+        // input term for every step at once: U = X Wx^T + b
+        GemmArgs g{};
+        g.A = static_cast<const float*>(x); g.B = P->Wx; g.C = at<float>(ws, pl.U);
+        g.M = (int)z.N; g.N = z.H; g.K = z.NVin;
+        g.lda = z.NVin; g.ldb = z.NVin; g.ldc = z.H;
+        g.a_t = false; g.b_t = true; g.bias_n = P->b; g.beta = 0;
+        g.splitk_ws = at<float>(ws, pl.splitk);
+        RNN_TRY(launch_gemm(g, s));
+        a.x = nullptr;
+        a.U = at<float>(ws, pl.U);
+    }
+    return launch_rec_fwd_reference(a, s);
+}
+
+hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, const void* targets,
+                    float* loss, void* ws, const Plan& pl, hipStream_t s) {
+    const Sizes z = sizes_of(d);
+    const int N = (int)z.N;
+    float* Z = at<float>(ws, pl.Z);
+    GemmArgs g{};
+    g.A = h_all + (size_t)z.B * z.H;  // rows of h_all[1:]
+    g.B = P->V; g.C = Z;
+    g.M = N; g.N = z.O; g.K = z.H;
+    g.lda = z.H; g.ldb = z.O; g.ldc = z.O;
+    g.a_t = false; g.b_t = false; g.bias_n = P->c; g.beta = 0;
+    g.splitk_ws = at<float>(ws, pl.splitk);
+    RNN_TRY(launch_gemm(g, s));
+    float* rowloss = at<float>(ws, pl.rowloss);
+    if (z.ce) {
+        RNN_TRY(launch_ce_row_stats(Z, static_cast<const int32_t*>(targets), at<float>(ws, pl.lse),
+                                    rowloss, N, z.O, s));
+        return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
+    }
+    RNN_TRY(launch_mse_row_loss(Z, static_cast<const float*>(targets), rowloss, N, z.O, s));
+    return launch_loss_reduce(rowloss, N, (float)(1.0 / ((double)N * (double)z.O)), loss, s);
+}
+
+hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const void* targets,
+                    const float* h_all, const float* dh_last, const rnn_grads* Gr, float* dh0,
+                    void* ws, const Plan& pl, hipStream_t s) {
+    const Sizes z = sizes_of(d);
+    const int N = (int)z.N, H = z.H, O = z.O;
+    const int beta = (d->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
+    float* Z = at<float>(ws, pl.Z);
+    float* part = at<float>(ws, pl.part);
+    float* splitk = at<float>(ws, pl.splitk);
+    float* G = at<float>(ws, pl.G);
+    float* Delta = at<float>(ws, pl.Delta);
+    const float* Hs = h_all + (size_t)z.B * H;  // h_t rows
+    const int chunks = colsum_chunks(N);
+
+    // logits -> d loss / d logits (in place) and dc
+    RNN_TRY(launch_dz(Z, at<float>(ws, pl.lse), z.ce ? static_cast<const int32_t*>(targets) : nullptr,
+                      z.ce ? nullptr : static_cast<const float*>(targets), part, N, O,
+                      d->loss_kind, s));
+    RNN_TRY(launch_colsum_finish(part, Gr->dc, chunks, O, beta, s));
+
+    // dV = Hs^T dZ
+    {
+        GemmArgs g{};
+        g.A = Hs; g.B = Z; g.C = Gr->dV;
+        g.M = H; g.N = O; g.K = N;
+        g.lda = H; g.ldb = O; g.ldc = O;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    // G = dZ V^T
+    {
+        GemmArgs g{};
+        g.A = Z; g.B = P->V; g.C = G;
+        g.M = N; g.N = H; g.K = O;
+        g.lda = O; g.ldb = O; g.ldc = H;
+        g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    // reverse-time loop
+    {
+        float* WhT = at<float>(ws, pl.WhT);
+        RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
+        RecBwdArgs a{};
+        a.Wh = P->Wh; a.WhT = WhT; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
+        a.Delta = Delta; a.dh0 = dh0;
+        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
+        RNN_TRY(launch_rec_bwd_reference(a, s));
+    }
+    // dWh = Delta^T Hprev  (Hprev rows = h_all[0:T])
+    {
+        GemmArgs g{};
+        g.A = Delta; g.B = h_all; g.C = Gr->dWh;
+        g.M = H; g.N = H; g.K = N;
+        g.lda = H; g.ldb = H; g.ldc = H;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    // db = column sums of Delta
+    RNN_TRY(launch_colsum_partial(Delta, part, N, H, s));
+    RNN_TRY(launch_colsum_finish(part, Gr->db, chunks, H, beta, s));
+    // dWx
+    if (z.tokens) {
+        RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta, s));
+    } else {
+        GemmArgs g{};
+        g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;
+        g.M = H; g.N = z.NVin; g.K = N;
+        g.lda = H; g.ldb = z.NVin; g.ldc = z.NVin;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    return hipSuccess;
+}
+
+bool params_ok(const rnn_params* P) {
+    return P && P->Wx && P->Wh && P->b && P->V && P->c && !misaligned(P->Wx) && !misaligned(P->Wh) &&
+           !misaligned(P->b) && !misaligned(P->V) && !misaligned(P->c);
+}
+
+bool reference_supported(const rnn_dims* d) { return d->hidden <= 8192; }
+
+}  // namespace
+
+extern "C" {
+
+int rnn_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
+    if (!dims_valid(dims) || !bytes) return RNN_EINVAL;
+    *bytes = make_plan(dims).total;
+    return RNN_OK;
+}
+
+int rnn_forward(const rnn_dims* dims, const rnn_params* params, const void* x, const float* h0,
+                float* h_all, float* h_last, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+    if (!dims_valid(dims) || !params_ok(params) || !x || (!h_all && !h_last)) return RNN_EINVAL;
+    if (misaligned(x) || misaligned(h0) || misaligned(h_all) || misaligned(h_last)) return RNN_EINVAL;
+    if (!reference_supported(dims)) return RNN_EUNSUPPORTED;
+    Plan pl;
+    const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return finish(dims, s, run_forward(dims, params, x, h0, h_all, h_last, workspace, pl, s));
+}
+
+int rnn_loss(const rnn_dims* dims, const rnn_params* params, const float* h_all, const void* targets,
+             float* loss, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!dims_valid(dims) || !params_ok(params) || !h_all || !targets || !loss) return RNN_EINVAL;
+    if (misaligned(h_all) || misaligned(targets)) return RNN_EINVAL;
+    Plan pl;
+    const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return finish(dims, s, run_loss(dims, params, h_all, targets, loss, workspace, pl, s));
+}
+
+int rnn_bptt(const rnn_dims* dims, const rnn_params* params, const void* x, const void* targets,
+             const float* h_all, const float* dh_last, const rnn_grads* grads, float* dh0,
+             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!dims_valid(dims) || !params_ok(params) || !x || !targets || !h_all || !grads)
+        return RNN_EINVAL;
+    if (!grads->dWx || !grads->dWh || !grads->db || !grads->dV || !grads->dc) return RNN_EINVAL;
+    if (misaligned(x) || misaligned(targets) || misaligned(h_all) || misaligned(dh_last) ||
+        misaligned(dh0) || misaligned(grads->dWx) || misaligned(grads->dWh) ||
+        misaligned(grads->db) || misaligned(grads->dV) || misaligned(grads->dc))
+        return RNN_EINVAL;
+    if (!reference_supported(dims)) return RNN_EUNSUPPORTED;
+    Plan pl;
+    const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (dims->flags & RNN_FLAG_BPTT_RECOMPUTE) {
+        // recompute logits and row statistics; the scalar loss goes to workspace scratch
+        hipError_t e = run_loss(dims, params, h_all, targets, at<float>(workspace, pl.scratch),
+                                workspace, pl, s);
+        if (e != hipSuccess) return RNN_EHIP;
+    }
+    return finish(dims, s, run_bptt(dims, params, x, targets, h_all, dh_last, grads, dh0, workspace, pl, s));
+}
+
+int rnn_check_tokens(const void* ids, int64_t n, int32_t limit, int32_t* bad_count, void* hip_stream) {
+    if (!ids || !bad_count || n < 0 || limit <= 0) return RNN_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return launch_check_tokens(static_cast<const int32_t*>(ids), n, limit, bad_count, s) == hipSuccess
+               ? RNN_OK : RNN_EHIP;
+}
+
+const char* rnn_strerror(int code) {
+    switch (code) {
+        case RNN_OK: return "ok";
+        case RNN_EINVAL: return "invalid argument (size, enum, flag, alignment or NULL required pointer)";
+        case RNN_EWORKSPACE: return "workspace missing, misaligned or too small (see rnn_workspace_bytes)";
+        case RNN_EUNSUPPORTED: return "no kernel for this shape in this build";
+        case RNN_EHIP: return "HIP launch or synchronisation failed";
+        default: return "unknown error code";
+    }
+}
+
+const char* rnn_recurrence_variant(const rnn_dims* dims) {
+    if (!dims_valid(dims)) return "invalid";
+    return "reference";
+}
+
+}  // extern "C"

@@ -1,0 +1,322 @@
+// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32), used for every product that
+// the path batches over time outside the loop (the paper's Scan property 8: per-step
+// vector-matrix products become one matrix-matrix product): the output projection Z = H V + c,
+// its two backward products dV = H^T dZ and G = dZ V^T, the recurrent weight gradient
+// dWh = Delta^T H_prev, and the dense-input projections.
+//
+// Tiling: a 256-thread workgroup (4 wavefronts as 2x2) owns a BM x BN tile of C; each
+// wavefront owns (BM/2) x (BN/2) as 32x32 MFMA blocks held in accumulation registers.
+// K advances in slabs of 16 through two LDS buffers: the next slab is fetched from global
+// memory into registers while the current one feeds the MFMAs, then parked in the other
+// buffer (one barrier per slab).  LDS keeps both operands K-major ([k][row]) so the MFMA
+// operand fetch of a wavefront (lane -> row = lane%32, k = lane/32) reads 32 consecutive
+// words per half-wave.
+#include "common.hpp"
+#include "internal.hpp"
+
+namespace rnn {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;
+constexpr int PAD = 4;
+constexpr int NT = 256;
+
+struct GemmParams {
+    const float* A;
+    const float* B;
+    float* C;          // final output, or split-K partials [splits][M][N]
+    const float* bias_n;
+    int M, N, K;
+    int lda, ldb, ldc;
+    int kchunk;        // K range per blockIdx.z (multiple of BK)
+    int beta;
+    int splits;
+    int tiles_m, tiles_n;
+};
+
+// One operand tile of R rows (R = BM or BN) by BK columns of K, fetched into registers.
+// KCONTIG: element (r,k) lives at src[r*ld + k]   (A not transposed, or B given as [N,K])
+// else   : element (r,k) lives at src[k*ld + r]   (A given as [K,M], or B given as [K,N])
+template <int R, bool KCONTIG, bool VEC>
+struct TileLoader {
+    static constexpr int NV4 = R * BK / 4 / NT;  // float4 per thread
+    float4 v[NV4];
+
+    __device__ __forceinline__ void load(const float* __restrict__ src, int ld, int r0, int k0,
+                                         int rlim, int klim, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            int r, k;
+            if (KCONTIG) {
+                r = tid / 4 + (NT / 4) * i;
+                k = (tid % 4) * 4;
+            } else {
+                constexpr int Q = R / 4;  // float4 per k-row
+                const int idx = tid + NT * i;
+                k = idx / Q;
+                r = (idx % Q) * 4;
+            }
+            const int gr = r0 + r, gk = k0 + k;
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (KCONTIG) {
+                if (gr < rlim) {
+                    const float* p = src + (size_t)gr * ld + gk;
+                    if (VEC && gk + 3 < klim) {
+                        t = *reinterpret_cast<const float4*>(p);
+                    } else {
+                        if (gk + 0 < klim) t.x = p[0];
+                        if (gk + 1 < klim) t.y = p[1];
+                        if (gk + 2 < klim) t.z = p[2];
+                        if (gk + 3 < klim) t.w = p[3];
+                    }
+                }
+            } else {
+                if (gk < klim) {
+                    const float* p = src + (size_t)gk * ld + gr;
+                    if (VEC && gr + 3 < rlim) {
+                        t = *reinterpret_cast<const float4*>(p);
+                    } else {
+                        if (gr + 0 < rlim) t.x = p[0];
+                        if (gr + 1 < rlim) t.y = p[1];
+                        if (gr + 2 < rlim) t.z = p[2];
+                        if (gr + 3 < rlim) t.w = p[3];
+                    }
+                }
+            }
+            v[i] = t;
+        }
+    }
+
+    // LDS tile layout: S[k][r], row stride R + PAD
+    __device__ __forceinline__ void store(float* __restrict__ S, int tid) const {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            if (KCONTIG) {
+                const int r = tid / 4 + (NT / 4) * i;
+                const int k = (tid % 4) * 4;
+                S[(k + 0) * (R + PAD) + r] = v[i].x;
+                S[(k + 1) * (R + PAD) + r] = v[i].y;
+                S[(k + 2) * (R + PAD) + r] = v[i].z;
+                S[(k + 3) * (R + PAD) + r] = v[i].w;
+            } else {
+                constexpr int Q = R / 4;
+                const int idx = tid + NT * i;
+                const int k = idx / Q;
+                const int r = (idx % Q) * 4;
+                *reinterpret_cast<float4*>(&S[k * (R + PAD) + r]) = v[i];
+            }
+        }
+    }
+};
+
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (round-robin
+// dispatch over 8 dies, each with its own L2), so give every XCD a contiguous band of
+// tiles, and inside a band walk down M within a narrow group of N tiles so that the
+// workgroups resident together share operand slabs in that die's L2.
+__device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int total = tiles_m * tiles_n;
+    int id = bid;
+    const int per = total / 8;
+    if (per > 0 && bid < per * 8) id = (bid % 8) * per + bid / 8;
+    constexpr int GROUP_N = 4;
+    const int group = id / (GROUP_N * tiles_m);
+    const int first_n = group * GROUP_N;
+    const int gsz = min(GROUP_N, tiles_n - first_n);
+    const int in_group = id - group * GROUP_N * tiles_m;
+    tn = first_n + in_group % gsz;
+    tm = in_group / gsz;
+}
+
+template <int BM, int BN, bool AT, bool BT, bool VEC>
+__global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
+    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA blocks per wavefront, per dim
+    __shared__ __attribute__((aligned(16))) float As[2][BK * (BM + PAD)];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK * (BN + PAD)];
+
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wm = wave / 2, wn = wave % 2;
+
+    int tile_m, tile_n;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int kbeg = blockIdx.z * p.kchunk;
+    const int kend = min(p.K, kbeg + p.kchunk);
+    const int nk = (kend - kbeg + BK - 1) / BK;
+
+    TileLoader<BM, !AT, VEC> la;
+    TileLoader<BN, BT, VEC> lb;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    if (nk > 0) {
+        la.load(p.A, p.lda, m0, kbeg, p.M, kend, tid);
+        lb.load(p.B, p.ldb, n0, kbeg, p.N, kend, tid);
+        la.store(As[0], tid);
+        lb.store(Bs[0], tid);
+    }
+    __syncthreads();
+
+    const int arow = wm * (BM / 2) + lane % 32;
+    const int brow = wn * (BN / 2) + lane % 32;
+    const int ksub = lane / 32;
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) {
+            la.load(p.A, p.lda, m0, kbeg + (kt + 1) * BK, p.M, kend, tid);
+            lb.load(p.B, p.ldb, n0, kbeg + (kt + 1) * BK, p.N, kend, tid);
+        }
+        const float* as = As[cur];
+        const float* bs = Bs[cur];
+#pragma unroll
+        for (int kk = 0; kk < BK / 2; ++kk) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + ksub) * (BM + PAD) + arow + 32 * i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + ksub) * (BN + PAD) + brow + 32 * j];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            la.store(As[cur ^ 1], tid);
+            lb.store(Bs[cur ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    // Accumulator layout of the 32x32 block: lane -> column lane%32; register e -> row
+    // 8*(e/4) + 4*(lane/32) + e%4.
+    float* Cout = p.C + (p.splits > 1 ? (size_t)blockIdx.z * p.M * p.ldc : 0);
+    const bool final_out = p.splits == 1;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * (BN / 2) + 32 * j + lane % 32;
+            if (col >= p.N) continue;
+            const float bias = (final_out && p.bias_n) ? p.bias_n[col] : 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * (BM / 2) + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+                if (row < p.M) {
+                    float* dst = Cout + (size_t)row * p.ldc + col;
+                    float v = acc[i][j][e] + bias;
+                    if (final_out && p.beta) v += *dst;
+                    *dst = v;
+                }
+            }
+        }
+}
+
+// C[m,n] = (beta ? C : 0) + sum_s part[s][m][n] + bias[n], fixed summation order
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
+                                                            float* __restrict__ C,
+                                                            const float* __restrict__ bias, int M,
+                                                            int N, int ldc, int splits, int beta) {
+    const size_t total = (size_t)M * N;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(idx / N), n = (int)(idx % N);
+        float s = 0.f;
+        for (int k = 0; k < splits; ++k) s += part[(size_t)k * total + idx];
+        if (bias) s += bias[n];
+        float* dst = C + (size_t)m * ldc + n;
+        if (beta) s += *dst;
+        *dst = s;
+    }
+}
+
+constexpr int BM_ = 128, BN_ = 128;
+
+struct SplitPlan {
+    int splits, kchunk;
+};
+
+SplitPlan plan_split(int M, int N, int K) {
+    const int tiles = ((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_);
+    int splits = 1;
+    if (tiles < 256 && K > 512) {
+        const int by_k = (K + 255) / 256;          // at least 256 of K per split
+        const int by_fill = (1024 + tiles - 1) / tiles;  // aim at ~4 workgroups per CU
+        splits = by_k < by_fill ? by_k : by_fill;
+        if (splits < 1) splits = 1;
+    }
+    int kchunk = (K + splits - 1) / splits;
+    kchunk = (kchunk + BK - 1) / BK * BK;
+    if (kchunk < BK) kchunk = BK;
+    splits = (K + kchunk - 1) / kchunk;
+    if (splits < 1) splits = 1;
+    return {splits, kchunk};
+}
+
+template <bool AT, bool BT, bool VEC>
+hipError_t launch_variant(const GemmParams& p, hipStream_t s) {
+    dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
+    hipLaunchKernelGGL((gemm_f32_kernel<BM_, BN_, AT, BT, VEC>), grid, dim3(NT), 0, s, p);
+    return hipGetLastError();
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+size_t gemm_splitk_floats(int M, int N, int K) {
+    const SplitPlan sp = plan_split(M, N, K);
+    return sp.splits > 1 ? (size_t)sp.splits * M * N : 0;
+}
+
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+    const SplitPlan sp = plan_split(g.M, g.N, g.K);
+    if (sp.splits > 1 && !g.splitk_ws) return hipErrorInvalidValue;
+
+    GemmParams p;
+    p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
+    p.M = g.M; p.N = g.N; p.K = g.K;
+    p.lda = g.lda; p.ldb = g.ldb;
+    p.kchunk = sp.kchunk; p.beta = g.beta; p.splits = sp.splits;
+    p.tiles_m = (g.M + BM_ - 1) / BM_;
+    p.tiles_n = (g.N + BN_ - 1) / BN_;
+    if (sp.splits > 1) { p.C = g.splitk_ws; p.ldc = g.N; } else { p.C = g.C; p.ldc = g.ldc; }
+
+    // float4 global loads need 16-byte aligned bases, leading dimensions that are multiples
+    // of 4, and split boundaries that keep every 4-group inside the valid range (kchunk is a
+    // multiple of 16).  The loaders check the per-element limits themselves.
+    const bool vec = aligned16(g.A) && aligned16(g.B) && g.lda % 4 == 0 && g.ldb % 4 == 0;
+
+    hipError_t e;
+#define RNN_GEMM_DISPATCH(AT, BT)                                         \
+    e = vec ? launch_variant<AT, BT, true>(p, s) : launch_variant<AT, BT, false>(p, s)
+    if (!g.a_t && !g.b_t) RNN_GEMM_DISPATCH(false, false);
+    else if (g.a_t && !g.b_t) RNN_GEMM_DISPATCH(true, false);
+    else if (!g.a_t && g.b_t) RNN_GEMM_DISPATCH(false, true);
+    else RNN_GEMM_DISPATCH(true, true);
+#undef RNN_GEMM_DISPATCH
+    if (e != hipSuccess) return e;
+
+    if (sp.splits > 1) {
+        const size_t total = (size_t)g.M * g.N;
+        int blocks = (int)((total + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, s, g.splitk_ws, g.C,
+                           g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace rnn

@@ -1,0 +1,77 @@
+// Host-side declarations of the kernel launchers behind the C ABI (one translation unit each).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rnn {
+
+// ---------------------------------------------------------------------------------------
+// fp32 MFMA GEMM:  C[M,N] = (beta ? C : 0) + op(A) op(B) + bias_n[col]
+//   a_t == false : A stored [M,K] (lda >= K)      a_t == true : A stored [K,M] (lda >= M)
+//   b_t == false : B stored [K,N] (ldb >= N)      b_t == true : B stored [N,K] (ldb >= K)
+// splitk_ws must hold gemm_splitk_floats(M,N,K) floats (0 => not needed).
+struct GemmArgs {
+    const float* A;
+    const float* B;
+    float* C;
+    int M, N, K;
+    int lda, ldb, ldc;
+    bool a_t, b_t;
+    const float* bias_n;  // nullable, length N
+    int beta;             // 0 overwrite, 1 accumulate
+    float* splitk_ws;     // nullable when gemm_splitk_floats == 0
+};
+size_t gemm_splitk_floats(int M, int N, int K);
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// Recurrence (forward and reverse-time loops)
+struct RecFwdArgs {
+    const float* Wh;   // [H,H]
+    const float* Wx;   // token input: [NV,H]; unused for dense input
+    const float* b;    // [H]
+    const int32_t* x;  // token ids [T,B] or NULL
+    const float* U;    // dense input: precomputed Wx x_t + b, [T,B,H]; NULL for token input
+    const float* h0;   // nullable [B,H]
+    float* hist;       // [T+1,B,H], or a 2-slot ring [2,B,H] when ring != 0
+    float* h_last;     // nullable [B,H]
+    int H, T, B, act, ring;
+};
+struct RecBwdArgs {
+    const float* Wh;      // [H,H]
+    const float* WhT;     // [H,H] transposed copy (reference kernels)
+    const float* G;       // [T,B,H] output-layer contribution to d loss / d h_t
+    const float* h_all;   // [T+1,B,H]
+    const float* dh_last; // nullable [B,H]
+    float* Delta;         // [T,B,H] receives d loss / d a_t
+    float* dh0;           // nullable [B,H]
+    int H, T, B, act;
+};
+hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hipStream_t s);
+hipError_t launch_rec_fwd_reference(const RecFwdArgs& a, hipStream_t s);
+hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// Output layer element-wise / row-wise kernels
+hipError_t launch_ce_row_stats(const float* Z, const int32_t* y, float* lse, float* rowloss,
+                               int N, int O, hipStream_t s);
+hipError_t launch_mse_row_loss(const float* Z, const float* Y, float* rowloss, int N, int O,
+                               hipStream_t s);
+hipError_t launch_loss_reduce(const float* rowloss, int N, float scale, float* loss, hipStream_t s);
+// Z -> dZ in place, plus per-row-chunk column sums into part[chunks][O]
+int colsum_chunks(int N);
+hipError_t launch_dz(float* Z, const float* lse, const int32_t* y, const float* Y, float* part,
+                     int N, int O, int loss_kind, hipStream_t s);
+hipError_t launch_colsum_partial(const float* M, float* part, int N, int C, hipStream_t s);
+hipError_t launch_colsum_finish(const float* part, float* out, int chunks, int C, int beta,
+                                hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// Token-keyed gradient of the input matrix and id validation
+hipError_t launch_dwx_tokens(const int32_t* x, const float* Delta, float* dWx, int N, int NV,
+                             int H, int beta, hipStream_t s);
+hipError_t launch_check_tokens(const int32_t* ids, int64_t n, int32_t limit, int32_t* bad,
+                               hipStream_t s);
+
+}  // namespace rnn

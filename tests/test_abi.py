@@ -1,0 +1,80 @@
+"""The C-ABI library loads without a GPU, exports everything include/rnn.h declares, and
+rejects bad arguments before launching anything (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1211_5590_amd as rnn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "rnn.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(rnn_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"rnn_forward", "rnn_loss", "rnn_bptt", "rnn_workspace_bytes"} <= set(names)
+    L = ctypes.CDLL(rnn.lib_path())
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(rnn.exported_symbols()) == set(names)
+
+
+def good_dims(**kw):
+    d = dict(in_dim=64, hidden=16, out_dim=64, seq_len=32, batch=1, input_kind=0, act=0, loss_kind=0)
+    d.update(kw)
+    return rnn.Dims.of(d, kw.get("flags", 0))
+
+
+def test_workspace_bytes_grows_with_the_problem_and_rejects_bad_dims():
+    small = rnn.rnn_workspace_bytes(good_dims())
+    big = rnn.rnn_workspace_bytes(good_dims(seq_len=64))
+    assert 0 < small < big
+    for bad in (dict(hidden=0), dict(seq_len=-1), dict(act=2), dict(loss_kind=5), dict(input_kind=3),
+                dict(flags=1 << 20), dict(seq_len=1 << 20, batch=1 << 12)):
+        with pytest.raises(rnn.RnnError) as e:
+            rnn.rnn_workspace_bytes(good_dims(**bad))
+        assert e.value.code == -1
+
+
+def test_hot_calls_reject_bad_arguments_without_a_gpu():
+    d = good_dims()
+    fake = 0x1000  # never dereferenced: every check below fails before any launch
+    P = rnn.Params(fake, fake, fake, fake, fake)
+    G = rnn.Grads(fake, fake, fake, fake, fake)
+    L = rnn.lib()
+    need = rnn.rnn_workspace_bytes(d)
+    # NULL required pointers
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), None, None, fake, None, fake, need, None) == -1
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, None, None, None, fake, need, None) == -1
+    assert L.rnn_loss(ctypes.byref(d), ctypes.byref(P), fake, fake, None, fake, need, None) == -1
+    assert L.rnn_bptt(ctypes.byref(d), ctypes.byref(P), fake, fake, fake, None, None, None, fake, need, None) == -1
+    Gbad = rnn.Grads(fake, fake, None, fake, fake)
+    assert L.rnn_bptt(ctypes.byref(d), ctypes.byref(P), fake, fake, fake, None, ctypes.byref(Gbad), None, fake, need, None) == -1
+    Pbad = rnn.Params(fake, None, fake, fake, fake)
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(Pbad), fake, None, fake, None, fake, need, None) == -1
+    # misaligned pointer
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake + 4, None, fake, None, fake, need, None) == -1
+    # workspace missing / too small / misaligned
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, None, fake, None, None, need, None) == -2
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, None, fake, None, fake, need - 1, None) == -2
+    assert L.rnn_loss(ctypes.byref(d), ctypes.byref(P), fake, fake, fake, fake + 8, need, None) == -2
+    assert L.rnn_bptt(ctypes.byref(d), ctypes.byref(P), fake, fake, fake, None, ctypes.byref(G), None, fake, 16, None) == -2
+    # bad dims in a hot call
+    dbad = good_dims(hidden=-3)
+    assert L.rnn_forward(ctypes.byref(dbad), ctypes.byref(P), fake, None, fake, None, fake, need, None) == -1
+    assert L.rnn_check_tokens(None, 4, 10, fake, None) == -1
+    assert L.rnn_check_tokens(fake, 4, 0, fake, None) == -1
+
+
+def test_strerror_and_variant_names():
+    assert rnn.rnn_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(rnn.rnn_strerror(code)) > 0
+    assert rnn.rnn_recurrence_variant(good_dims()) in ("wg_resident", "grid_resident", "batch_mfma", "reference")

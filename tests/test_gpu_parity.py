@@ -1,0 +1,163 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the
+same seeded inputs.  Sizes span several tiles and ragged tails; edge cases cover T=1, B=1,
+sizes that are multiples of nothing, carried state, incoming gradients, accumulate mode,
+history-free forward and both kernel families (tuned and shape-agnostic)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1211_5590_amd as rnn
+import rnn_inputs as ri
+from gpu_harness import GRAD_NAMES, Runner, compare, grad_close, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+LM = dict(input_kind=ri.INPUT_TOKENS, act=ri.ACT_SIGMOID, loss_kind=ri.LOSS_SOFTMAX_CE)
+DENSE = dict(input_kind=ri.INPUT_DENSE, act=ri.ACT_TANH, loss_kind=ri.LOSS_LINEAR_MSE)
+
+SMALL_CASES = {
+    # name: (in_dim, hidden, out_dim, T, B, extra)
+    "lm_tiny_config": (64, 16, 64, 32, 1, dict(LM, tokens="uniform")),
+    "lm_ragged": (301, 37, 301, 7, 3, dict(LM, wdist=("normal", 0.5), bias_std=0.3)),
+    "lm_T1": (50, 20, 50, 1, 5, dict(LM, wdist=("normal", 0.5), bias_std=0.3, with_h0=True)),
+    "lm_state_and_incoming_grad": (130, 100, 130, 10, 1,
+                                   dict(LM, wdist=("normal", 0.3), bias_std=0.2, with_h0=True, with_dh_last=True)),
+    "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
+    "lm_hidden_500": (700, 500, 700, 12, 1, dict(LM, wdist=("uniform", 0.05))),
+    "lm_batched_mfma_shape": (512, 256, 512, 6, 32, dict(LM, wdist=("normal_fan", None), with_h0=True)),
+    "dense_tanh_mse": (24, 64, 24, 9, 16, dict(DENSE, wdist=("normal_fan", None), bias_std=0.2,
+                                                with_h0=True, with_dh_last=True)),
+    "dense_ragged": (13, 29, 7, 5, 3, dict(DENSE, wdist=("normal", 0.4), bias_std=0.2)),
+    "dense_T1_B1": (8, 12, 8, 1, 1, dict(DENSE, wdist=("normal", 0.4))),
+    "dense_input_ce": (10, 33, 45, 6, 4, dict(input_kind=ri.INPUT_DENSE, act=ri.ACT_SIGMOID,
+                                               loss_kind=ri.LOSS_SOFTMAX_CE, wdist=("normal", 0.4), bias_std=0.2)),
+    "tokens_tanh_mse": (40, 18, 5, 6, 2, dict(input_kind=ri.INPUT_TOKENS, act=ri.ACT_TANH,
+                                               loss_kind=ri.LOSS_LINEAR_MSE, wdist=("normal", 0.4), bias_std=0.2)),
+}
+
+
+def make(name, seed=100):
+    i, h, o, T, B, extra = SMALL_CASES[name]
+    return ri.make_case(i, h, o, T, B, seed=seed + len(name), **extra)
+
+
+@pytest.mark.parametrize("flags", [0, rnn.FLAG_REFERENCE_KERNELS], ids=["tuned", "reference"])
+@pytest.mark.parametrize("name", list(SMALL_CASES))
+def test_small_cases_match_oracle(name, flags):
+    case = make(name)
+    print(f"case={name} flags={flags}", flush=True)
+    ref = oracle.fwd_bptt(case)
+    got = run_gpu(case, flags)
+    compare(got, ref)
+    if case["input_kind"] == 0:
+        unseen = np.setdiff1d(np.arange(case["in_dim"]), np.unique(case["x"]))
+        assert np.all(got["dWx"][unseen] == 0.0)          # exact zeros for tokens that do not occur
+
+
+def test_softmax_rows_sum_to_one_and_zero_weight_closed_form():
+    case = ri.make_case(10000, 20, 10000, 4, 2, seed=5, **LM)
+    for k in ("Wx", "Wh", "b", "V", "c"):
+        case[k][...] = 0
+    got = run_gpu(case)
+    assert abs(got["loss"] - np.log(10000.0)) <= 1e-4 * np.log(10000.0)
+    counts = np.bincount(case["y"].reshape(-1), minlength=10000)
+    dc = 1.0 / 10000 - counts / 8.0
+    grad_close("dc", got["dc"], dc)
+    grad_close("dV", got["dV"], 0.5 * np.broadcast_to(dc, (20, 10000)))
+    assert np.all(got["dWx"] == 0) and np.all(got["dWh"] == 0) and np.all(got["db"] == 0)
+    # rows of softmax sum to one  <=>  rows of dZ sum to zero  <=>  sum_k dc[k] = 0 (float32 noise)
+    case = make("lm_multi_tile")
+    got = run_gpu(case)
+    assert abs(got["dc"].sum()) < 1e-5
+    assert np.max(np.abs(got["dV"].sum(1))) < 1e-5
+    np.testing.assert_allclose(got["dWx"].sum(0), got["db"], atol=1e-5)
+
+
+def test_accumulate_mode_adds_and_leaves_unseen_rows_alone():
+    case = make("lm_ragged")
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case, rnn.FLAG_ACCUMULATE)
+    for k, g in r.grads.items():
+        g.fill_(1.0)
+    r.step()
+    got = r.results()
+    for k in GRAD_NAMES:
+        grad_close(k, got[k] - 1.0, ref[k], rtol=2e-3)
+    unseen = np.setdiff1d(np.arange(case["in_dim"]), np.unique(case["x"]))
+    assert np.all(got["dWx"][unseen] == 1.0)
+
+
+def test_bptt_recompute_flag_needs_no_prior_loss_call():
+    case = make("lm_multi_tile")
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case, rnn.FLAG_BPTT_RECOMPUTE)
+    r.forward()
+    r.bptt()
+    got = r.results()
+    for k in GRAD_NAMES:
+        grad_close(k, got[k], ref[k])
+
+
+@pytest.mark.parametrize("name", ["lm_state_and_incoming_grad", "dense_tanh_mse", "lm_hidden_500"])
+def test_history_free_forward_returns_last_state(name):
+    case = make(name)
+    ref = oracle.forward(case)
+    r = Runner(case, keep_history=False)
+    r.forward()
+    torch.cuda.synchronize()
+    assert np.max(np.abs(r.h_last.cpu().numpy() - ref[-1])) <= 2e-5
+
+
+def test_results_are_bit_identical_run_to_run():
+    case = make("lm_multi_tile")
+    r = Runner(case)
+    r.step()
+    first = r.results()
+    for _ in range(5):
+        r.step()
+        again = r.results()
+        for k in GRAD_NAMES + ("h_all", "dh0"):
+            assert np.array_equal(first[k], again[k]), k
+        assert first["loss"] == again["loss"]
+
+
+def test_two_windows_chain_state_forward_and_gradient_backward():
+    full = ri.make_case(200, 48, 200, 12, 2, seed=77, wdist=("normal", 0.3), bias_std=0.1, **LM)
+    ref = oracle.fwd_bptt(full)
+    halves = []
+    for w in range(2):
+        q = dict(full); q["seq_len"] = 6
+        q["x"], q["y"] = full["x"][6 * w:6 * w + 6], full["y"][6 * w:6 * w + 6]
+        halves.append(q)
+    ra, rb = Runner(halves[0]), Runner(halves[1])
+    ra.forward(); ra.loss_()
+    rb.h0 = ra.h_last
+    rb.forward(); rb.loss_(); rb.bptt()
+    ra.dh_last = rb.dh0
+    ra.bptt()
+    ga, gb = ra.results(), rb.results()
+    assert np.max(np.abs(np.concatenate([ga["h_all"], gb["h_all"][1:]]) - ref["h_all"])) <= 2e-5
+    for k in GRAD_NAMES:
+        grad_close(k, 0.5 * (ga[k] + gb[k]), ref[k])
+    assert abs(0.5 * (ga["loss"] + gb["loss"]) - ref["loss"]) <= 1e-4 * ref["loss"]
+
+
+def test_check_tokens_counts_out_of_range_ids():
+    ids = torch.tensor([0, 5, 9, 10, -1, 3, 99], dtype=torch.int32, device="cuda")
+    bad = torch.full((1,), 123, dtype=torch.int32, device="cuda")
+    rnn.rnn_check_tokens(ids, ids.numel(), 10, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 3
+
+
+def test_calls_are_asynchronous_on_a_side_stream():
+    case = make("lm_multi_tile")
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r.forward(); r.loss_(); r.bptt()
+    side.synchronize()
+    compare(r.results(), ref)
