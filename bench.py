@@ -1,0 +1,277 @@
+#!/usr/bin/env python3
+"""Benchmark of the Elman-RNN training path (forward recurrence -> output layer + loss -> BPTT).
+
+One "step" is one pass of the whole path over one batch of synthetic input:
+  C2 (headline, the paper's benchmark shape: batch 1, vocabulary-sized input and output layers):
+     the 100000-token Zipf stream as 10000 dependent truncated-BPTT windows of 10 steps; every
+     window runs rnn_forward -> rnn_loss -> rnn_bptt with the hidden state carried, in stream
+     order, exactly as if an optimiser step sat between windows.
+  C1, C3, C4, C5: one window of the named configuration.
+Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--windows", type=int, default=None, help="override the number of C2 windows")
+    ap.add_argument("--others", default="C3,C4,C5",
+                    help="comma list of further configurations reported under 'per_config' ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
+    ap.add_argument("--reference-kernels", action="store_true")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device-resident buffers and pre-marshalled C calls of one configuration."""
+
+    def __init__(self, name, flags=0, windows=None):
+        import numpy as np
+        import torch
+        import paper_1211_5590_amd as rnn
+        import rnn_inputs as ri
+        self.rnn, self.torch, self.name = rnn, torch, name
+        over = {}
+        if windows is not None and ri.CONFIGS[name]["windows"] > 1:
+            over["windows"] = windows
+        case = ri.make_config(name, **over)
+        self.case = case
+        self.T, self.B, self.H = case["seq_len"], case["batch"], case["hidden"]
+        self.windows = case["windows"]
+        self.dims = rnn.Dims.of(case, flags)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.p = {k: dev(case[k]) for k in ("Wx", "Wh", "b", "V", "c")}
+        self.x = dev(case["x"] if case["input_kind"] == 0 else case["X"])
+        self.y = dev(case["y"] if case["loss_kind"] == 0 else case["Y"])
+        self.g = {"d" + k: torch.zeros_like(v) for k, v in self.p.items()}
+        self.h_all = torch.zeros((self.T + 1, self.B, self.H), device="cuda")
+        self.carry = torch.zeros((2, self.B, self.H), device="cuda")
+        self.loss = torch.zeros((max(self.windows, 1),), device="cuda")
+        self.ws = torch.empty(rnn.rnn_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
+        # pre-marshalled arguments: plain ints and ctypes structs, no per-call Python objects
+        self.L = rnn.lib()
+        self.P = rnn.Params(*[self.p[k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])
+        self.G = rnn.Grads(*[self.g["d" + k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])
+        self.x_stride = self.x[0].numel() * self.x.element_size() * self.T
+        self.y_stride = self.y[0].numel() * self.y.element_size() * self.T
+        self.tokens_per_step = self.T * self.B * self.windows
+        self.timesteps_per_step = self.T * self.windows
+
+    def step(self, stream):
+        """All windows of the stream, in order, on `stream` (a raw hipStream_t as int)."""
+        L, d, P, G = self.L, ctypes.byref(self.dims), ctypes.byref(self.P), ctypes.byref(self.G)
+        ws, wb = self.ws.data_ptr(), self.ws.numel()
+        h_all = self.h_all.data_ptr()
+        xb, yb, lb = self.x.data_ptr(), self.y.data_ptr(), self.loss.data_ptr()
+        c0, c1 = self.carry[0].data_ptr(), self.carry[1].data_ptr()
+        fwd, loss, bptt = L.rnn_forward, L.rnn_loss, L.rnn_bptt
+        for w in range(self.windows):
+            x, y = xb + w * self.x_stride, yb + w * self.y_stride
+            h0 = None if w == 0 else (c1 if w & 1 else c0)
+            hl = c0 if w & 1 else c1
+            rc = fwd(d, P, x, h0, h_all, hl, ws, wb, stream)
+            rc |= loss(d, P, h_all, y, lb + 4 * w, ws, wb, stream)
+            rc |= bptt(d, P, x, y, h_all, None, G, None, ws, wb, stream)
+            if rc:
+                raise RuntimeError(f"rnn call failed in window {w}: {rc}")
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        stream = torch.cuda.current_stream().cuda_stream
+        for _ in range(warmup):
+            self.step(stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.step(stream)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, e0.elapsed_time(e1) / 1e3
+
+    def profile(self, steps=1):
+        """Per-kernel HIP-event timing of `steps` further steps (events perturb throughput a
+        little, so this runs after the timed region, on the same stream)."""
+        stream = self.torch.cuda.current_stream().cuda_stream
+        self.torch.cuda.synchronize()
+        self.rnn.rnn_profile_begin(1 << 20)
+        for _ in range(steps):
+            self.step(stream)
+        prof = self.rnn.rnn_profile_end()
+        return {k: dict(launches=c, total_ms=ms, avg_us=1e3 * ms / c) for k, (c, ms) in prof.items()}
+
+
+def algorithmic_work(kernel, c):
+    """Algorithmic (bytes, flops) of ONE launch of `kernel` for configuration dict `c`: what the
+    method must move/compute, not what the implementation happens to move."""
+    N, H, O, I = c["seq_len"] * c["batch"], c["hidden"], c["out_dim"], c["in_dim"]
+    T, B = c["seq_len"], c["batch"]
+    f = 4
+    table = {
+        "gemm_nn": (f * (N * H + H * O + N * O), 2.0 * N * H * O),           # Z = Hs V + c
+        "gemm_tn": (f * (N * H + N * O + H * O), 2.0 * N * H * O),           # dV = Hs^T dZ (largest TN)
+        "gemm_nt": (f * (N * O + H * O + N * H), 2.0 * N * H * O),           # G = dZ V^T
+        "ce_row_stats": (f * N * O, 3.0 * N * O),
+        "dz": (2 * f * N * O, 3.0 * N * O),
+        "dwx_tokens": (f * (N * H + I * H), 1.0 * N * H),
+        "rec_fwd": (f * (H * H + 2 * N * H), 2.0 * N * H * H),               # Wh once + in/out rows
+        "rec_bwd": (f * (H * H + 3 * N * H), 2.0 * N * H * H),
+        "skinny_logits": (f * (H * O + N * O + N * H), 2.0 * N * H * O),
+        "skinny_back": (f * (2 * H * O + N * O + I * H), 4.0 * N * H * O),
+        "skinny_reverse": (f * (H * H + 3 * N * H), 2.0 * N * H * H),
+    }
+    return table.get(kernel)
+
+
+def roofline_of(prof, case):
+    """Roofline entry of the dominant kernel (largest total time in the profile pass)."""
+    if not prof:
+        return None
+    name = max(prof, key=lambda k: prof[k]["total_ms"])
+    work = algorithmic_work(name, case)
+    if work is None:
+        return dict(kernel=name, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
+                    traffic=None, avg_us=prof[name]["avg_us"])
+    nbytes, flops = work
+    sec = prof[name]["avg_us"] * 1e-6
+    ai = flops / nbytes
+    if ai >= FP32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and name.startswith("gemm"):
+        ach = flops / sec / 1e12
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=None, avg_us=prof[name]["avg_us"])
+    ach = nbytes / sec / 1e9
+    return dict(kernel=name, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
+                frac=ach / HBM_PEAK_GBS, traffic=None, avg_us=prof[name]["avg_us"],
+                algorithmic_bytes=nbytes)
+
+
+def cpu_baseline(name, budget_s):
+    """The oracle as it stands, timed on the host cores over a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    import rnn_inputs as ri
+    cores = oracle.num_threads()
+    cfg = ri.CONFIGS[name]
+    if cfg["windows"] > 1:
+        case = ri.make_config(name, windows=64)
+        t0 = time.perf_counter()
+        h, done = None, 0
+        while done < 64 and (done < 4 or time.perf_counter() - t0 < budget_s):
+            r = oracle.fwd_bptt(ri.window(case, done), h0=h)
+            h = r["h_all"][-1]
+            done += 1
+        dt = time.perf_counter() - t0
+        tokens = done * cfg["seq_len"] * cfg["batch"]
+        sample = f"first {done} windows of the stream (state carried), forward+loss+BPTT each"
+    else:
+        # shrink T (and B) until the estimated double-precision work fits the budget
+        T, B = cfg["seq_len"], cfg["batch"]
+        H, O, I = cfg["hidden"], cfg["out_dim"], cfg["in_dim"]
+        per_row = 6.0 * H * O + 6.0 * H * H + (0 if cfg["input_kind"] == 0 else 4.0 * H * I)
+        rate = 1.0e9 * cores                     # conservative plain-loop estimate, flop/s
+        rows = max(1, int(budget_s * rate / per_row))
+        while T * B > rows and T > 1:
+            T = max(1, T // 2)
+        while T * B > rows and B > 1:
+            B = max(1, B // 2)
+        case = ri.make_config(name, seq_len=T, batch=B)
+        t0 = time.perf_counter()
+        oracle.fwd_bptt(case)
+        dt = time.perf_counter() - t0
+        tokens = T * B
+        sample = f"one window with seq_len {T}, batch {B} (same widths), forward+loss+BPTT"
+    return dict(value=tokens / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample,
+                seconds=dt)
+
+
+def describe(c):
+    return dict(in_dim=c["in_dim"], hidden=c["hidden"], out_dim=c["out_dim"], seq_len=c["seq_len"],
+                batch=c["batch"], windows=c["windows"],
+                input="token ids" if c["input_kind"] == 0 else "dense",
+                act="sigmoid" if c["act"] == 0 else "tanh",
+                loss="softmax-CE" if c["loss_kind"] == 0 else "linear-MSE")
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              f"--gpus {a.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    import paper_1211_5590_amd as rnn
+    flags = rnn.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
+    default_steps = {"C1": 200, "C2": 3, "C3": 50, "C4": 10, "C5": 5}
+    default_warm = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
+    steps = a.steps if a.steps is not None else default_steps[a.workload]
+    warm = a.warmup if a.warmup is not None else default_warm[a.workload]
+
+    wl = Workload(a.workload, flags, a.windows)
+    wall, gpu_s = wl.time_steps(steps, warm)
+    prof = wl.profile(1)
+    out = {
+        "metric": "fwd+BPTT tokens/sec",
+        "value": wl.tokens_per_step * steps / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": 1e3 * wall / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": dict(workload=a.workload, **describe(wl.case),
+                       recurrence_variant=rnn.rnn_recurrence_variant(wl.dims)),
+        "timesteps_per_s": wl.timesteps_per_step * steps / wall,
+        "gpu_event_ms_per_step": 1e3 * gpu_s / steps,
+        "roofline": roofline_of(prof, wl.case),
+        "kernels": {k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3),
+                            total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
+    }
+    del wl
+    torch.cuda.empty_cache()
+
+    per = {}
+    for name in [s for s in a.others.split(",") if s and s != a.workload]:
+        w = Workload(name, flags)
+        wall_o, _ = w.time_steps(default_steps[name], default_warm[name])
+        pr = w.profile(1)
+        per[name] = dict(tokens_per_s=w.tokens_per_step * default_steps[name] / wall_o,
+                         timesteps_per_s=w.timesteps_per_step * default_steps[name] / wall_o,
+                         ms_per_step=1e3 * wall_o / default_steps[name],
+                         recurrence_variant=rnn.rnn_recurrence_variant(w.dims),
+                         roofline=roofline_of(pr, w.case),
+                         kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
+                                  for k, v in sorted(pr.items())})
+        del w
+        torch.cuda.empty_cache()
+    if per:
+        out["per_config"] = per
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -33,7 +33,9 @@
  *   - Call order on one stream with one workspace: rnn_forward -> rnn_loss -> rnn_bptt.
  *     rnn_loss leaves the logits and row statistics in the workspace for rnn_bptt; with
  *     RNN_FLAG_BPTT_RECOMPUTE rnn_bptt recomputes them itself and needs no prior rnn_loss.
- *   - Pointers must be 16-byte aligned.  No size needs to be a multiple of anything.
+ *   - Parameter, gradient, state and workspace pointers must be 16-byte aligned; inputs x,
+ *     targets and the loss scalar only 4-byte aligned (so a window may start anywhere in a
+ *     longer stream).  No size needs to be a multiple of anything.
  *   - Return value: RNN_OK or a negative RNN_E* code; nothing is printed, nothing aborts.
  *     When a call returns an error nothing has been enqueued, except RNN_EHIP which reports
  *     a failed launch.
@@ -138,6 +140,20 @@ const char *rnn_strerror(int code);
 /* Name of the recurrence kernel family the dispatcher picks for these sizes (host-only; for
  * reports and tests): "wg_resident", "grid_resident", "batch_mfma" or "reference". */
 const char *rnn_recurrence_variant(const rnn_dims *dims);
+
+/*
+ * Per-kernel timing for roofline reports (the paper keeps a synchronous mode "for profiling
+ * execution time of the different GPU kernels"; this is the asynchronous equivalent).  Between
+ * rnn_profile_begin and rnn_profile_end every kernel the library launches is bracketed by two
+ * HIP events on its stream (at most max_launches launches are recorded, later ones are not).
+ * rnn_profile_end waits for the recorded events and fills counts[k] / total_ms[k] (host arrays
+ * of n_kernels >= rnn_profile_kernel_count() entries) per kernel id.  Host state, single
+ * thread; the events add a little stream overhead, so time throughput with profiling off.
+ */
+int rnn_profile_begin(int max_launches);
+int rnn_profile_end(int n_kernels, int64_t *counts, double *total_ms);
+int rnn_profile_kernel_count(void);
+const char *rnn_profile_kernel_name(int kernel_id);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,8 @@ LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
 FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 4, 8
 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
-           "rnn_strerror", "rnn_recurrence_variant")
+           "rnn_strerror", "rnn_recurrence_variant", "rnn_profile_begin", "rnn_profile_end",
+           "rnn_profile_kernel_count", "rnn_profile_kernel_name")
 
 
 class RnnError(RuntimeError):
@@ -71,6 +72,12 @@ def lib():
         L.rnn_strerror.restype = ctypes.c_char_p
         L.rnn_recurrence_variant.argtypes = [ctypes.POINTER(Dims)]
         L.rnn_recurrence_variant.restype = ctypes.c_char_p
+        L.rnn_profile_begin.argtypes = [ctypes.c_int]
+        L.rnn_profile_end.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
+        L.rnn_profile_kernel_name.argtypes = [ctypes.c_int]
+        L.rnn_profile_kernel_name.restype = ctypes.c_char_p
+        for name in ("rnn_profile_begin", "rnn_profile_end", "rnn_profile_kernel_count"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -172,3 +179,18 @@ def rnn_check_tokens(ids, n, limit, bad_count, stream=None, check=True):
     if check:
         _check(rc)
     return rc
+
+
+def rnn_profile_begin(max_launches: int = 1 << 16) -> None:
+    _check(lib().rnn_profile_begin(int(max_launches)))
+
+
+def rnn_profile_end() -> dict:
+    """{kernel name: (launch count, total ms)} for the kernels launched since rnn_profile_begin."""
+    L = lib()
+    n = L.rnn_profile_kernel_count()
+    counts = (ctypes.c_int64 * n)()
+    ms = (ctypes.c_double * n)()
+    _check(L.rnn_profile_end(n, counts, ms))
+    return {L.rnn_profile_kernel_name(k).decode(): (int(counts[k]), float(ms[k]))
+            for k in range(n) if counts[k] > 0}

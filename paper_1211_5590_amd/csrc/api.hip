@@ -98,6 +98,9 @@ template <typename T>
 T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
 bool misaligned(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); }
+// ids, targets and the loss scalar are only ever accessed as 4-byte words (windows of a stream
+// start at arbitrary element offsets)
+bool misaligned4(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 3u); }
 
 int finish(const rnn_dims* d, hipStream_t s, hipError_t e) {
     if (e != hipSuccess) return RNN_EHIP;
@@ -259,7 +262,7 @@ int rnn_forward(const rnn_dims* dims, const rnn_params* params, const void* x, c
                 float* h_all, float* h_last, void* workspace, size_t workspace_bytes,
                 void* hip_stream) {
     if (!dims_valid(dims) || !params_ok(params) || !x || (!h_all && !h_last)) return RNN_EINVAL;
-    if (misaligned(x) || misaligned(h0) || misaligned(h_all) || misaligned(h_last)) return RNN_EINVAL;
+    if (misaligned4(x) || misaligned(h0) || misaligned(h_all) || misaligned(h_last)) return RNN_EINVAL;
     if (!reference_supported(dims)) return RNN_EUNSUPPORTED;
     Plan pl;
     const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
@@ -271,7 +274,7 @@ int rnn_forward(const rnn_dims* dims, const rnn_params* params, const void* x, c
 int rnn_loss(const rnn_dims* dims, const rnn_params* params, const float* h_all, const void* targets,
              float* loss, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!dims_valid(dims) || !params_ok(params) || !h_all || !targets || !loss) return RNN_EINVAL;
-    if (misaligned(h_all) || misaligned(targets)) return RNN_EINVAL;
+    if (misaligned(h_all) || misaligned4(targets) || misaligned4(loss)) return RNN_EINVAL;
     Plan pl;
     const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
     if (rc != RNN_OK) return rc;
@@ -285,7 +288,7 @@ int rnn_bptt(const rnn_dims* dims, const rnn_params* params, const void* x, cons
     if (!dims_valid(dims) || !params_ok(params) || !x || !targets || !h_all || !grads)
         return RNN_EINVAL;
     if (!grads->dWx || !grads->dWh || !grads->db || !grads->dV || !grads->dc) return RNN_EINVAL;
-    if (misaligned(x) || misaligned(targets) || misaligned(h_all) || misaligned(dh_last) ||
+    if (misaligned4(x) || misaligned4(targets) || misaligned(h_all) || misaligned(dh_last) ||
         misaligned(dh0) || misaligned(grads->dWx) || misaligned(grads->dWh) ||
         misaligned(grads->db) || misaligned(grads->dV) || misaligned(grads->dc))
         return RNN_EINVAL;

@@ -13,6 +13,7 @@
 // words per half-wave.
 #include "common.hpp"
 #include "internal.hpp"
+#include "prof.hpp"
 
 namespace rnn {
 namespace {
@@ -266,6 +267,7 @@ SplitPlan plan_split(int M, int N, int K) {
 template <bool AT, bool BT, bool VEC>
 hipError_t launch_variant(const GemmParams& p, hipStream_t s) {
     dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
+    ProfileScope ps(AT ? (BT ? K_GEMM_TT : K_GEMM_TN) : (BT ? K_GEMM_NT : K_GEMM_NN), s);
     hipLaunchKernelGGL((gemm_f32_kernel<BM_, BN_, AT, BT, VEC>), grid, dim3(NT), 0, s, p);
     return hipGetLastError();
 }
@@ -312,6 +314,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
         const size_t total = (size_t)g.M * g.N;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
+        ProfileScope ps(K_SPLITK_REDUCE, s);
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, s, g.splitk_ws, g.C,
                            g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
         e = hipGetLastError();

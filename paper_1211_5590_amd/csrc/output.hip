@@ -4,6 +4,7 @@
 // column-sum / scalar reductions.  All of these are HBM-bandwidth bound.
 #include "common.hpp"
 #include "internal.hpp"
+#include "prof.hpp"
 
 namespace rnn {
 namespace {
@@ -139,17 +140,20 @@ int colsum_chunks(int N) { const int r = rows_per_chunk(N); return (N + r - 1) /
 
 hipError_t launch_ce_row_stats(const float* Z, const int32_t* y, float* lse, float* rowloss, int N,
                                int O, hipStream_t s) {
+    ProfileScope ps(K_CE_ROW_STATS, s);
     hipLaunchKernelGGL(ce_row_stats_kernel, dim3(N), dim3(256), 0, s, Z, y, lse, rowloss, O);
     return hipGetLastError();
 }
 
 hipError_t launch_mse_row_loss(const float* Z, const float* Y, float* rowloss, int N, int O,
                                hipStream_t s) {
+    ProfileScope ps(K_MSE_ROW_LOSS, s);
     hipLaunchKernelGGL(mse_row_loss_kernel, dim3(N), dim3(256), 0, s, Z, Y, rowloss, O);
     return hipGetLastError();
 }
 
 hipError_t launch_loss_reduce(const float* rowloss, int N, float scale, float* loss, hipStream_t s) {
+    ProfileScope ps(K_LOSS_REDUCE, s);
     hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, rowloss, N, scale, loss);
     return hipGetLastError();
 }
@@ -157,6 +161,7 @@ hipError_t launch_loss_reduce(const float* rowloss, int N, float scale, float* l
 hipError_t launch_dz(float* Z, const float* lse, const int32_t* y, const float* Y, float* part,
                      int N, int O, int loss_kind, hipStream_t s) {
     dim3 grid((O + 255) / 256, colsum_chunks(N));
+    ProfileScope ps(K_DZ, s);
     if (loss_kind == 0) {
         const float scale = 1.0f / (float)N;
         hipLaunchKernelGGL(dz_kernel<0>, grid, dim3(256), 0, s, Z, lse, y, Y, part, N, O, scale);
@@ -169,12 +174,14 @@ hipError_t launch_dz(float* Z, const float* lse, const int32_t* y, const float* 
 
 hipError_t launch_colsum_partial(const float* M, float* part, int N, int C, hipStream_t s) {
     dim3 grid((C + 255) / 256, colsum_chunks(N));
+    ProfileScope ps(K_COLSUM_PARTIAL, s);
     hipLaunchKernelGGL(colsum_partial_kernel, grid, dim3(256), 0, s, M, part, N, C);
     return hipGetLastError();
 }
 
 hipError_t launch_colsum_finish(const float* part, float* out, int chunks, int C, int beta,
                                 hipStream_t s) {
+    ProfileScope ps(K_COLSUM_FINISH, s);
     hipLaunchKernelGGL(colsum_finish_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, out,
                        chunks, C, beta);
     return hipGetLastError();

@@ -1,0 +1,29 @@
+// Optional per-kernel timing with HIP events, for roofline reports.  Off by default; when off a
+// launch costs one predictable branch.  When on, every kernel launch of the library is
+// bracketed by two events recorded on the launch stream; rnn_profile_read synchronises on
+// them and returns per-kernel launch counts and total milliseconds.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace rnn {
+
+enum KernelId : int {
+    K_GEMM_NN = 0, K_GEMM_TN, K_GEMM_NT, K_GEMM_TT, K_SPLITK_REDUCE, K_TRANSPOSE,
+    K_REC_FWD, K_REC_BWD, K_CE_ROW_STATS, K_MSE_ROW_LOSS, K_LOSS_REDUCE, K_DZ,
+    K_COLSUM_PARTIAL, K_COLSUM_FINISH, K_DWX_TOKENS, K_CHECK_TOKENS,
+    K_SKINNY_LOGITS, K_SKINNY_BACK, K_SKINNY_REVERSE, K_MISC,
+    K_COUNT
+};
+
+extern int g_profile_on;
+void profile_before(int kid, hipStream_t s);
+void profile_after(int kid, hipStream_t s);
+
+struct ProfileScope {
+    int kid;
+    hipStream_t s;
+    ProfileScope(int k, hipStream_t st) : kid(k), s(st) { if (g_profile_on) profile_before(kid, s); }
+    ~ProfileScope() { if (g_profile_on) profile_after(kid, s); }
+};
+
+}  // namespace rnn

@@ -5,6 +5,7 @@
 // the A/B partner in tests (RNN_FLAG_REFERENCE_KERNELS).
 #include "common.hpp"
 #include "internal.hpp"
+#include "prof.hpp"
 
 namespace rnn {
 namespace {
@@ -110,6 +111,7 @@ __global__ __launch_bounds__(256) void rec_bwd_ref_kernel(RecBwdArgs a) {
 
 hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hipStream_t s) {
     dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+    ProfileScope ps(K_TRANSPOSE, s);
     hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, src, dst, rows, cols);
     return hipGetLastError();
 }
@@ -117,6 +119,7 @@ hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hi
 hipError_t launch_rec_fwd_reference(const RecFwdArgs& a, hipStream_t s) {
     const size_t smem = 2 * sizeof(float) * (size_t)a.H;
     if (smem > 64 * 1024) return hipErrorInvalidValue;
+    ProfileScope ps(K_REC_FWD, s);
     if (a.act == 0)
         hipLaunchKernelGGL(rec_fwd_ref_kernel<0>, dim3(a.B), dim3(256), smem, s, a);
     else
@@ -127,6 +130,7 @@ hipError_t launch_rec_fwd_reference(const RecFwdArgs& a, hipStream_t s) {
 hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s) {
     const size_t smem = 2 * sizeof(float) * (size_t)a.H;
     if (smem > 64 * 1024) return hipErrorInvalidValue;
+    ProfileScope ps(K_REC_BWD, s);
     if (a.act == 0)
         hipLaunchKernelGGL(rec_bwd_ref_kernel<0>, dim3(a.B), dim3(256), smem, s, a);
     else

@@ -5,6 +5,7 @@
 // writes the zero rows of tokens that do not occur.
 #include "common.hpp"
 #include "internal.hpp"
+#include "prof.hpp"
 
 namespace rnn {
 namespace {
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(256) void check_tokens_kernel(const int32_t* __rest
 hipError_t launch_dwx_tokens(const int32_t* x, const float* Delta, float* dWx, int N, int NV, int H,
                              int beta, hipStream_t s) {
     const int rows_per_block = 256 / kWave;
+    ProfileScope ps(K_DWX_TOKENS, s);
     hipLaunchKernelGGL(dwx_tokens_kernel, dim3((NV + rows_per_block - 1) / rows_per_block),
                        dim3(256), 0, s, x, Delta, dWx, N, NV, H, beta);
     return hipGetLastError();
@@ -82,6 +84,7 @@ hipError_t launch_dwx_tokens(const int32_t* x, const float* Delta, float* dWx, i
 
 hipError_t launch_check_tokens(const int32_t* ids, int64_t n, int32_t limit, int32_t* bad,
                                hipStream_t s) {
+    ProfileScope ps(K_CHECK_TOKENS, s);
     hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(64), 0, s, bad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

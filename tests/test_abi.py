@@ -60,7 +60,8 @@ def test_hot_calls_reject_bad_arguments_without_a_gpu():
     Pbad = rnn.Params(fake, None, fake, fake, fake)
     assert L.rnn_forward(ctypes.byref(d), ctypes.byref(Pbad), fake, None, fake, None, fake, need, None) == -1
     # misaligned pointer
-    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake + 4, None, fake, None, fake, need, None) == -1
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake + 2, None, fake, None, fake, need, None) == -1
+    assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, fake + 4, fake, None, fake, need, None) == -1
     # workspace missing / too small / misaligned
     assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, None, fake, None, None, need, None) == -2
     assert L.rnn_forward(ctypes.byref(d), ctypes.byref(P), fake, None, fake, None, fake, need - 1, None) == -2
