@@ -134,11 +134,25 @@ int rnn_bptt(const rnn_dims *dims, const rnn_params *params, const void *x,
 int rnn_check_tokens(const void *ids, int64_t n, int32_t limit, int32_t *bad_count,
                      void *hip_stream);
 
+/*
+ * Device status word kept in the workspace.  The multi-workgroup persistent loops wait for
+ * each other with a bounded spin; if a wait ever expires (which needs the GPU to be shared in a
+ * way that defeats the cooperative launch) the kernel sets the word to 1, every workgroup
+ * leaves, and the results of that call are invalid.  rnn_workspace_init clears the word
+ * (asynchronous; call it once after allocating a workspace if the word will be read);
+ * rnn_workspace_status copies it to *status_host and synchronises the stream.
+ */
+int rnn_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+int rnn_workspace_status(const rnn_dims *dims, const void *workspace, size_t workspace_bytes,
+                         void *hip_stream, int32_t *status_host);
+
 /* Static description of an error code (host string, never NULL). */
 const char *rnn_strerror(int code);
 
 /* Name of the recurrence kernel family the dispatcher picks for these sizes (host-only; for
- * reports and tests): "wg_resident", "grid_resident", "batch_mfma" or "reference". */
+ * reports and tests): "wg_resident" (one workgroup per sequence, weights in LDS),
+ * "grid_resident" (several cooperating workgroups per sequence), "batch_mfma" or "reference". */
 const char *rnn_recurrence_variant(const rnn_dims *dims);
 
 /*

@@ -18,7 +18,8 @@ FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 
 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
            "rnn_strerror", "rnn_recurrence_variant", "rnn_profile_begin", "rnn_profile_end",
-           "rnn_profile_kernel_count", "rnn_profile_kernel_name")
+           "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
+           "rnn_workspace_status")
 
 
 class RnnError(RuntimeError):
@@ -72,6 +73,10 @@ def lib():
         L.rnn_strerror.restype = ctypes.c_char_p
         L.rnn_recurrence_variant.argtypes = [ctypes.POINTER(Dims)]
         L.rnn_recurrence_variant.restype = ctypes.c_char_p
+        L.rnn_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
+        L.rnn_workspace_status.argtypes = [ctypes.POINTER(Dims), vp, sz, vp, ctypes.POINTER(ctypes.c_int32)]
+        L.rnn_workspace_init.restype = ctypes.c_int
+        L.rnn_workspace_status.restype = ctypes.c_int
         L.rnn_profile_begin.argtypes = [ctypes.c_int]
         L.rnn_profile_end.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         L.rnn_profile_kernel_name.argtypes = [ctypes.c_int]
@@ -194,3 +199,15 @@ def rnn_profile_end() -> dict:
     _check(L.rnn_profile_end(n, counts, ms))
     return {L.rnn_profile_kernel_name(k).decode(): (int(counts[k]), float(ms[k]))
             for k in range(n) if counts[k] > 0}
+
+
+def rnn_workspace_init(dims, workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(lib().rnn_workspace_init(ctypes.byref(dims), wp, wb, _stream(stream)))
+
+
+def rnn_workspace_status(dims, workspace, stream=None) -> int:
+    wp, wb = _ws(workspace)
+    out = ctypes.c_int32(-1)
+    _check(lib().rnn_workspace_status(ctypes.byref(dims), wp, wb, _stream(stream), ctypes.byref(out)))
+    return int(out.value)

@@ -14,7 +14,16 @@ constexpr size_t kAlign = 256;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
-    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, total;  // byte offsets
+    // byte offsets into the workspace
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, pm, ps, zy, gpart,
+        total;
+};
+
+// Which kernel family serves these sizes.
+struct Variant {
+    bool resident;        // resident-weight persistent loops (else shape-agnostic loops)
+    bool skinny;          // column-strip output layer + fused tail of the reverse loop
+    RecResPlan fwd, bwd;  // plans of the two loops when resident
 };
 
 struct Sizes {
@@ -65,6 +74,22 @@ size_t max_splitk_floats(const Sizes& s) {
     return m;
 }
 
+Variant pick_variant(const rnn_dims* d) {
+    const Sizes s = sizes_of(d);
+    Variant v{};
+    if (d->flags & RNN_FLAG_REFERENCE_KERNELS) return v;
+    v.resident = rec_resident_plan(s.H, s.B, s.T, false, &v.fwd);
+    if (!v.resident) return v;
+    v.bwd = v.fwd;
+    RecResPlan fused;
+    if (s.tokens && s.ce && s.B == 1 && skinny_supported((int)s.N, s.H, s.O) &&
+        rec_resident_plan(s.H, s.B, s.T, true, &fused)) {
+        v.skinny = true;
+        v.bwd = fused;
+    }
+    return v;
+}
+
 Plan make_plan(const rnn_dims* d) {
     const Sizes s = sizes_of(d);
     const size_t N = (size_t)s.N, H = (size_t)s.H, O = (size_t)s.O, B = (size_t)s.B;
@@ -83,6 +108,13 @@ Plan make_plan(const rnn_dims* d) {
     p.part = take((size_t)colsum_chunks((int)N) * widest * 4);
     p.splitk = take(max_splitk_floats(s) * 4);
     p.scratch = take(256);
+    p.flags = take(4096);
+    const size_t strips = (size_t)skinny_strips(s.O);
+    const bool small = N <= 32;
+    p.pm = take(small ? N * strips * 4 : 0);
+    p.ps = take(small ? N * strips * 4 : 0);
+    p.zy = take(small ? N * 4 : 0);
+    p.gpart = take(small ? strips * N * H * 4 : 0);
     p.total = off;
     return p;
 }
@@ -141,13 +173,39 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         a.x = nullptr;
         a.U = at<float>(ws, pl.U);
     }
+    const Variant v = pick_variant(d);
+    if (v.resident) {
+        RecResArgs r{};
+        r.Wh = P->Wh; r.H = z.H; r.T = z.T; r.B = z.B; r.act = d->act;
+        r.flags = at<int32_t>(ws, pl.flags); r.status = at<int32_t>(ws, pl.scratch) + 1;
+        r.Wx = P->Wx; r.b = P->b; r.x = a.x; r.U = a.U; r.h0 = h0;
+        r.hist = a.hist; r.h_last = h_last; r.ring = a.ring;
+        return launch_rec_resident(r, v.fwd, false, s);
+    }
     return launch_rec_fwd_reference(a, s);
+}
+
+SkinnyArgs skinny_args(const rnn_dims* d, const rnn_params* P, const float* h_all, const void* targets,
+                       void* ws, const Plan& pl) {
+    const Sizes z = sizes_of(d);
+    SkinnyArgs k{};
+    k.Hs = h_all + (size_t)z.B * z.H; k.V = P->V; k.c = P->c;
+    k.y = static_cast<const int32_t*>(targets);
+    k.Z = at<float>(ws, pl.Z); k.pm = at<float>(ws, pl.pm); k.ps = at<float>(ws, pl.ps);
+    k.zy = at<float>(ws, pl.zy); k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart);
+    k.H = z.H; k.O = z.O; k.N = (int)z.N; k.NV = z.NVin;
+    return k;
 }
 
 hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, const void* targets,
                     float* loss, void* ws, const Plan& pl, hipStream_t s) {
     const Sizes z = sizes_of(d);
     const int N = (int)z.N;
+    if (pick_variant(d).skinny) {
+        const SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
+        RNN_TRY(launch_skinny_logits(k, s));
+        return launch_skinny_loss(k, loss, s);
+    }
     float* Z = at<float>(ws, pl.Z);
     GemmArgs g{};
     g.A = h_all + (size_t)z.B * z.H;  // rows of h_all[1:]
@@ -180,6 +238,25 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
     float* Delta = at<float>(ws, pl.Delta);
     const float* Hs = h_all + (size_t)z.B * H;  // h_t rows
     const int chunks = colsum_chunks(N);
+    const Variant v = pick_variant(d);
+
+    RecResArgs r{};
+    r.Wh = P->Wh; r.H = H; r.T = z.T; r.B = z.B; r.act = d->act;
+    r.flags = at<int32_t>(ws, pl.flags); r.status = at<int32_t>(ws, pl.scratch) + 1;
+    r.G = G; r.h_all = h_all; r.dh_last = dh_last; r.Delta = Delta; r.dh0 = dh0;
+
+    if (v.skinny) {
+        // column-strip output layer, then one kernel for the reverse loop and the small
+        // weight gradients (dWh, db, touched rows of dWx)
+        SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
+        k.dV = Gr->dV; k.dc = Gr->dc; k.beta = beta;
+        k.dWx_zero = beta ? nullptr : Gr->dWx;
+        RNN_TRY(launch_skinny_back(k, s));
+        r.gpart = k.gpart; r.gstrips = skinny_strips(O); r.Gw = G;
+        r.fuse_post = 1; r.x = static_cast<const int32_t*>(x);
+        r.dWh = Gr->dWh; r.db = Gr->db; r.dWx = Gr->dWx; r.beta = beta;
+        return launch_rec_resident(r, v.bwd, true, s);
+    }
 
     // logits -> d loss / d logits (in place) and dc
     RNN_TRY(launch_dz(Z, at<float>(ws, pl.lse), z.ce ? static_cast<const int32_t*>(targets) : nullptr,
@@ -206,7 +283,9 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         RNN_TRY(launch_gemm(g, s));
     }
     // reverse-time loop
-    {
+    if (v.resident) {
+        RNN_TRY(launch_rec_resident(r, v.bwd, true, s));
+    } else {
         float* WhT = at<float>(ws, pl.WhT);
         RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
         RecBwdArgs a{};
@@ -326,7 +405,31 @@ const char* rnn_strerror(int code) {
 
 const char* rnn_recurrence_variant(const rnn_dims* dims) {
     if (!dims_valid(dims)) return "invalid";
-    return "reference";
+    const Variant v = pick_variant(dims);
+    if (!v.resident) return "reference";
+    return v.fwd.P == 1 ? "wg_resident" : "grid_resident";
+}
+
+int rnn_workspace_status(const rnn_dims* dims, const void* workspace, size_t workspace_bytes,
+                         void* hip_stream, int32_t* status_host) {
+    if (!dims_valid(dims) || !status_host) return RNN_EINVAL;
+    Plan pl;
+    const int rc = check_ws(dims, const_cast<void*>(workspace), workspace_bytes, &pl);
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(status_host, at<int32_t>(const_cast<void*>(workspace), pl.scratch) + 1, 4,
+                       hipMemcpyDeviceToHost, s) != hipSuccess)
+        return RNN_EHIP;
+    return hipStreamSynchronize(s) == hipSuccess ? RNN_OK : RNN_EHIP;
+}
+
+int rnn_workspace_init(const rnn_dims* dims, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!dims_valid(dims)) return RNN_EINVAL;
+    Plan pl;
+    const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return launch_zero_words(at<int32_t>(workspace, pl.scratch), 64, s) == hipSuccess ? RNN_OK : RNN_EHIP;
 }
 
 }  // extern "C"

@@ -48,6 +48,29 @@ struct RecBwdArgs {
     float* dh0;           // nullable [B,H]
     int H, T, B, act;
 };
+// Resident-weight persistent loops (recurrence.hip).  One struct serves both directions.
+struct RecResArgs {
+    const float* Wh;
+    int H, T, B, act;
+    int P, R, L, ldw, w_floats;  // filled from the plan by the launcher
+    int32_t* flags;              // [B][P] step counters in the workspace (P > 1)
+    int32_t* status;             // device status word: set to 1 when a bounded wait expires
+    int spin_limit;              // <= 0: default
+    // forward
+    const float* Wx; const float* b; const int32_t* x; const float* U; const float* h0;
+    float* hist; float* h_last; int ring;
+    // reverse
+    const float* G; const float* h_all; const float* dh_last; float* Delta; float* dh0;
+    // fused weight gradients of a short single sequence (reverse, P == 1, B == 1)
+    int fuse_post; float* dWh; float* db; float* dWx; int beta;
+    // per-strip partial G [strips][T*B][H] to be summed into Gw before the loop (nullable)
+    const float* gpart; int gstrips; float* Gw;
+};
+struct RecResPlan { int P, R, L, ldw, w_floats; size_t smem; };
+bool rec_resident_plan(int H, int B, int T, bool fuse_post, RecResPlan* out);
+hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s);
+
+hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s);
 hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hipStream_t s);
 hipError_t launch_rec_fwd_reference(const RecFwdArgs& a, hipStream_t s);
 hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s);
@@ -66,6 +89,28 @@ hipError_t launch_dz(float* Z, const float* lse, const int32_t* y, const float* 
 hipError_t launch_colsum_partial(const float* M, float* part, int N, int C, hipStream_t s);
 hipError_t launch_colsum_finish(const float* part, float* out, int chunks, int C, int beta,
                                 hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// Output layer of a short single sequence (skinny.hip): column-strip kernels, N <= 32 rows
+struct SkinnyArgs {
+    const float* Hs;      // [N,H] rows h_t
+    const float* V;       // [H,O]
+    const float* c;       // [O]
+    const int32_t* y;     // [N]
+    float* Z;             // [N,O] logits (workspace)
+    float* pm; float* ps; // [N][strips] strip max / sum exp
+    float* zy;            // [N] target logits
+    float* lse;           // [N]
+    float* dV; float* dc; // gradients
+    float* gpart;         // [strips][N][H]
+    float* dWx_zero;      // token-gradient matrix to zero fill, or NULL
+    int H, O, N, NV, beta;
+};
+int skinny_strips(int O);
+bool skinny_supported(int N, int H, int O);
+hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);
+hipError_t launch_skinny_loss(const SkinnyArgs& a, float* loss, hipStream_t s);
+hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // Token-keyed gradient of the input matrix and id validation

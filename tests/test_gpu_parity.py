@@ -23,6 +23,11 @@ SMALL_CASES = {
     "lm_T1": (50, 20, 50, 1, 5, dict(LM, wdist=("normal", 0.5), bias_std=0.3, with_h0=True)),
     "lm_state_and_incoming_grad": (130, 100, 130, 10, 1,
                                    dict(LM, wdist=("normal", 0.3), bias_std=0.2, with_h0=True, with_dh_last=True)),
+    "lm_window_rnnlm_shape": (10000, 100, 10000, 10, 1, dict(LM, wdist=("normal", 0.1), with_h0=True)),
+    "lm_short_ragged_single": (301, 37, 301, 7, 1, dict(LM, wdist=("normal", 0.5), bias_std=0.3,
+                                                       with_h0=True, with_dh_last=True)),
+    "lm_short_two_passes": (700, 60, 700, 29, 1, dict(LM, wdist=("normal", 0.3), bias_std=0.2)),
+    "lm_small_batch_resident": (300, 132, 300, 9, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1, with_h0=True)),
     "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_hidden_500": (700, 500, 700, 12, 1, dict(LM, wdist=("uniform", 0.05))),
     "lm_batched_mfma_shape": (512, 256, 512, 6, 32, dict(LM, wdist=("normal_fan", None), with_h0=True)),
@@ -141,6 +146,32 @@ def test_two_windows_chain_state_forward_and_gradient_backward():
     for k in GRAD_NAMES:
         grad_close(k, 0.5 * (ga[k] + gb[k]), ref[k])
     assert abs(0.5 * (ga["loss"] + gb["loss"]) - ref["loss"]) <= 1e-4 * ref["loss"]
+
+
+def test_variant_names_and_clean_status_word():
+    expect = {"lm_window_rnnlm_shape": "wg_resident", "lm_hidden_500": "grid_resident",
+              "lm_batched_mfma_shape": "reference"}
+    for name, want in expect.items():
+        case = make(name)
+        r = Runner(case)
+        assert rnn.rnn_recurrence_variant(r.dims) == want
+        rnn.rnn_workspace_init(r.dims, r.ws)
+        r.step()
+        assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
+
+
+def test_accumulate_mode_on_the_short_sequence_path():
+    case = make("lm_short_ragged_single")
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case, rnn.FLAG_ACCUMULATE)
+    for k, g in r.grads.items():
+        g.fill_(1.0)
+    r.step()
+    got = r.results()
+    for k in GRAD_NAMES:
+        grad_close(k, got[k] - 1.0, ref[k], rtol=2e-3)
+    unseen = np.setdiff1d(np.arange(case["in_dim"]), np.unique(case["x"]))
+    assert np.all(got["dWx"][unseen] == 1.0)
 
 
 def test_check_tokens_counts_out_of_range_ids():
