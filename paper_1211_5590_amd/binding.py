@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "librnn_mi355x.so")
+# RNN_MI355X_LIB selects another build of the same library (e.g. an instrumented one)
+_LIB_PATH = os.environ.get("RNN_MI355X_LIB") or os.path.join(_PKG, "librnn_mi355x.so")
 
 INPUT_TOKENS, INPUT_DENSE = 0, 1
 ACT_SIGMOID, ACT_TANH = 0, 1

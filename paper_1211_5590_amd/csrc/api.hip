@@ -78,12 +78,12 @@ Variant pick_variant(const rnn_dims* d) {
     const Sizes s = sizes_of(d);
     Variant v{};
     if (d->flags & RNN_FLAG_REFERENCE_KERNELS) return v;
-    v.resident = rec_resident_plan(s.H, s.B, s.T, false, &v.fwd);
+    v.resident = rec_resident_plan(s.H, s.B, s.T, false, false, &v.fwd) &&
+                 rec_resident_plan(s.H, s.B, s.T, true, false, &v.bwd);
     if (!v.resident) return v;
-    v.bwd = v.fwd;
     RecResPlan fused;
     if (s.tokens && s.ce && s.B == 1 && skinny_supported((int)s.N, s.H, s.O) &&
-        rec_resident_plan(s.H, s.B, s.T, true, &fused)) {
+        rec_resident_plan(s.H, s.B, s.T, true, true, &fused)) {
         v.skinny = true;
         v.bwd = fused;
     }

@@ -7,65 +7,244 @@
 // (reverse) with the previous state, a fused bias/activation (or activation-derivative)
 // epilogue, and the store of the new state.
 //
-// Work split: P workgroups per batch row, each holding R = ceil(H/P) rows of the matrix in LDS
-// for the whole launch (loaded once).  A row's dot product is shared by L lanes that read the
-// row and the state vector as float4 and combine with wavefront shuffles.  P = 1: the state
-// lives in LDS and a step costs one workgroup barrier.  P > 1: every workgroup stores its
-// slice of the new state to global memory, publishes a per-workgroup step counter with
-// release semantics, waits (bounded) for the other P-1 counters, and re-reads the full vector.
-// The launch is cooperative, so all P*B workgroups are co-resident; a wait that exceeds its
-// spin limit sets the status word and makes the whole workgroup leave, so every wavefront
-// terminates whatever happens.
+// Work split: P workgroups per batch row, each owning R = ceil(H/P) outputs and holding the
+// matching slice of Wh in LDS for the whole launch (loaded once, always with coalesced global
+// reads and conflict-free LDS writes):
+//   forward  slice = rows of Wh, LDS layout [row][k]; a row's dot product is shared by L lanes
+//            that read row and state as float4 and combine with wavefront shuffles;
+//   reverse  slice = columns of Wh, LDS layout [k][column] (the natural layout again, so no
+//            transposed copy is ever made); a column is owned by one lane per k-range, the
+//            Q k-ranges combine through LDS.
+// P = 1: the state lives in LDS and a step costs workgroup barriers that order LDS only.
+// P > 1: every workgroup stores its slice of the new state to global memory, publishes a
+// per-workgroup step counter with release semantics, waits (bounded) for the other P-1
+// counters, and re-reads the full vector.  The launch is cooperative, so all P*B workgroups
+// are co-resident; a wait that exceeds its spin limit sets the status word and makes the
+// whole workgroup leave, so every wavefront terminates whatever happens.
+//
+// Global-memory latency is kept off the dependent chain: everything the setup needs is
+// requested before anything is waited for, and the per-step epilogue operands (forward: the
+// hoisted input term; reverse: G_t and h_t) are fetched a chunk of steps ahead.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
+
+#include <type_traits>
 
 namespace rnn {
 namespace {
 
 constexpr int kThreads = 512;
+constexpr int kFuseMaxT = 32;  // longest sequence the fused weight-gradient tail accepts
+constexpr int TC = 8;          // steps per prefetch chunk of the epilogue operands
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int NL = 20;         // independent global loads in flight per thread during setup
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store, which would put a DRAM round trip on each step of the
+// time loop; the steps exchange the state vector through LDS, so LDS ordering is enough.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// i / d for 0 <= i < 2^24 and d > 0 without the integer-division expansion
+__device__ __forceinline__ int fast_div(int i, int d, float inv) {
+    int qn = (int)((float)i * inv);
+    const int r = i - qn * d;
+    if (r < 0) --qn;
+    else if (r >= d) ++qn;
+    return qn;
+}
+
+// Sum over groups of L adjacent lanes (L a power of two), result in every lane of the group.
+// The first four stages use DPP lane permutations (a few cycles each, no LDS round trip):
+// quad_perm xor 1, quad_perm xor 2, mirror within 8 lanes, mirror within 16 lanes; mirrors
+// work because after the earlier stages all lanes of a half already hold the same sum.
+__device__ __forceinline__ float group_sum(float v, int L) {
+    if (L >= 2) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+    if (L >= 4) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
+    if (L >= 8) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
+    if (L >= 16) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
+    if (L >= 32) v += __shfl_xor(v, 16, kWave);
+    if (L >= 64) v += __shfl_xor(v, 32, kWave);
+    return v;
+}
 
 template <int ACT, bool BWD>
 __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ int s_abort;
+    __shared__ int s_ids[kFuseMaxT];
+    __shared__ int s_first[kFuseMaxT];
     const int H = a.H, P = a.P, R = a.R, ldw = a.ldw, L = a.L, B = a.B, T = a.T;
     const int p = blockIdx.x, bb = blockIdx.y;
     const int tid = threadIdx.x;
     const int r0 = p * R;
     const int rows = max(0, min(R, H - r0));
     const int H4 = (H + 3) / 4, Hp = H4 * 4;
-    float* W = smem;                       // [R][ldw], zero padded
-    float* vbuf = smem + a.w_floats;       // [2][Hp], zero padded
-    const int q = tid % L, grp = tid / L, ngrp = kThreads / L;
+    const float invH = 1.0f / (float)H;
+    // LDS carve-up
+    float* W = smem;                          // forward [R][ldw]; reverse [H][ldw]
+    float* vbuf = smem + a.w_floats;          // [2][Hp], zero padded
+    float* stash = vbuf + 2 * Hp;             // [2][TC][2][R] epilogue operands, private per lane
+    float* Gl = stash + 2 * TC * 2 * R;       // fused tail only: [T][H] G, delta, h_{t-1}
+    float* Dl = Gl + T * H;
+    float* Hl = Dl + T * H;
 
+    // thread roles
+    const int q = tid % L;                               // which share of the k range
+    const int own = tid / L;                             // which output of the slice
+    const bool lead = (q == 0) && own < rows;            // finishes output r0 + own
+    const int nsteps = BWD ? T - 1 : T;
+
+    // Epilogue operands of TC consecutive steps starting at s0, for output j (lead lanes only).
+    // Branch-free and in two phases (all ids first, then all rows), so that the requests
+    // overlap instead of waiting for each other; steps past the end re-read the last one.
+    const float bj = (!BWD && lead && !a.U) ? a.b[r0 + own] : 0.f;
+    auto fetch_chunk = [&](int s0, int j, float (&x0)[TC], float (&x1)[TC]) {
+        if (!BWD) {
+            if (a.U) {
+#pragma unroll
+                for (int u = 0; u < TC; ++u) {
+                    const size_t n = (size_t)min(s0 + u, nsteps - 1) * B + bb;
+                    x0[u] = a.U[n * H + j];
+                }
+            } else {
+                int ids[TC];
+#pragma unroll
+                for (int u = 0; u < TC; ++u) ids[u] = a.x[(size_t)min(s0 + u, nsteps - 1) * B + bb];
+#pragma unroll
+                for (int u = 0; u < TC; ++u) x0[u] = a.Wx[(size_t)ids[u] * H + j];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < TC; ++u) {
+                const int t = T - 2 - min(s0 + u, nsteps - 1);
+                x1[u] = a.h_all[((size_t)(t + 1) * B + bb) * H + j];
+                if (!a.gpart) x0[u] = a.G[((size_t)t * B + bb) * H + j];
+            }
+        }
+    };
+
+    // ---- requests first: epilogue operands of the first chunk ------------------------------
+    float nx0[TC], nx1[TC];
+#pragma unroll
+    for (int u = 0; u < TC; ++u) { nx0[u] = 0.f; nx1[u] = 0.f; }
+    if (lead && nsteps > 0) fetch_chunk(0, r0 + own, nx0, nx1);
     if (tid == 0) s_abort = 0;
-    for (int i = tid; i < R * ldw; i += kThreads) W[i] = 0.f;
-    for (int i = tid; i < 2 * Hp; i += kThreads) vbuf[i] = 0.f;
-    __syncthreads();
-    if (!BWD) {
-        for (int i = tid; i < rows * H; i += kThreads) {
-            const int r = i / H, k = i - r * H;
-            W[r * ldw + k] = a.Wh[(size_t)(r0 + r) * H + k];
-        }
-    } else {  // rows of Wh^T: W[r][k] = Wh[k][r0 + r]
-        for (int i = tid; i < rows * H; i += kThreads) {
-            const int k = i / rows, r = i - k * rows;
-            W[r * ldw + k] = a.Wh[(size_t)k * H + r0 + r];
-        }
-    }
+    if (BWD && a.fuse_post && tid < T) s_ids[tid] = a.x[tid];
 
-    // sum of the per-strip partial G (fixed strip order) when the output layer ran column-split
-    if (BWD && a.gpart) {
-        const int n = T * B * H;
-        for (int e = tid; e < n; e += kThreads) {
-            float g = 0.f;
-#pragma unroll 8
-            for (int sidx = 0; sidx < a.gstrips; ++sidx) g += a.gpart[(size_t)sidx * n + e];
-            a.Gw[e] = g;
+    // ---- weight slice into LDS ----------------------------------------------------------------
+    if (!BWD) {
+        const int n = rows * H;  // rows r0.. are one contiguous block of Wh
+        for (int base = tid; base < n; base += NL * kThreads) {
+            float t[NL];
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                t[u] = i < n ? a.Wh[(size_t)r0 * H + i] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                if (i < n) {
+                    const int r = fast_div(i, H, invH);
+                    W[r * ldw + (i - r * H)] = t[u];
+                }
+            }
         }
-        __syncthreads();
+        const int padw = ldw - H;
+        if (padw > 0)
+            for (int i = tid; i < rows * padw; i += kThreads) {  // zero the row padding
+                const int r = i / padw;
+                W[r * ldw + H + (i - r * padw)] = 0.f;
+            }
+    } else {
+        const int n = H * rows;  // W[k][c] = Wh[k][r0 + c]; for P == 1 a plain copy
+        const float invR = 1.0f / (float)(rows > 0 ? rows : 1);
+        for (int base = tid; base < n; base += NL * kThreads) {
+            float t[NL];
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                t[u] = 0.f;
+                if (i < n) {
+                    const int k = fast_div(i, rows, invR);
+                    t[u] = a.Wh[(size_t)k * H + r0 + (i - k * rows)];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                if (i < n) {
+                    const int k = fast_div(i, rows, invR);
+                    W[k * ldw + (i - k * rows)] = t[u];
+                }
+            }
+        }
     }
+    for (int i = tid; i < 2 * Hp; i += kThreads) vbuf[i] = 0.f;
+
+    // ---- fused tail inputs (short single sequence): h_{t-1} rows and the summed partial G -----
+    if (BWD && a.fuse_post) {
+        const int n = T * H;
+        for (int base = tid; base < n; base += 8 * kThreads) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (base + u * kThreads < n) ? a.h_all[base + u * kThreads] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + u * kThreads < n) Hl[base + u * kThreads] = t[u];
+        }
+    }
+    if (BWD && a.gpart) {
+        // Sum of the per-strip partial G.  The order is fixed (a strip range per lane, then a
+        // shuffle tree), so results repeat bit for bit.  Only used with the fused tail (B == 1).
+        const int n = T * H;
+        if ((n & 3) == 0) {
+            const int n4 = n / 4;
+            int parts = 1;
+            while (parts < 8 && parts * 2 * n4 <= kThreads) parts *= 2;
+            const int part_id = tid % parts;
+            const int per = (a.gstrips + parts - 1) / parts;
+            const int sb = part_id * per, se = min(a.gstrips, sb + per);
+            for (int e = tid / parts; e < n4; e += kThreads / parts) {
+                float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int s0 = sb; s0 < se; s0 += 20) {
+                    float4 t[20];
+#pragma unroll
+                    for (int u = 0; u < 20; ++u)
+                        t[u] = (s0 + u < se)
+                                   ? reinterpret_cast<const float4*>(a.gpart + (size_t)(s0 + u) * n)[e]
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int u = 0; u < 20; ++u) { g.x += t[u].x; g.y += t[u].y; g.z += t[u].z; g.w += t[u].w; }
+                }
+                for (int off = 1; off < parts; off <<= 1) {
+                    g.x += __shfl_xor(g.x, off, kWave);
+                    g.y += __shfl_xor(g.y, off, kWave);
+                    g.z += __shfl_xor(g.z, off, kWave);
+                    g.w += __shfl_xor(g.w, off, kWave);
+                }
+                if (part_id == 0) reinterpret_cast<float4*>(Gl)[e] = g;
+            }
+        } else {
+            for (int e = tid; e < n; e += kThreads) {
+                float g = 0.f;
+                for (int s0 = 0; s0 < a.gstrips; s0 += 8) {
+                    float t[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        t[u] = (s0 + u < a.gstrips) ? a.gpart[(size_t)(s0 + u) * n + e] : 0.f;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) g += t[u];
+                }
+                Gl[e] = g;
+            }
+        }
+    }
+    __syncthreads();
 
     // ---- initial vector ------------------------------------------------------------------
     // forward: h_{-1} = h0 (or zeros), also stored as slot 0 of the history.
@@ -81,65 +260,105 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         const float* ht = a.h_all + ((size_t)T * B + bb) * H;
         for (int j = tid; j < H; j += kThreads) {
             const float c = a.dh_last ? a.dh_last[(size_t)bb * H + j] : 0.f;
-            const float d = (a.G[row + j] + c) * act_grad<ACT>(ht[j]);
+            const float g = a.gpart ? Gl[(T - 1) * H + j] : a.G[row + j];
+            const float d = (g + c) * act_grad<ACT>(ht[j]);
             vbuf[j] = d;
             if (j >= r0 && j < r0 + rows) a.Delta[row + j] = d;
+            if (a.fuse_post) Dl[(T - 1) * H + j] = d;
         }
     }
     __syncthreads();
 
+    // One product of the resident slice with the vector v: every lane of an output's group gets
+    // the full sum.  LDS reads are issued eight at a time before the multiply-adds, so a step
+    // pays for one or two LDS round trips instead of one per element.
+    auto slice_dot = [&](const float* v) -> float {
+        float acc0 = 0.f, acc1 = 0.f;
+        if (!BWD) {
+            const float4* w4 = reinterpret_cast<const float4*>(W + min(own, R - 1) * ldw);
+            const float4* v4 = reinterpret_cast<const float4*>(v);
+            for (int c0 = q; c0 < H4; c0 += 8 * L) {
+                float4 w[8], x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int c = c0 + u * L;
+                    const bool ok = c < H4;
+                    w[u] = ok ? w4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    x[u] = ok ? v4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; u += 2) {
+                    acc0 = fmaf(w[u].x, x[u].x, acc0);
+                    acc1 = fmaf(w[u + 1].x, x[u + 1].x, acc1);
+                    acc0 = fmaf(w[u].y, x[u].y, acc0);
+                    acc1 = fmaf(w[u + 1].y, x[u + 1].y, acc1);
+                    acc0 = fmaf(w[u].z, x[u].z, acc0);
+                    acc1 = fmaf(w[u + 1].z, x[u + 1].z, acc1);
+                    acc0 = fmaf(w[u].w, x[u].w, acc0);
+                    acc1 = fmaf(w[u + 1].w, x[u + 1].w, acc1);
+                }
+            }
+        } else {
+            // lane q of the group owns k in [q*KC, (q+1)*KC); column `own` of the slice
+            const int k0 = q * a.bKC, k1 = min(H, k0 + a.bKC);
+            const float* wc = W + min(own, R - 1);
+            for (int kb = k0; kb < k1; kb += 8) {
+                float w[8], x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool ok = kb + u < k1;
+                    w[u] = ok ? wc[(kb + u) * ldw] : 0.f;
+                    x[u] = ok ? v[kb + u] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; u += 2) {
+                    acc0 = fmaf(w[u], x[u], acc0);
+                    acc1 = fmaf(w[u + 1], x[u + 1], acc1);
+                }
+            }
+        }
+        return group_sum(acc0 + acc1, L);
+    };
+
     // Steps.  forward: s = 0..T-1 computes h_s from h_{s-1}.  reverse: s = 0..T-2 computes
     // delta_t for t = T-2-s from delta_{t+1}.
-    const int nsteps = BWD ? T - 1 : T;
     int cur = 0;
-    // first-row operands of the epilogue are fetched one step ahead (latency off the chain)
-    const bool lead = (q == 0) && grp < rows;
-    float pre0 = 0.f, pre1 = 0.f;  // fwd: input term; bwd: G_t and h_t
-    auto fetch = [&](int s, int j, float& x0, float& x1) {
-        if (!BWD) {
-            const size_t n = (size_t)s * B + bb;
-            x0 = a.U ? a.U[n * H + j] : a.Wx[(size_t)a.x[n] * H + j] + a.b[j];
-            x1 = 0.f;
-        } else {
-            const int t = T - 2 - s;
-            x0 = a.G[((size_t)t * B + bb) * H + j];
-            x1 = a.h_all[((size_t)(t + 1) * B + bb) * H + j];
-        }
-    };
-    if (lead && nsteps > 0) fetch(0, r0 + grp, pre0, pre1);
-
     for (int s = 0; s < nsteps; ++s) {
-        const float c0 = pre0, c1 = pre1;
-        if (lead && s + 1 < nsteps) fetch(s + 1, r0 + grp, pre0, pre1);
-        const float4* v4 = reinterpret_cast<const float4*>(vbuf + cur * Hp);
+        const int chunk = s / TC, su = s - chunk * TC;
+        float* st = stash + (size_t)(chunk & 1) * TC * 2 * R;
+        if (su == 0 && lead) {
+#pragma unroll
+            for (int u = 0; u < TC; ++u) {
+                st[(u * 2) * R + own] = nx0[u] + bj;
+                if (BWD) st[(u * 2 + 1) * R + own] = nx1[u];
+            }
+            if (s + TC < nsteps) fetch_chunk(s + TC, r0 + own, nx0, nx1);
+        }
+        const float* v = vbuf + cur * Hp;
         float* vnext = vbuf + (cur ^ 1) * Hp;
         const int t = BWD ? T - 2 - s : s;
         float* out_row = BWD ? a.Delta + ((size_t)t * B + bb) * H
                              : a.hist + ((size_t)(a.ring ? ((s + 1) & 1) : (s + 1)) * B + bb) * H;
-        for (int row = grp; row < rows; row += ngrp) {
-            const float4* w4 = reinterpret_cast<const float4*>(W + row * ldw);
-            float acc = 0.f;
-            for (int c = q; c < H4; c += L) {
-                const float4 w = w4[c], x = v4[c];
-                acc = fmaf(w.x, x.x, acc);
-                acc = fmaf(w.y, x.y, acc);
-                acc = fmaf(w.z, x.z, acc);
-                acc = fmaf(w.w, x.w, acc);
+        // one pass covers every output of the slice: each output has its own lane group
+        {
+            const int j = r0 + own;
+            float x0 = 0.f, x1 = 0.f;
+            if (lead) {  // operands of the epilogue, requested before the product is waited for
+                x0 = (BWD && a.gpart) ? Gl[t * H + j] : st[(su * 2) * R + own];
+                if (BWD) x1 = st[(su * 2 + 1) * R + own];
             }
-            for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-            if (q == 0) {
-                const int j = r0 + row;
-                float x0 = c0, x1 = c1;
-                if (row != grp) fetch(s, j, x0, x1);
-                const float v = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
-                out_row[j] = v;
-                vnext[j] = v;
+            const float acc = slice_dot(v);
+            if (lead) {
+                const float val = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
+                out_row[j] = val;
+                vnext[j] = val;
+                if (BWD && a.fuse_post) Dl[t * H + j] = val;
             }
         }
         if (P > 1) {
             const int step = s + 1;
             __threadfence();
-            __syncthreads();
+            lds_barrier();
             int32_t* fl = a.flags + (size_t)bb * P;
             if (tid == 0) __hip_atomic_store(fl + p, step, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
             if (tid < P) {
@@ -149,7 +368,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                     __builtin_amdgcn_s_sleep(1);
                 }
             }
-            __syncthreads();
+            lds_barrier();
             if (s_abort) {
                 if (tid == 0) atomicExch(a.status, 1);
                 return;  // uniform: the whole workgroup leaves
@@ -157,9 +376,10 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             for (int j = tid; j < H; j += kThreads) vnext[j] = out_row[j];
         }
-        __syncthreads();
+        lds_barrier();
         cur ^= 1;
     }
+    __syncthreads();
 
     const float* vfin = vbuf + cur * Hp;
     if (!BWD) {
@@ -168,68 +388,83 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         return;
     }
     if (a.dh0) {  // dh0 = Wh^T delta_0
-        const float4* v4 = reinterpret_cast<const float4*>(vfin);
-        for (int row = grp; row < rows; row += ngrp) {
-            const float4* w4 = reinterpret_cast<const float4*>(W + row * ldw);
-            float acc = 0.f;
-            for (int c = q; c < H4; c += L) {
-                const float4 w = w4[c], x = v4[c];
-                acc = fmaf(w.x, x.x, acc);
-                acc = fmaf(w.y, x.y, acc);
-                acc = fmaf(w.z, x.z, acc);
-                acc = fmaf(w.w, x.w, acc);
-            }
-            for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-            if (q == 0) a.dh0[(size_t)bb * H + r0 + row] = acc;
-        }
+        const float acc = slice_dot(vfin);
+        if (lead) a.dh0[(size_t)bb * H + r0 + own] = acc;
     }
     if (!a.fuse_post) return;
 
     // ---- fused weight gradients for a short single sequence (P == 1, B == 1) -----------------
-    // dWh = sum_t delta_t (x) h_{t-1},  db = sum_t delta_t,  dWx rows by token id.
-    __syncthreads();               // everyone is done with W and vbuf
-    float* D = smem;               // [T][H] delta rows
-    float* Hprev = smem + T * H;   // [T][H] h_{t-1} rows
-    for (int i = tid; i < T * H; i += kThreads) {
-        D[i] = a.Delta[i];
-        Hprev[i] = a.h_all[i];
-    }
+    // dWh = sum_t delta_t (x) h_{t-1},  db = sum_t delta_t,  dWx rows by token id; delta and
+    // h_{t-1} rows are already in LDS.
     __syncthreads();
-    for (int j = tid; j < H; j += kThreads) {
-        float sum = 0.f;
-        for (int t = 0; t < T; ++t) sum += D[t * H + j];
-        a.db[j] = a.beta ? a.db[j] + sum : sum;
+    // Overwrite and accumulate run as separate loops: a load inside a storing loop would make
+    // every iteration wait for the previous store to be acknowledged.
+    if (tid < T) {  // first step at which each step's token occurs
+        int f = tid;
+        for (int u = tid - 1; u >= 0; --u)
+            if (s_ids[u] == s_ids[tid]) f = u;
+        s_first[tid] = f;
     }
-    for (int e = tid; e < H * H; e += kThreads) {
-        const int j = e / H, i = e - j * H;
-        float sum = 0.f;
-        for (int t = 0; t < T; ++t) sum = fmaf(D[t * H + j], Hprev[t * H + i], sum);
-        a.dWh[e] = a.beta ? a.dWh[e] + sum : sum;
-    }
-    // token rows: the first occurrence of an id sums all its steps in ascending order
-    for (int t = 0; t < T; ++t) {
-        const int id = a.x[t];
-        bool first = true;
-        for (int u = 0; u < t; ++u) first = first && (a.x[u] != id);
-        if (!first) continue;      // uniform across the workgroup
+    auto tail = [&](auto accumulate) {
+        constexpr bool ACC = decltype(accumulate)::value;
         for (int j = tid; j < H; j += kThreads) {
             float sum = 0.f;
-            for (int u = t; u < T; ++u)
-                if (a.x[u] == id) sum += D[u * H + j];
-            float* dst = a.dWx + (size_t)id * H + j;
-            *dst = a.beta ? *dst + sum : sum;
+            for (int t0 = 0; t0 < T; t0 += 8) {
+                float d[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) d[u] = (t0 + u < T) ? Dl[(t0 + u) * H + j] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += d[u];
+            }
+            a.db[j] = ACC ? a.db[j] + sum : sum;
         }
-    }
+        // dWh = Delta^T Hprev on the matrix cores: both operands already sit K-major in LDS
+        // ([t][.]), which is the order the 32x32x2 MFMA wants its lanes to fetch them in.
+        const int lane = tid % kWave, wave = tid / kWave;
+        const int nt = (H + 31) / 32;
+        for (int tile = wave; tile < nt * nt; tile += kThreads / kWave) {
+            const int m0 = (tile / nt) * 32, n0 = (tile % nt) * 32;
+            const int m = m0 + lane % 32, n = n0 + lane % 32, ks = lane / 32;
+            f32x16 acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+            for (int kk = 0; kk < T; kk += 2) {
+                const int k = kk + ks;
+                const float av = (k < T && m < H) ? Dl[k * H + m] : 0.f;
+                const float bv = (k < T && n < H) ? Hl[k * H + n] : 0.f;
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+            }
+            if (n < H) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+                    if (row < H) {
+                        float* dst = a.dWh + (size_t)row * H + n;
+                        *dst = ACC ? *dst + acc[e] : acc[e];
+                    }
+                }
+            }
+        }
+        __syncthreads();  // Delta rows are folded in place below
+        // Token rows: fold every repeated step into the row of its token's first step (ascending
+        // step order, each lane only touches its own column), then write the first-step rows.
+        for (int j = tid; j < H; j += kThreads) {
+            for (int u = 1; u < T; ++u) {
+                const int f = s_first[u];
+                if (f != u) Dl[f * H + j] += Dl[u * H + j];
+            }
+            for (int t = 0; t < T; ++t) {
+                if (s_first[t] != t) continue;
+                float* dst = a.dWx + (size_t)s_ids[t] * H + j;
+                *dst = ACC ? *dst + Dl[t * H + j] : Dl[t * H + j];
+            }
+        }
+    };
+    if (a.beta) tail(std::true_type{}); else tail(std::false_type{});
 }
 
 __global__ void zero_words_kernel(int32_t* p, int n) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
-}
-
-template <typename K>
-hipError_t allow_lds(K kernel, size_t bytes) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
 int pow2_floor(int v) {
@@ -246,25 +481,45 @@ hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s) {
     return hipGetLastError();
 }
 
-bool rec_resident_plan(int H, int B, int T, bool fuse_post, RecResPlan* out) {
+bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan* out) {
     if (B > 4 || H > 4096) return false;
+    if (fuse_post && (B != 1 || T > kFuseMaxT || !bwd)) return false;
     constexpr size_t kLdsBudget = 150 * 1024;  // of 160 KB per CU
     const int Hp = (H + 3) / 4 * 4;
     for (int P = 1; P <= 128; P *= 2) {
         if (P * B > 128) break;
         const int R = (H + P - 1) / P;
-        int L = pow2_floor(kThreads / R);
-        if (L < 1) L = 1;
+        if (R > kThreads) continue;  // one output per lane group
+        RecResPlan pl{};
+        pl.P = P; pl.R = R;
+        int L = pow2_floor(kThreads / R);  // lanes sharing one output; R * L <= kThreads
         if (L > 64) L = 64;
-        int ldw = Hp;
-        if (L < 8) while (ldw % 32 != (4 * L) % 32) ldw += 4;
-        size_t w_floats = (size_t)R * ldw;
-        if (fuse_post && P == 1 && (size_t)2 * T * H > w_floats) w_floats = (size_t)2 * T * H;
+        pl.L = L;
+        size_t w_floats;
+        if (!bwd) {
+            // rows of float4: lanes of a group read 4L consecutive words, groups should start
+            // 4L banks apart
+            int ldw = Hp;
+            if (L < 8) while (ldw % 32 != (4 * L) % 32) ldw += 4;
+            pl.ldw = ldw;
+            pl.bKC = 0;
+            w_floats = (size_t)R * ldw;
+        } else {
+            // [k][column] with scalar reads: a wavefront touches 64/L consecutive columns in L
+            // different k rows, which should start 64/L banks apart
+            int ldw = R;
+            if (L >= 2) while (ldw % 32 != (64 / L) % 32) ldw += 1;
+            pl.ldw = ldw;
+            pl.bKC = (H + L - 1) / L;
+            w_floats = (size_t)H * ldw;
+        }
+        pl.bI = 0; pl.bQ = 0;
         w_floats = (w_floats + 3) / 4 * 4;  // keeps the state vectors 16-byte aligned
-        const size_t bytes = (w_floats + 2 * (size_t)Hp) * 4;
-        if (bytes <= kLdsBudget) {
-            out->P = P; out->R = R; out->L = L; out->ldw = ldw;
-            out->w_floats = (int)w_floats; out->smem = bytes;
+        size_t floats = w_floats + 2 * (size_t)Hp + (size_t)2 * TC * 2 * R;
+        if (fuse_post) floats += (size_t)3 * T * H;
+        if (floats * 4 <= kLdsBudget) {
+            pl.w_floats = (int)w_floats; pl.smem = floats * 4;
+            *out = pl;
             return true;
         }
         if (fuse_post) return false;  // the fused tail needs the single-workgroup form
@@ -274,6 +529,7 @@ bool rec_resident_plan(int H, int B, int T, bool fuse_post, RecResPlan* out) {
 
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s) {
     a.P = pl.P; a.R = pl.R; a.L = pl.L; a.ldw = pl.ldw; a.w_floats = pl.w_floats;
+    a.bI = pl.bI; a.bQ = pl.bQ; a.bKC = pl.bKC;
     if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
     if (pl.P > 1) {
         hipError_t e = launch_zero_words(a.flags, pl.P * a.B, s);

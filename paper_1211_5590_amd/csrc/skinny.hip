@@ -1,84 +1,128 @@
 // Output layer for a short single sequence (N = T*B <= 32 rows, the paper's batch-1 language
 // model benchmark shape): with so few rows the three products with the H x NV output matrix
 // are bound by streaming that matrix, not by arithmetic, so they run as column-parallel
-// kernels in which every workgroup owns a strip of vocabulary columns, reads its strip of V
-// exactly once per kernel, and keeps the N hidden rows in LDS.
+// kernels in which every workgroup owns a strip of 128 vocabulary columns, reads its strip of
+// V once per kernel with 16-byte loads, and keeps the N hidden rows in LDS.
 //
 //   skinny_logits : Z strip = Hs V + c, per-row (max, sum exp) of the strip, target logit
 //   skinny_loss   : merges the strip statistics -> lse per row, loss
 //   skinny_back   : dZ strip from Z and lse (never written back), dc, dV strip = Hs^T dZ,
 //                   partial G = dZ V^T over the strip, and the zero fill of dWx
 // The partial G of all strips is summed, in strip order, by the reverse-loop kernel.
+//
+// Thread layout inside a strip: lane%32 = a quad of 4 adjacent columns, tid/32 = one of 16
+// groups that split the hidden dimension.  Requires NV % 4 == 0 (16-byte column quads).
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
+
+#include <type_traits>
 
 namespace rnn {
 namespace {
 
 constexpr int NR = 16;    // rows held in registers per pass
 constexpr int CW = 128;   // vocabulary columns per workgroup
-constexpr int NTH = 256;
-constexpr int IG = NTH / CW;  // groups splitting the H dimension
+constexpr int NTH = 512;
+constexpr int QW = CW / 4;     // column quads per strip (32)
+constexpr int IG = NTH / QW;   // groups splitting the H dimension (16)
+constexpr int NWV = NTH / 64;  // wavefronts per workgroup (8)
+constexpr int NB = 8;          // independent 16-byte loads in flight per thread
 
 // hidden rows of one pass into LDS as hs[i][NR] (zero padded rows)
 __device__ __forceinline__ void load_rows(const float* __restrict__ Hs, float* hs, int n0, int N,
                                           int H, int tid) {
-    for (int e = tid; e < H * NR; e += NTH) {
-        const int i = e / NR, r = e % NR;
-        hs[e] = (n0 + r < N) ? Hs[(size_t)(n0 + r) * H + i] : 0.f;
+    const int n = H * NR;
+    for (int base = tid; base < n; base += NB * NTH) {
+        float t[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int e = base + u * NTH;
+            const int r = e / H, i = e - r * H;            // coalesced along i
+            t[u] = (e < n && n0 + r < N) ? Hs[(size_t)(n0 + r) * H + i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int e = base + u * NTH;
+            const int r = e / H, i = e - r * H;
+            if (e < n) hs[i * NR + r] = t[u];
+        }
     }
 }
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 
 __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int H = a.H, O = a.O, N = a.N;
     float* hs = smem;                 // [H][NR]
-    float* red = hs + H * NR;         // [IG][NR][CW]
-    const int tid = threadIdx.x, kk = tid % CW, ig = tid / CW;
-    const int k = blockIdx.x * CW + kk;
-    const bool kin = k < O;
+    float* red = hs + H * NR;         // [NWV][NR][CW]
+    const int tid = threadIdx.x, kq = tid % QW, ig = tid / QW;
     const int lane = tid % kWave, wave = tid / kWave;
+    const int k = blockIdx.x * CW + 4 * kq;
+    const bool kin = k < O;           // O % 4 == 0: a quad is entirely inside or outside
+
+    // request the strip of V and the bias before waiting for anything
+    auto load_v = [&](int i0, float4 (&v)[NB]) {
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int i = i0 + u * IG;
+            v[u] = (kin && i < H) ? ld4(a.V + (size_t)i * O + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    float4 v[NB];
+    load_v(ig, v);
+    const int kc_own = blockIdx.x * CW + tid % CW;          // column of this thread in the combine
+    const float cbias = kc_own < O ? a.c[kc_own] : 0.f;
+    const bool one_batch = H <= IG * NB;
 
     for (int n0 = 0; n0 < N; n0 += NR) {
         __syncthreads();
         load_rows(a.Hs, hs, n0, N, H, tid);
         __syncthreads();
-        float acc[NR];
+        float4 acc[NR];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-        if (kin) {
-#pragma unroll 4
-            for (int i = ig; i < H; i += IG) {
-                const float v = a.V[(size_t)i * O + k];
-                const float4* h4 = reinterpret_cast<const float4*>(hs + i * NR);
+        for (int r = 0; r < NR; ++r) acc[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i0 = ig; i0 < H; i0 += IG * NB) {
+            if (i0 != ig || (n0 > 0 && !one_batch)) load_v(i0, v);
 #pragma unroll
-                for (int r4 = 0; r4 < NR / 4; ++r4) {
-                    const float4 h = h4[r4];
-                    acc[4 * r4 + 0] = fmaf(h.x, v, acc[4 * r4 + 0]);
-                    acc[4 * r4 + 1] = fmaf(h.y, v, acc[4 * r4 + 1]);
-                    acc[4 * r4 + 2] = fmaf(h.z, v, acc[4 * r4 + 2]);
-                    acc[4 * r4 + 3] = fmaf(h.w, v, acc[4 * r4 + 3]);
+            for (int u = 0; u < NB; ++u) {
+                const int i = i0 + u * IG;
+                if (i < H) {
+                    const float* hrow = hs + i * NR;
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        const float h = hrow[r];
+                        acc[r].x = fmaf(h, v[u].x, acc[r].x);
+                        acc[r].y = fmaf(h, v[u].y, acc[r].y);
+                        acc[r].z = fmaf(h, v[u].z, acc[r].z);
+                        acc[r].w = fmaf(h, v[u].w, acc[r].w);
+                    }
                 }
             }
         }
+        // the two H-groups of a wavefront combine by shuffle, the four wavefronts through LDS
 #pragma unroll
-        for (int r = 0; r < NR; ++r) red[(ig * NR + r) * CW + kk] = acc[r];
+        for (int r = 0; r < NR; ++r) {
+            acc[r].x += __shfl_xor(acc[r].x, 32, kWave);
+            acc[r].y += __shfl_xor(acc[r].y, 32, kWave);
+            acc[r].z += __shfl_xor(acc[r].z, 32, kWave);
+            acc[r].w += __shfl_xor(acc[r].w, 32, kWave);
+            if (lane < 32) *reinterpret_cast<float4*>(red + (wave * NR + r) * CW + 4 * kq) = acc[r];
+        }
         __syncthreads();
-        // combine the H-groups, add the bias, store the strip of Z; keep z in red[0]
-        for (int e = tid; e < NR * CW; e += NTH) {
+        for (int e = tid; e < NR * CW; e += NTH) {   // NTH is a multiple of CW: column = tid % CW
             const int r = e / CW, c = e % CW;
             float z = red[r * CW + c];
 #pragma unroll
-            for (int g = 1; g < IG; ++g) z += red[(g * NR + r) * CW + c];
-            const int kc = blockIdx.x * CW + c;
-            if (kc < O) z += a.c[kc]; else z = -INFINITY;
+            for (int w = 1; w < NWV; ++w) z += red[(w * NR + r) * CW + c];
+            if (kc_own < O) z += cbias; else z = -INFINITY;
             red[r * CW + c] = z;
-            if (kc < O && n0 + r < N) a.Z[(size_t)(n0 + r) * O + kc] = z;
+            if (kc_own < O && n0 + r < N) a.Z[(size_t)(n0 + r) * O + kc_own] = z;
         }
         __syncthreads();
         // strip statistics: one wavefront per row
-        for (int r = wave; r < NR && n0 + r < N; r += NTH / kWave) {
+        for (int r = wave; r < NR && n0 + r < N; r += NWV) {
             const float z0 = red[r * CW + lane], z1 = red[r * CW + 64 + lane];
             const float m = wave_max(fmaxf(z0, z1));
             const float e = __expf(z0 - m) + __expf(z1 - m);  // exp(-inf) = 0 for padding
@@ -97,7 +141,7 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
 __global__ __launch_bounds__(NTH) void skinny_loss_kernel(SkinnyArgs a, int strips, float* loss) {
     __shared__ float rl[32];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    for (int n = wave; n < a.N; n += NTH / kWave) {
+    for (int n = wave; n < a.N; n += NWV) {
         float m = -INFINITY, s = 0.f;
         for (int g = lane; g < strips; g += kWave)
             lse_merge(m, s, a.pm[(size_t)n * strips + g], a.ps[(size_t)n * strips + g]);
@@ -120,109 +164,141 @@ __global__ __launch_bounds__(NTH) void skinny_loss_kernel(SkinnyArgs a, int stri
     }
 }
 
+// Sum p[0..15] over the 32 lanes that share lane/32, leaving the total of row
+// r = 8*b4 + 4*b3 + 2*b2 + b1 (bits of lane%32) in every lane: each stage halves the number of
+// live values, so the whole reduction costs 16 shuffles instead of 80.
+__device__ __forceinline__ float quad_rows_reduce(float (&p)[NR], int lane) {
+    float q8[8], q4[4], q2[2];
+    const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float send = b4 ? p[j] : p[j + 8], keep = b4 ? p[j + 8] : p[j];
+        q8[j] = keep + __shfl_xor(send, 16, kWave);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float send = b3 ? q8[j] : q8[j + 4], keep = b3 ? q8[j + 4] : q8[j];
+        q4[j] = keep + __shfl_xor(send, 8, kWave);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float send = b2 ? q4[j] : q4[j + 2], keep = b2 ? q4[j + 2] : q4[j];
+        q2[j] = keep + __shfl_xor(send, 4, kWave);
+    }
+    const float send = b1 ? q2[0] : q2[1], keep = b1 ? q2[1] : q2[0];
+    float v = keep + __shfl_xor(send, 2, kWave);
+    v += __shfl_xor(v, 1, kWave);
+    return v;
+}
+
 __global__ __launch_bounds__(NTH) void skinny_back_kernel(SkinnyArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int H = a.H, O = a.O, N = a.N;
     float* hs = smem;                    // [H][NR]
-    float* dzs = hs + H * NR;            // [CW][NR]
-    float* Vs = dzs + CW * NR;           // [H][CW+1]
-    float* gred = Vs + H * (CW + 1);     // [IG][NR][H] partial G of the H-groups' column halves
-    const int tid = threadIdx.x, kk = tid % CW, ig = tid / CW;
-    const int k0 = blockIdx.x * CW, k = k0 + kk;
+    float* dzs = hs + H * NR;            // [NR][CW]
+    float* gs = dzs + NR * CW;           // [NR][H] this strip's partial G
+    const int tid = threadIdx.x, kq = tid % QW, ig = tid / QW, lane = tid % kWave;
+    const int k0 = blockIdx.x * CW, k = k0 + 4 * kq;
     const bool kin = k < O;
     const float invN = 1.0f / (float)N;
+    const int myrow = ((lane & 16) ? 8 : 0) + ((lane & 8) ? 4 : 0) + ((lane & 4) ? 2 : 0) + ((lane & 2) ? 1 : 0);
 
-    // strip of V into LDS (coalesced), reused by every row pass
-    for (int e = tid; e < H * CW; e += NTH) {
-        const int i = e / CW, c = e % CW;
-        Vs[i * (CW + 1) + c] = (k0 + c < O) ? a.V[(size_t)i * O + k0 + c] : 0.f;
-    }
+    auto load_v = [&](int i0, float4 (&v)[NB]) {
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int i = i0 + u * IG;
+            v[u] = (kin && i < H) ? ld4(a.V + (size_t)i * O + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    const bool one_batch = H <= IG * NB;
+    float4 v[NB];
 
-    float dc = 0.f;
+    float4 dc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int n0 = 0; n0 < N; n0 += NR) {
+        // requests first: logits, row statistics and targets of row ig, then the strip of V
+        const int nrow = n0 + ig;                     // IG == NR: group ig produces row ig
+        float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+        float l = 0.f;
+        int y = -1;
+        if (nrow < N && kin) {
+            z = ld4(a.Z + (size_t)nrow * O + k);
+            l = a.lse[nrow];
+            y = a.y[nrow] - k;
+        }
+        if (n0 == 0 || !one_batch) load_v(ig, v);
         __syncthreads();
         load_rows(a.Hs, hs, n0, N, H, tid);
-        // d loss / d z of the strip for this pass: dzs[c][r]
-        for (int e = tid; e < NR * CW; e += NTH) {
-            const int r = e / CW, c = e % CW;
-            float d = 0.f;
-            if (n0 + r < N && k0 + c < O) {
-                d = __expf(a.Z[(size_t)(n0 + r) * O + k0 + c] - a.lse[n0 + r]);
-                if (a.y[n0 + r] == k0 + c) d -= 1.f;
-                d *= invN;
+        {
+            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (nrow < N && kin) {
+                d.x = (__expf(z.x - l) - (y == 0 ? 1.f : 0.f)) * invN;
+                d.y = (__expf(z.y - l) - (y == 1 ? 1.f : 0.f)) * invN;
+                d.z = (__expf(z.z - l) - (y == 2 ? 1.f : 0.f)) * invN;
+                d.w = (__expf(z.w - l) - (y == 3 ? 1.f : 0.f)) * invN;
             }
-            dzs[c * NR + r] = d;
+            *reinterpret_cast<float4*>(dzs + ig * CW + 4 * kq) = d;
         }
         __syncthreads();
-        float dz[NR];
-        {
-            const float4* d4 = reinterpret_cast<const float4*>(dzs + kk * NR);
+        float4 dz[NR];
 #pragma unroll
-            for (int r4 = 0; r4 < NR / 4; ++r4) {
-                const float4 d = d4[r4];
-                dz[4 * r4] = d.x; dz[4 * r4 + 1] = d.y; dz[4 * r4 + 2] = d.z; dz[4 * r4 + 3] = d.w;
-            }
-        }
+        for (int r = 0; r < NR; ++r) dz[r] = ld4(dzs + r * CW + 4 * kq);
         if (ig == 0) {
 #pragma unroll
-            for (int r = 0; r < NR; ++r) dc += dz[r];
+            for (int r = 0; r < NR; ++r) { dc.x += dz[r].x; dc.y += dz[r].y; dc.z += dz[r].z; dc.w += dz[r].w; }
         }
-        // dV[i,k] (+)= sum_r hs[i][r] dz[r]
-        if (kin) {
-            for (int i = ig; i < H; i += IG) {
-                const float4* h4 = reinterpret_cast<const float4*>(hs + i * NR);
-                float sum = 0.f;
+        // Overwrite and accumulate are separate instantiations: a load of the old dV inside the
+        // storing loop would make every iteration wait for the previous store's acknowledgement.
+        auto products = [&](auto accumulate) {
+            constexpr bool ACC = decltype(accumulate)::value;
+            for (int i0 = ig; i0 < H; i0 += IG * NB) {
+                if (i0 != ig) load_v(i0, v);
 #pragma unroll
-                for (int r4 = 0; r4 < NR / 4; ++r4) {
-                    const float4 h = h4[r4];
-                    sum = fmaf(h.x, dz[4 * r4], sum);
-                    sum = fmaf(h.y, dz[4 * r4 + 1], sum);
-                    sum = fmaf(h.z, dz[4 * r4 + 2], sum);
-                    sum = fmaf(h.w, dz[4 * r4 + 3], sum);
-                }
-                float* dst = a.dV + (size_t)i * O + k;
-                *dst = (a.beta || n0 > 0) ? *dst + sum : sum;
-            }
-        }
-        // partial G[r][i] = sum over the strip's columns of dz[r][c] V[i][c]; thread = (i, half)
-        {
-            constexpr int HALF = CW / IG;
-            for (int i = tid % CW; i < H; i += CW) {
-                float g[NR];
+                for (int u = 0; u < NB; ++u) {
+                    const int i = i0 + u * IG;
+                    if (i >= H) continue;                       // uniform within a 32-lane group
+                    // dV[i, quad] (+)= sum_r h[r][i] dz[r]
+                    const float* hrow = hs + i * NR;
+                    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+                    float p[NR];
 #pragma unroll
-                for (int r = 0; r < NR; ++r) g[r] = 0.f;
-                const float* vrow = Vs + i * (CW + 1) + ig * HALF;
-                for (int c = 0; c < HALF; ++c) {
-                    const float v = vrow[c];
-                    const float4* d4 = reinterpret_cast<const float4*>(dzs + (ig * HALF + c) * NR);
-#pragma unroll
-                    for (int r4 = 0; r4 < NR / 4; ++r4) {
-                        const float4 d = d4[r4];
-                        g[4 * r4 + 0] = fmaf(d.x, v, g[4 * r4 + 0]);
-                        g[4 * r4 + 1] = fmaf(d.y, v, g[4 * r4 + 1]);
-                        g[4 * r4 + 2] = fmaf(d.z, v, g[4 * r4 + 2]);
-                        g[4 * r4 + 3] = fmaf(d.w, v, g[4 * r4 + 3]);
+                    for (int r = 0; r < NR; ++r) {
+                        const float h = hrow[r];
+                        sum.x = fmaf(h, dz[r].x, sum.x);
+                        sum.y = fmaf(h, dz[r].y, sum.y);
+                        sum.z = fmaf(h, dz[r].z, sum.z);
+                        sum.w = fmaf(h, dz[r].w, sum.w);
+                        // this quad's share of G[r][i] = sum_c dz[r][c] V[i][c]
+                        p[r] = fmaf(dz[r].x, v[u].x, fmaf(dz[r].y, v[u].y, fmaf(dz[r].z, v[u].z, dz[r].w * v[u].w)));
                     }
+                    if (kin) {
+                        float4* dst = reinterpret_cast<float4*>(a.dV + (size_t)i * O + k);
+                        if (ACC) {
+                            const float4 old = *dst;
+                            sum.x += old.x; sum.y += old.y; sum.z += old.z; sum.w += old.w;
+                        }
+                        *dst = sum;
+                    }
+                    const float g = quad_rows_reduce(p, lane);
+                    if ((lane & 1) == 0) gs[myrow * H + i] = g;
                 }
-#pragma unroll
-                for (int r = 0; r < NR; ++r) gred[(ig * NR + r) * H + i] = g[r];
             }
-        }
+        };
+        if (a.beta || n0 > 0) products(std::true_type{}); else products(std::false_type{});
         __syncthreads();
         for (int e = tid; e < NR * H; e += NTH) {
-            const int r = e / H, i = e % H;
-            if (n0 + r >= N) continue;
-            float g = gred[r * H + i];
-#pragma unroll
-            for (int q = 1; q < IG; ++q) g += gred[(q * NR + r) * H + i];
-            a.gpart[((size_t)blockIdx.x * N + n0 + r) * H + i] = g;
+            const int r = e / H;
+            if (n0 + r < N) a.gpart[((size_t)blockIdx.x * N + n0 + r) * H + (e - r * H)] = gs[e];
         }
     }
-    if (ig == 0 && kin) a.dc[k] = a.beta ? a.dc[k] + dc : dc;
+    if (ig == 0 && kin) {
+        float4* dst = reinterpret_cast<float4*>(a.dc + k);
+        if (a.beta) { const float4 o = *dst; dc.x += o.x; dc.y += o.y; dc.z += o.z; dc.w += o.w; }
+        *dst = dc;
+    }
 
     // zero fill of the token-gradient matrix, an even share per workgroup (overwrite mode)
     if (a.dWx_zero) {
-        const size_t total4 = ((size_t)a.NV * H) / 4;  // NV*H*4 bytes; dWx is 16-byte aligned
+        const size_t total4 = ((size_t)a.NV * H) / 4;  // dWx is 16-byte aligned
         const size_t per = (total4 + gridDim.x - 1) / gridDim.x;
         const size_t b0 = (size_t)blockIdx.x * per;
         const size_t b1 = b0 + per < total4 ? b0 + per : total4;
@@ -233,20 +309,30 @@ __global__ __launch_bounds__(NTH) void skinny_back_kernel(SkinnyArgs a) {
     }
 }
 
+static_assert(IG == NR, "one group per register row");
+size_t logits_smem(int H) { return ((size_t)H * NR + (size_t)NWV * NR * CW) * 4; }
+size_t back_smem(int H) { return ((size_t)H * NR + (size_t)NR * CW + (size_t)NR * H) * 4; }
+
 }  // namespace
 
 int skinny_strips(int O) { return (O + CW - 1) / CW; }
 
 bool skinny_supported(int N, int H, int O) {
-    if (N > 32 || N < 1) return false;
-    const size_t back = ((size_t)H * NR + (size_t)CW * NR + (size_t)H * (CW + 1) + (size_t)IG * NR * H) * 4;
-    return back <= 150 * 1024 && O >= 1;
+    if (N > 32 || N < 1 || O % 4 != 0) return false;
+    return back_smem(H) <= 64 * 1024 && logits_smem(H) <= 140 * 1024;
 }
 
 hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s) {
-    const size_t smem = ((size_t)a.H * NR + (size_t)IG * NR * CW) * 4;
+    static size_t allowed = 0;
+    if (logits_smem(a.H) > 64 * 1024 && logits_smem(a.H) > allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_logits_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)logits_smem(a.H));
+        if (e != hipSuccess) return e;
+        allowed = logits_smem(a.H);
+    }
     ProfileScope ps(K_SKINNY_LOGITS, s);
-    hipLaunchKernelGGL(skinny_logits_kernel, dim3(skinny_strips(a.O)), dim3(NTH), smem, s, a);
+    hipLaunchKernelGGL(skinny_logits_kernel, dim3(skinny_strips(a.O)), dim3(NTH), logits_smem(a.H), s, a);
     return hipGetLastError();
 }
 
@@ -257,16 +343,8 @@ hipError_t launch_skinny_loss(const SkinnyArgs& a, float* loss, hipStream_t s) {
 }
 
 hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s) {
-    const size_t smem = ((size_t)a.H * NR + (size_t)CW * NR + (size_t)a.H * (CW + 1) + (size_t)IG * NR * a.H) * 4;
-    static size_t allowed = 0;
-    if (smem > 64 * 1024 && smem > allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_back_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        allowed = smem;
-    }
     ProfileScope ps(K_SKINNY_BACK, s);
-    hipLaunchKernelGGL(skinny_back_kernel, dim3(skinny_strips(a.O)), dim3(NTH), smem, s, a);
+    hipLaunchKernelGGL(skinny_back_kernel, dim3(skinny_strips(a.O)), dim3(NTH), back_smem(a.H), s, a);
     return hipGetLastError();
 }
 
