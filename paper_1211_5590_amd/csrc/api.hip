@@ -23,6 +23,8 @@ struct Plan {
 struct Variant {
     bool resident;        // resident-weight persistent loops (else shape-agnostic loops)
     bool skinny;          // column-strip output layer + fused tail of the reverse loop
+    bool stepwise;        // batched recurrence as one fused MFMA launch per step
+    bool batch_mfma;      // batched persistent loop, weights in registers (H <= 256)
     RecResPlan fwd, bwd;  // plans of the two loops when resident
 };
 
@@ -67,6 +69,7 @@ size_t max_splitk_floats(const Sizes& s) {
     take(gemm_splitk_floats(H, O, N));   // dV = Hs^T dZ
     take(gemm_splitk_floats(N, H, O));   // G = dZ V^T
     take(gemm_splitk_floats(H, H, N));   // dWh = Delta^T Hprev
+    take(gemm_splitk_floats(s.B, H, H)); // dh0 = delta_0 Wh (stepwise recurrence)
     if (!s.tokens) {
         take(gemm_splitk_floats(N, H, D));  // U = X Wx^T
         take(gemm_splitk_floats(H, D, N));  // dWx = Delta^T X
@@ -80,7 +83,11 @@ Variant pick_variant(const rnn_dims* d) {
     if (d->flags & RNN_FLAG_REFERENCE_KERNELS) return v;
     v.resident = rec_resident_plan(s.H, s.B, s.T, false, false, &v.fwd) &&
                  rec_resident_plan(s.H, s.B, s.T, true, false, &v.bwd);
-    if (!v.resident) return v;
+    if (!v.resident) {
+        v.batch_mfma = rec_batch_mfma_supported(s.H, s.B);
+        v.stepwise = !v.batch_mfma && s.B > 4;
+        return v;
+    }
     RecResPlan fused;
     if (s.tokens && s.ce && s.B == 1 && skinny_supported((int)s.N, s.H, s.O) &&
         rec_resident_plan(s.H, s.B, s.T, true, true, &fused)) {
@@ -99,7 +106,7 @@ Plan make_plan(const rnn_dims* d) {
     p.Z = take(N * O * 4);
     p.lse = take(N * 4);
     p.rowloss = take(N * 4);
-    p.U = take(s.tokens ? 0 : N * H * 4);
+    p.U = take((!s.tokens || s.B > 4) ? N * H * 4 : 0);  // hoisted input term (dense, or batched tokens)
     p.G = take(N * H * 4);
     p.Delta = take(N * H * 4);
     p.WhT = take(H * H * 4);
@@ -182,6 +189,15 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         r.hist = a.hist; r.h_last = h_last; r.ring = a.ring;
         return launch_rec_resident(r, v.fwd, false, s);
     }
+    if (v.batch_mfma) {
+        float* U = at<float>(ws, pl.U);
+        if (z.tokens) RNN_TRY(launch_gather_input(a.x, P->Wx, P->b, U, (int)z.N, z.H, s));
+        RecMfmaArgs m{};
+        m.Wh = P->Wh; m.H = z.H; m.T = z.T; m.B = z.B; m.act = d->act;
+        m.U = U; m.h0 = h0; m.hist = a.hist; m.h_last = h_last; m.ring = a.ring;
+        return launch_rec_batch_mfma(m, false, s);
+    }
+    if (v.stepwise) return run_rec_fwd_stepwise(a, s);
     return launch_rec_fwd_reference(a, s);
 }
 
@@ -285,6 +301,17 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
     // reverse-time loop
     if (v.resident) {
         RNN_TRY(launch_rec_resident(r, v.bwd, true, s));
+    } else if (v.batch_mfma) {
+        RecMfmaArgs m{};
+        m.Wh = P->Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
+        m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
+        RNN_TRY(launch_rec_batch_mfma(m, true, s));
+    } else if (v.stepwise) {
+        RecBwdArgs a{};
+        a.Wh = P->Wh; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
+        a.Delta = Delta; a.dh0 = dh0; a.splitk_ws = splitk;
+        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
+        RNN_TRY(run_rec_bwd_stepwise(a, s));
     } else {
         float* WhT = at<float>(ws, pl.WhT);
         RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
@@ -406,6 +433,8 @@ const char* rnn_strerror(int code) {
 const char* rnn_recurrence_variant(const rnn_dims* dims) {
     if (!dims_valid(dims)) return "invalid";
     const Variant v = pick_variant(dims);
+    if (v.batch_mfma) return "batch_mfma";
+    if (v.stepwise) return "step_mfma";
     if (!v.resident) return "reference";
     return v.fwd.P == 1 ? "wg_resident" : "grid_resident";
 }

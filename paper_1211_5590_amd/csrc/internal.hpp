@@ -21,7 +21,17 @@ struct GemmArgs {
     const float* bias_n;  // nullable, length N
     int beta;             // 0 overwrite, 1 accumulate
     float* splitk_ws;     // nullable when gemm_splitk_floats == 0
+    // Fused epilogue of one time step of the batched recurrence (forces 64x64 tiles, no split-K):
+    //   GEMM_EPI_REC_FWD: C = act(acc + in)   in = e0[row,col] (dense input term, ld N) or, when
+    //                     ids != NULL, e0[ids[row]*N + col] + e1[col] (token rows of Wx plus bias)
+    //   GEMM_EPI_REC_BWD: C = (acc + e0[row,col]) * act'(e1[row,col])   (e0 = G_t, e1 = h_t)
+    int epi;
+    const float* e0;
+    const float* e1;
+    const int32_t* ids;
+    int act;
 };
+enum { GEMM_EPI_PLAIN = 0, GEMM_EPI_REC_FWD = 1, GEMM_EPI_REC_BWD = 2 };
 size_t gemm_splitk_floats(int M, int N, int K);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 
@@ -47,6 +57,7 @@ struct RecBwdArgs {
     float* Delta;         // [T,B,H] receives d loss / d a_t
     float* dh0;           // nullable [B,H]
     int H, T, B, act;
+    float* splitk_ws;     // split-K scratch for the dh0 product (stepwise path)
 };
 // Resident-weight persistent loops (recurrence.hip).  One struct serves both directions.
 struct RecResArgs {
@@ -70,6 +81,29 @@ struct RecResArgs {
 struct RecResPlan { int P, R, L, ldw, w_floats, bI, bQ, bKC; size_t smem; };
 bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan* out);
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s);
+
+// Batched recurrence run as one fused GEMM launch per time step (recurrence_step.hip); serves
+// the shapes the resident-weight kernels do not cover (batch > 4).
+hipError_t run_rec_fwd_stepwise(const RecFwdArgs& a, hipStream_t s);
+hipError_t run_rec_bwd_stepwise(const RecBwdArgs& a, hipStream_t s);
+
+// Persistent batched loop with register-resident weights (recurrence_mfma.hip), H <= 256, B > 4.
+struct RecMfmaArgs {
+    const float* Wh;
+    int H, T, B, act;
+    // forward
+    const float* U;       // [T,B,H] input term including the bias (always materialised)
+    const float* h0;      // nullable
+    float* hist;          // [T+1,B,H] or 2-slot ring
+    float* h_last;        // nullable
+    int ring;
+    // reverse
+    const float* G; const float* h_all; const float* dh_last; float* Delta; float* dh0;
+};
+bool rec_batch_mfma_supported(int H, int B);
+hipError_t launch_gather_input(const int32_t* x, const float* Wx, const float* b, float* U, int N,
+                               int H, hipStream_t s);
+hipError_t launch_rec_batch_mfma(const RecMfmaArgs& a, bool bwd, hipStream_t s);
 
 hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s);
 hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hipStream_t s);

@@ -93,6 +93,10 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     float* Hl = Dl + T * H;
 
     // thread roles
+    // Layout of the resident slice: [output][k] with float4 reads for the forward loop and for
+    // the multi-workgroup reverse loop (long-running, so a one-off transposing load pays off);
+    // [k][output] for the single-workgroup reverse loop, whose launches are short.
+    const bool rowmajor = !BWD || P > 1;
     const int q = tid % L;                               // which share of the k range
     const int own = tid / L;                             // which output of the slice
     const bool lead = (q == 0) && own < rows;            // finishes output r0 + own
@@ -157,6 +161,35 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         const int padw = ldw - H;
         if (padw > 0)
             for (int i = tid; i < rows * padw; i += kThreads) {  // zero the row padding
+                const int r = i / padw;
+                W[r * ldw + H + (i - r * padw)] = 0.f;
+            }
+    } else if (rowmajor) {
+        const int n = H * rows;  // W[c][k] = Wh[k][r0 + c]: coalesced reads, transposing LDS writes
+        const float invR = 1.0f / (float)(rows > 0 ? rows : 1);
+        for (int base = tid; base < n; base += NL * kThreads) {
+            float t[NL];
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                t[u] = 0.f;
+                if (i < n) {
+                    const int k = fast_div(i, rows, invR);
+                    t[u] = a.Wh[(size_t)k * H + r0 + (i - k * rows)];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                const int i = base + u * kThreads;
+                if (i < n) {
+                    const int k = fast_div(i, rows, invR);
+                    W[(i - k * rows) * ldw + k] = t[u];
+                }
+            }
+        }
+        const int padw = ldw - H;
+        if (padw > 0)
+            for (int i = tid; i < rows * padw; i += kThreads) {
                 const int r = i / padw;
                 W[r * ldw + H + (i - r * padw)] = 0.f;
             }
@@ -274,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     // pays for one or two LDS round trips instead of one per element.
     auto slice_dot = [&](const float* v) -> float {
         float acc0 = 0.f, acc1 = 0.f;
-        if (!BWD) {
+        if (rowmajor) {
             const float4* w4 = reinterpret_cast<const float4*>(W + min(own, R - 1) * ldw);
             const float4* v4 = reinterpret_cast<const float4*>(v);
             for (int c0 = q; c0 < H4; c0 += 8 * L) {
@@ -496,7 +529,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
         if (L > 64) L = 64;
         pl.L = L;
         size_t w_floats;
-        if (!bwd) {
+        if (!bwd || P > 1) {
             // rows of float4: lanes of a group read 4L consecutive words, groups should start
             // 4L banks apart
             int ldw = Hp;

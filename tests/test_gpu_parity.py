@@ -28,6 +28,12 @@ SMALL_CASES = {
                                                        with_h0=True, with_dh_last=True)),
     "lm_short_two_passes": (700, 60, 700, 29, 1, dict(LM, wdist=("normal", 0.3), bias_std=0.2)),
     "lm_small_batch_resident": (300, 132, 300, 9, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1, with_h0=True)),
+    "lm_lanes16": (120, 24, 120, 11, 2, dict(LM, wdist=("normal", 0.4), bias_std=0.2, with_h0=True, with_dh_last=True)),
+    "lm_hidden_300_two_groups": (400, 300, 400, 9, 1, dict(LM, wdist=("uniform", 0.08), bias_std=0.1, with_dh_last=True)),
+    "lm_batch5_stepwise": (200, 70, 200, 6, 5, dict(LM, wdist=("normal", 0.3), bias_std=0.2, with_h0=True, with_dh_last=True)),
+    "dense_batched_stepwise": (48, 160, 40, 12, 40, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True)),
+    "lm_batched_wide_stepwise": (300, 320, 300, 5, 24, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
+    "lm_batched_ragged_mfma": (150, 100, 150, 7, 21, dict(LM, wdist=("normal", 0.2), bias_std=0.2, with_h0=True, with_dh_last=True)),
     "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_hidden_500": (700, 500, 700, 12, 1, dict(LM, wdist=("uniform", 0.05))),
     "lm_batched_mfma_shape": (512, 256, 512, 6, 32, dict(LM, wdist=("normal_fan", None), with_h0=True)),
@@ -150,7 +156,7 @@ def test_two_windows_chain_state_forward_and_gradient_backward():
 
 def test_variant_names_and_clean_status_word():
     expect = {"lm_window_rnnlm_shape": "wg_resident", "lm_hidden_500": "grid_resident",
-              "lm_batched_mfma_shape": "reference"}
+              "lm_batched_mfma_shape": "batch_mfma"}
     for name, want in expect.items():
         case = make(name)
         r = Runner(case)
