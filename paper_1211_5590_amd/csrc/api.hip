@@ -15,7 +15,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     // byte offsets into the workspace
-    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, pm, ps, zy, gpart,
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, pm, ps, zy, gpart, seen,
         total;
 };
 
@@ -122,6 +122,7 @@ Plan make_plan(const rnn_dims* d) {
     p.ps = take(small ? N * strips * 4 : 0);
     p.zy = take(small ? N * 4 : 0);
     p.gpart = take(small ? strips * N * H * 4 : 0);
+    p.seen = take(s.tokens && N >= 2048 ? (size_t)32 * s.NVin * 4 : 0);
     p.total = off;
     return p;
 }
@@ -197,7 +198,10 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         m.U = U; m.h0 = h0; m.hist = a.hist; m.h_last = h_last; m.ring = a.ring;
         return launch_rec_batch_mfma(m, false, s);
     }
-    if (v.stepwise) return run_rec_fwd_stepwise(a, s);
+    if (v.stepwise) {
+        a.WhT = at<float>(ws, pl.WhT);
+        return run_rec_fwd_stepwise(a, s);
+    }
     return launch_rec_fwd_reference(a, s);
 }
 
@@ -335,7 +339,11 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
     RNN_TRY(launch_colsum_finish(part, Gr->db, chunks, H, beta, s));
     // dWx
     if (z.tokens) {
-        RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta, s));
+        // the logits buffer is dead by now and serves as scratch for per-range partial rows
+        const bool chunked = N >= 2048;
+        RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta,
+                                  chunked ? Z : nullptr, (size_t)N * O,
+                                  chunked ? at<int32_t>(ws, pl.seen) : nullptr, s));
     } else {
         GemmArgs g{};
         g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;

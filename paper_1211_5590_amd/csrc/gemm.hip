@@ -35,10 +35,6 @@ struct GemmParams {
     int beta;
     int splits;
     int tiles_m, tiles_n;
-    int epi, act;
-    const float* e0;
-    const float* e1;
-    const int32_t* ids;
 };
 
 // One operand tile of R rows (R = BM or BN) by BK columns of K, fetched into registers.
@@ -214,24 +210,13 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
             const int col = n0 + wn * (BN / 2) + 32 * j + lane % 32;
             if (col >= p.N) continue;
             const float bias = (final_out && p.bias_n) ? p.bias_n[col] : 0.f;
-            const float tok_bias = (p.epi == GEMM_EPI_REC_FWD && p.ids) ? p.e1[col] : 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = m0 + wm * (BM / 2) + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
                 if (row < p.M) {
                     float* dst = Cout + (size_t)row * p.ldc + col;
                     float v = acc[i][j][e] + bias;
-                    if (p.epi == GEMM_EPI_REC_FWD) {
-                        const float in = p.ids ? p.e0[(size_t)p.ids[row] * p.N + col] + tok_bias
-                                               : p.e0[(size_t)row * p.N + col];
-                        v = p.act == 0 ? activate<0>(v + in) : activate<1>(v + in);
-                    } else if (p.epi == GEMM_EPI_REC_BWD) {
-                        const float g = p.e0[(size_t)row * p.N + col];
-                        const float h = p.e1[(size_t)row * p.N + col];
-                        v = (v + g) * (p.act == 0 ? act_grad<0>(h) : act_grad<1>(h));
-                    } else if (final_out && p.beta) {
-                        v += *dst;
-                    }
+                    if (final_out && p.beta) v += *dst;
                     *dst = v;
                 }
             }
@@ -282,8 +267,7 @@ SplitPlan plan_split(int M, int N, int K) {
 template <int BM, int BN, bool AT, bool BT, bool VEC>
 hipError_t launch_variant(const GemmParams& p, hipStream_t s) {
     dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
-    ProfileScope ps(p.epi == GEMM_EPI_REC_FWD ? K_REC_FWD : p.epi == GEMM_EPI_REC_BWD ? K_REC_BWD
-                    : AT ? (BT ? K_GEMM_TT : K_GEMM_TN) : (BT ? K_GEMM_NT : K_GEMM_NN), s);
+    ProfileScope ps(AT ? (BT ? K_GEMM_TT : K_GEMM_TN) : (BT ? K_GEMM_NT : K_GEMM_NN), s);
     hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, AT, BT, VEC>), grid, dim3(NT), 0, s, p);
     return hipGetLastError();
 }
@@ -299,11 +283,9 @@ size_t gemm_splitk_floats(int M, int N, int K) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
-    const bool small = g.epi != GEMM_EPI_PLAIN;  // per-step products: 64x64 tiles, no split-K
-    SplitPlan sp = plan_split(g.M, g.N, g.K);
-    if (small) { sp.splits = 1; sp.kchunk = (g.K + BK - 1) / BK * BK; }
+    const SplitPlan sp = plan_split(g.M, g.N, g.K);
     if (sp.splits > 1 && !g.splitk_ws) return hipErrorInvalidValue;
-    const int bm = small ? 64 : BM_, bn = small ? 64 : BN_;
+    const int bm = BM_, bn = BN_;
 
     GemmParams p;
     p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
@@ -312,7 +294,6 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     p.kchunk = sp.kchunk; p.beta = g.beta; p.splits = sp.splits;
     p.tiles_m = (g.M + bm - 1) / bm;
     p.tiles_n = (g.N + bn - 1) / bn;
-    p.epi = g.epi; p.act = g.act; p.e0 = g.e0; p.e1 = g.e1; p.ids = g.ids;
     if (sp.splits > 1) { p.C = g.splitk_ws; p.ldc = g.N; } else { p.C = g.C; p.ldc = g.ldc; }
 
     // float4 global loads need 16-byte aligned bases, leading dimensions that are multiples
@@ -321,11 +302,8 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     const bool vec = aligned16(g.A) && aligned16(g.B) && g.lda % 4 == 0 && g.ldb % 4 == 0;
 
     hipError_t e;
-#define RNN_GEMM_DISPATCH(AT, BT)                                                          \
-    e = small ? (vec ? launch_variant<64, 64, AT, BT, true>(p, s)                          \
-                     : launch_variant<64, 64, AT, BT, false>(p, s))                        \
-              : (vec ? launch_variant<BM_, BN_, AT, BT, true>(p, s)                        \
-                     : launch_variant<BM_, BN_, AT, BT, false>(p, s))
+#define RNN_GEMM_DISPATCH(AT, BT)                                              \
+    e = vec ? launch_variant<BM_, BN_, AT, BT, true>(p, s) : launch_variant<BM_, BN_, AT, BT, false>(p, s)
     if (!g.a_t && !g.b_t) RNN_GEMM_DISPATCH(false, false);
     else if (g.a_t && !g.b_t) RNN_GEMM_DISPATCH(true, false);
     else if (!g.a_t && g.b_t) RNN_GEMM_DISPATCH(false, true);

@@ -21,17 +21,7 @@ struct GemmArgs {
     const float* bias_n;  // nullable, length N
     int beta;             // 0 overwrite, 1 accumulate
     float* splitk_ws;     // nullable when gemm_splitk_floats == 0
-    // Fused epilogue of one time step of the batched recurrence (forces 64x64 tiles, no split-K):
-    //   GEMM_EPI_REC_FWD: C = act(acc + in)   in = e0[row,col] (dense input term, ld N) or, when
-    //                     ids != NULL, e0[ids[row]*N + col] + e1[col] (token rows of Wx plus bias)
-    //   GEMM_EPI_REC_BWD: C = (acc + e0[row,col]) * act'(e1[row,col])   (e0 = G_t, e1 = h_t)
-    int epi;
-    const float* e0;
-    const float* e1;
-    const int32_t* ids;
-    int act;
 };
-enum { GEMM_EPI_PLAIN = 0, GEMM_EPI_REC_FWD = 1, GEMM_EPI_REC_BWD = 2 };
 size_t gemm_splitk_floats(int M, int N, int K);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 
@@ -47,6 +37,7 @@ struct RecFwdArgs {
     float* hist;       // [T+1,B,H], or a 2-slot ring [2,B,H] when ring != 0
     float* h_last;     // nullable [B,H]
     int H, T, B, act, ring;
+    float* WhT;        // workspace for a transposed copy of Wh (stepwise path)
 };
 struct RecBwdArgs {
     const float* Wh;      // [H,H]
@@ -149,8 +140,10 @@ hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // Token-keyed gradient of the input matrix and id validation
+// scratch (>= scratch_floats floats) and seen_flags (>= 32*NV ints) enable the chunked form
 hipError_t launch_dwx_tokens(const int32_t* x, const float* Delta, float* dWx, int N, int NV,
-                             int H, int beta, hipStream_t s);
+                             int H, int beta, float* scratch, size_t scratch_floats,
+                             int32_t* seen_flags, hipStream_t s);
 hipError_t launch_check_tokens(const int32_t* ids, int64_t n, int32_t limit, int32_t* bad,
                                hipStream_t s);
 

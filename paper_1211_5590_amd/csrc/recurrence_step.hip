@@ -1,11 +1,22 @@
-// Batched recurrence (batch > 4) as one fused MFMA launch per time step.
+// Batched recurrence for hidden sizes whose matrix does not fit one CU's registers (batch > 4,
+// H > 256): one fused matrix-core launch per time step.
 //
-// With a batch the per-step product is a small GEMM (B x H x H); the kernel boundary is the
-// cheapest device-wide synchronisation measured on this part (a few microseconds, less than
-// an in-kernel release/acquire exchange between XCDs), so every step is one launch of the
-// 64x64-tile GEMM whose epilogue applies the input term and activation (forward) or the
-// output-layer term and activation derivative (reverse) -- the element-wise work stays fused
-// into the producing kernel, and the host still does nothing between steps but enqueue.
+// With a batch the per-step product is a small GEMM (B x H x H).  The kernel boundary is the
+// cheapest device-wide synchronisation measured on this part (a few microseconds -- less than
+// an in-kernel release/acquire exchange between XCDs, which has to write back and invalidate
+// whole L2s), so every step is one launch; its epilogue applies the input term and activation
+// (forward) or the output-layer term and activation derivative (reverse), so the element-wise
+// work stays fused into the producing kernel and the host does nothing between steps but
+// enqueue.
+//
+// Tiling of a step: a workgroup of 4 wavefronts owns 64 batch rows x 16 output columns (for
+// the 64 x 1024 x 1024 step that is 64 workgroups, each streaming its 64 KB slice of Wh and the
+// 256 KB state through LDS in K-chunks of 64, double buffered; the forward loop uses a
+// transposed copy of Wh made once per call so that both directions read the matrix as [k][n]
+// and neighbouring workgroups touch neighbouring bytes); wavefront w owns rows
+// 16w..16w+15 as one v_mfma_f32_16x16x4_f32 accumulator pair.  Inside a chunk K is walked in
+// a permuted order (lane group g takes k in [16g, 16g+16)), so a lane's 16 A and 16 B operands
+// are 64 contiguous bytes of LDS each.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -13,16 +24,149 @@
 namespace rnn {
 namespace {
 
-// dst[0:n) = src ? src : 0, and optionally a second copy
-__global__ __launch_bounds__(256) void copy_or_zero_kernel(const float* __restrict__ src,
-                                                           float* __restrict__ dst,
-                                                           float* __restrict__ dst2, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (size_t)gridDim.x * blockDim.x) {
-        const float v = src ? src[i] : 0.f;
-        dst[i] = v;
-        if (dst2) dst2[i] = v;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int SM = 64, SN = 16, SK = 64, SLD = SK + 4, NT = 256;
+
+struct StepArgs {
+    const float* A;      // [M,H] previous state (forward) or delta_{t+1} (reverse)
+    const float* Wm;     // [H(k),H(n)] matrix of the product: Wh^T (forward) or Wh (reverse)
+    float* C;            // [M,H] new state / delta_t
+    const float* e0;     // forward: input term rows [M,H], or Wx when ids != NULL; reverse: G_t
+    const float* e1;     // forward with ids: bias b; reverse: h_t
+    const int32_t* ids;  // forward token input: ids of the M rows, else NULL
+    int M, H;
+};
+
+template <int ACT, bool BWD, bool VEC>
+__global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
+    __shared__ __attribute__((aligned(16))) float As[2][SM][SLD];
+    __shared__ __attribute__((aligned(16))) float Bs[2][SN][SLD];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int g = lane / 16, nn = lane % 16;
+    const int n0 = blockIdx.x * SN, m0 = blockIdx.y * SM;
+    const int H = p.H, M = p.M;
+    const int nk = (H + SK - 1) / SK;
+
+    float4 ra[4], rb;
+    auto load4 = [&](const float* base, int k, int klim) -> float4 {  // 4 floats along k
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (VEC && k + 3 < klim) return *reinterpret_cast<const float4*>(base + k);
+        if (k + 0 < klim) t.x = base[k + 0];
+        if (k + 1 < klim) t.y = base[k + 1];
+        if (k + 2 < klim) t.z = base[k + 2];
+        if (k + 3 < klim) t.w = base[k + 3];
+        return t;
+    };
+    auto fetch = [&](int kc) {
+        const int k0 = kc * SK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + NT * i, r = idx / 16, kq = (idx % 16) * 4;
+            ra[i] = (m0 + r < M) ? load4(p.A + (size_t)(m0 + r) * H, k0 + kq, H)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        {   // Bs[n][k] = Wm[k0+k][n0+n]: 4 consecutive n of one k; neighbouring workgroups read
+            // neighbouring 64-byte pieces of the same matrix rows
+            const int k = tid / 4, nq = (tid % 4) * 4;
+            rb = (k0 + k < H) ? load4(p.Wm + (size_t)(k0 + k) * H, n0 + nq, H)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto park = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + NT * i, r = idx / 16, kq = (idx % 16) * 4;
+            *reinterpret_cast<float4*>(&As[buf][r][kq]) = ra[i];
+        }
+        const int k = tid / 4, nq = (tid % 4) * 4;
+        Bs[buf][nq + 0][k] = rb.x;
+        Bs[buf][nq + 1][k] = rb.y;
+        Bs[buf][nq + 2][k] = rb.z;
+        Bs[buf][nq + 3][k] = rb.w;
+    };
+
+    // Epilogue operands do not depend on the product: request them before the K loop so their
+    // latency (two dependent loads for token input) is hidden behind it.
+    const int col = n0 + nn;
+    float x0[4], x1[4];
+    {
+        const int cc = min(col, H - 1);
+        int rr[4], id[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rr[i] = min(m0 + 16 * wave + 4 * g + i, M - 1);
+        if (!BWD && p.ids) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) id[i] = p.ids[rr[i]];
+            const float tb = p.e1[cc];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { x0[i] = p.e0[(size_t)id[i] * H + cc] + tb; x1[i] = 0.f; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x0[i] = p.e0[(size_t)rr[i] * H + cc];
+                x1[i] = BWD ? p.e1[(size_t)rr[i] * H + cc] : 0.f;
+            }
+        }
     }
+
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    fetch(0);
+    park(0);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+        const int cur = kc & 1;
+        if (kc + 1 < nk) fetch(kc + 1);
+        float a[16], b[16];
+        const float4* pa = reinterpret_cast<const float4*>(&As[cur][16 * wave + nn][16 * g]);
+        const float4* pb = reinterpret_cast<const float4*>(&Bs[cur][nn][16 * g]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 va = pa[i], vb = pb[i];
+            a[4 * i] = va.x; a[4 * i + 1] = va.y; a[4 * i + 2] = va.z; a[4 * i + 3] = va.w;
+            b[4 * i] = vb.x; b[4 * i + 1] = vb.y; b[4 * i + 2] = vb.z; b[4 * i + 3] = vb.w;
+        }
+#pragma unroll
+        for (int s = 0; s < 16; s += 2) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[s], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s + 1], b[s + 1], acc1, 0, 0, 0);
+        }
+        if (kc + 1 < nk) park(cur ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = m0 + 16 * wave + 4 * g + i;
+        if (row >= M || col >= H) continue;
+        const float v = acc0[i] + acc1[i];
+        const float out = BWD ? (v + x0[i]) * act_grad<ACT>(x1[i]) : activate<ACT>(v + x0[i]);
+        p.C[(size_t)row * H + col] = out;
+    }
+}
+
+template <bool BWD>
+hipError_t launch_step(const StepArgs& p, int act, hipStream_t s) {
+    dim3 grid((p.H + SN - 1) / SN, (p.M + SM - 1) / SM);
+    const bool vec = p.H % 4 == 0 && (reinterpret_cast<uintptr_t>(p.A) & 15u) == 0 &&
+                     (reinterpret_cast<uintptr_t>(p.Wm) & 15u) == 0;
+    ProfileScope ps(BWD ? K_REC_BWD : K_REC_FWD, s);
+    if (act == 0) {
+        if (vec) hipLaunchKernelGGL((rec_step_kernel<0, BWD, true>), grid, dim3(NT), 0, s, p);
+        else hipLaunchKernelGGL((rec_step_kernel<0, BWD, false>), grid, dim3(NT), 0, s, p);
+    } else {
+        if (vec) hipLaunchKernelGGL((rec_step_kernel<1, BWD, true>), grid, dim3(NT), 0, s, p);
+        else hipLaunchKernelGGL((rec_step_kernel<1, BWD, false>), grid, dim3(NT), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+// dst[0:n) = src ? src : 0
+__global__ __launch_bounds__(256) void copy_or_zero_kernel(const float* __restrict__ src,
+                                                           float* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src ? src[i] : 0.f;
 }
 
 // delta_{T-1} = (G_{T-1} + dh_last) * act'(h_{T-1})
@@ -46,35 +190,37 @@ int blocks_for(size_t n) {
 
 hipError_t run_rec_fwd_stepwise(const RecFwdArgs& a, hipStream_t s) {
     const size_t bh = (size_t)a.B * a.H;
+    // one transposed copy per call: both directions then stream the matrix in the same
+    // channel-friendly [k][n] order
+    {
+        hipError_t e = launch_transpose(a.Wh, a.WhT, a.H, a.H, s);
+        if (e != hipSuccess) return e;
+    }
     {
         ProfileScope ps(K_MISC, s);
-        hipLaunchKernelGGL(copy_or_zero_kernel, dim3(blocks_for(bh)), dim3(256), 0, s, a.h0, a.hist,
-                           (float*)nullptr, bh);
+        hipLaunchKernelGGL(copy_or_zero_kernel, dim3(blocks_for(bh)), dim3(256), 0, s, a.h0, a.hist, bh);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     for (int t = 0; t < a.T; ++t) {
         const size_t in_slot = a.ring ? (size_t)(t & 1) : (size_t)t;
         const size_t out_slot = a.ring ? (size_t)((t + 1) & 1) : (size_t)(t + 1);
-        GemmArgs g{};
-        g.A = a.hist + in_slot * bh; g.B = a.Wh; g.C = a.hist + out_slot * bh;
-        g.M = a.B; g.N = a.H; g.K = a.H;
-        g.lda = a.H; g.ldb = a.H; g.ldc = a.H;
-        g.a_t = false; g.b_t = true;  // h_{t-1} Wh^T
-        g.epi = GEMM_EPI_REC_FWD; g.act = a.act;
+        StepArgs p{};
+        p.A = a.hist + in_slot * bh; p.Wm = a.WhT; p.C = a.hist + out_slot * bh;
+        p.M = a.B; p.H = a.H;
         if (a.U) {
-            g.e0 = a.U + (size_t)t * bh;
+            p.e0 = a.U + (size_t)t * bh;
         } else {
-            g.e0 = a.Wx; g.e1 = a.b; g.ids = a.x + (size_t)t * a.B;
+            p.e0 = a.Wx; p.e1 = a.b; p.ids = a.x + (size_t)t * a.B;
         }
-        hipError_t e = launch_gemm(g, s);
+        hipError_t e = launch_step<false>(p, a.act, s);
         if (e != hipSuccess) return e;
     }
     if (a.h_last) {
         const size_t last = a.ring ? (size_t)(a.T & 1) : (size_t)a.T;
         ProfileScope ps(K_MISC, s);
         hipLaunchKernelGGL(copy_or_zero_kernel, dim3(blocks_for(bh)), dim3(256), 0, s,
-                           (const float*)(a.hist + last * bh), a.h_last, (float*)nullptr, bh);
+                           (const float*)(a.hist + last * bh), a.h_last, bh);
         return hipGetLastError();
     }
     return hipSuccess;
@@ -91,15 +237,12 @@ hipError_t run_rec_bwd_stepwise(const RecBwdArgs& a, hipStream_t s) {
         if (e != hipSuccess) return e;
     }
     for (int t = a.T - 2; t >= 0; --t) {
-        GemmArgs g{};
-        g.A = a.Delta + (size_t)(t + 1) * bh; g.B = a.Wh; g.C = a.Delta + (size_t)t * bh;
-        g.M = a.B; g.N = a.H; g.K = a.H;
-        g.lda = a.H; g.ldb = a.H; g.ldc = a.H;
-        g.a_t = false; g.b_t = false;  // delta_{t+1} Wh
-        g.epi = GEMM_EPI_REC_BWD; g.act = a.act;
-        g.e0 = a.G + (size_t)t * bh;
-        g.e1 = a.h_all + (size_t)(t + 1) * bh;
-        hipError_t e = launch_gemm(g, s);
+        StepArgs p{};
+        p.A = a.Delta + (size_t)(t + 1) * bh; p.Wm = a.Wh; p.C = a.Delta + (size_t)t * bh;
+        p.M = a.B; p.H = a.H;
+        p.e0 = a.G + (size_t)t * bh;
+        p.e1 = a.h_all + (size_t)(t + 1) * bh;
+        hipError_t e = launch_step<true>(p, a.act, s);
         if (e != hipSuccess) return e;
     }
     if (a.dh0) {  // dh0 = delta_0 Wh
@@ -108,7 +251,7 @@ hipError_t run_rec_bwd_stepwise(const RecBwdArgs& a, hipStream_t s) {
         g.M = a.B; g.N = a.H; g.K = a.H;
         g.lda = a.H; g.ldb = a.H; g.ldc = a.H;
         g.a_t = false; g.b_t = false;
-        g.epi = GEMM_EPI_PLAIN; g.splitk_ws = a.splitk_ws;
+        g.splitk_ws = a.splitk_ws;
         return launch_gemm(g, s);
     }
     return hipSuccess;

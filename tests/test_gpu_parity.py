@@ -34,6 +34,7 @@ SMALL_CASES = {
     "dense_batched_stepwise": (48, 160, 40, 12, 40, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True)),
     "lm_batched_wide_stepwise": (300, 320, 300, 5, 24, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
     "lm_batched_ragged_mfma": (150, 100, 150, 7, 21, dict(LM, wdist=("normal", 0.2), bias_std=0.2, with_h0=True, with_dh_last=True)),
+    "lm_long_id_list_chunked_scatter": (500, 64, 500, 128, 20, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_hidden_500": (700, 500, 700, 12, 1, dict(LM, wdist=("uniform", 0.05))),
     "lm_batched_mfma_shape": (512, 256, 512, 6, 32, dict(LM, wdist=("normal_fan", None), with_h0=True)),
