@@ -72,6 +72,8 @@ class Workload:
         self.G = rnn.Grads(*[self.g["d" + k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])
         self.x_stride = self.x[0].numel() * self.x.element_size() * self.T
         self.y_stride = self.y[0].numel() * self.y.element_size() * self.T
+        case["_name"] = name
+        case["_variant"] = rnn.rnn_recurrence_variant(self.dims)
         self.tokens_per_step = self.T * self.B * self.windows
         self.timesteps_per_step = self.T * self.windows
 
@@ -123,46 +125,82 @@ class Workload:
 
 def algorithmic_work(kernel, c):
     """Algorithmic (bytes, flops) of ONE launch of `kernel` for configuration dict `c`: what the
-    method must move/compute, not what the implementation happens to move."""
+    method must move/compute (operands read once, results written once), not what the
+    implementation happens to move.  None for bookkeeping kernels."""
     N, H, O, I = c["seq_len"] * c["batch"], c["hidden"], c["out_dim"], c["in_dim"]
     T, B = c["seq_len"], c["batch"]
     f = 4
+    tokens = c["input_kind"] == 0
     table = {
-        "gemm_nn": (f * (N * H + H * O + N * O), 2.0 * N * H * O),           # Z = Hs V + c
-        "gemm_tn": (f * (N * H + N * O + H * O), 2.0 * N * H * O),           # dV = Hs^T dZ (largest TN)
-        "gemm_nt": (f * (N * O + H * O + N * H), 2.0 * N * H * O),           # G = dZ V^T
+        # hoisted matrix-matrix products
+        "gemm_logits": (f * (N * H + H * O + N * O), 2.0 * N * H * O),      # Z = Hs V + c
+        "gemm_dV": (f * (N * H + N * O + H * O), 2.0 * N * H * O),          # dV = Hs^T dZ
+        "gemm_G": (f * (N * O + H * O + N * H), 2.0 * N * H * O),           # G = dZ V^T
+        "gemm_dWh": (f * (2 * N * H + H * H), 2.0 * N * H * H),             # dWh = Delta^T Hprev
+        "gemm_U": (f * (N * I + H * I + N * H), 2.0 * N * H * I),           # U = X Wx^T + b
+        "gemm_dWx": (f * (N * H + N * I + H * I), 2.0 * N * H * I),         # dWx = Delta^T X
+        # element-wise / row-wise passes over the logits
         "ce_row_stats": (f * N * O, 3.0 * N * O),
-        "dz": (2 * f * N * O, 3.0 * N * O),
+        "mse_row_loss": (2 * f * N * O, 3.0 * N * O),
+        "dz": ((3 if not c["loss_kind"] == 0 else 2) * f * N * O, 3.0 * N * O),
         "dwx_tokens": (f * (N * H + I * H), 1.0 * N * H),
-        "rec_fwd": (f * (H * H + 2 * N * H), 2.0 * N * H * H),               # Wh once + in/out rows
-        "rec_bwd": (f * (H * H + 3 * N * H), 2.0 * N * H * H),
+        # time loops: the recurrent matrix once per launch, one state row in and out per step
+        "rec_fwd": None, "rec_bwd": None,
+        # short-sequence output layer (column strips)
         "skinny_logits": (f * (H * O + N * O + N * H), 2.0 * N * H * O),
-        "skinny_back": (f * (2 * H * O + N * O + I * H), 4.0 * N * H * O),
-        "skinny_reverse": (f * (H * H + 3 * N * H), 2.0 * N * H * H),
+        "skinny_back": (f * (H * O + H * O + N * O + I * H), 4.0 * N * H * O),   # V in, dV out, Z in, dWx zero fill
     }
+    variant = c.get("_variant", "")
+    if variant == "step_mfma":      # one launch = one step: matrix + state in, state out
+        table["rec_fwd"] = (f * (H * H + 3 * B * H), 2.0 * B * H * H)
+        table["rec_bwd"] = (f * (H * H + 4 * B * H), 2.0 * B * H * H)
+    else:                           # one launch = all T steps
+        table["rec_fwd"] = (f * (H * H + 2 * N * H + (0 if tokens else N * H)), 2.0 * N * H * H)
+        table["rec_bwd"] = (f * (H * H + 3 * N * H), 2.0 * N * H * H)
     return table.get(kernel)
 
 
+RIDGE = FP32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte
+
+
+def roofline_entry(name, prof, case):
+    work = algorithmic_work(name, case)
+    us = prof[name]["avg_us"]
+    if work is None:
+        return dict(kernel=name, bound=None, achieved=None, peak=None, unit=None, frac=None,
+                    traffic=None, avg_us=us)
+    nbytes, flops = work
+    sec = us * 1e-6
+    if flops / nbytes >= RIDGE:   # dense contraction above the ridge point: matrix-core bound
+        ach = flops / sec / 1e12
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=FP32_MFMA_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=None, avg_us=us,
+                    algorithmic_flops=flops)
+    ach = nbytes / sec / 1e9
+    return dict(kernel=name, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
+                frac=ach / HBM_PEAK_GBS, traffic=None, avg_us=us, algorithmic_bytes=nbytes)
+
+
 def roofline_of(prof, case):
-    """Roofline entry of the dominant kernel (largest total time in the profile pass)."""
+    """Roofline entry of the dominant kernel (largest total time in the profile pass), with the
+    counter-measured HBM traffic per launch when profiles/hbm_traffic.json has it."""
     if not prof:
         return None
     name = max(prof, key=lambda k: prof[k]["total_ms"])
-    work = algorithmic_work(name, case)
-    if work is None:
-        return dict(kernel=name, bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=None,
-                    traffic=None, avg_us=prof[name]["avg_us"])
-    nbytes, flops = work
-    sec = prof[name]["avg_us"] * 1e-6
-    ai = flops / nbytes
-    if ai >= FP32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and name.startswith("gemm"):
-        ach = flops / sec / 1e12
-        return dict(kernel=name, bound="mfma", achieved=ach, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=None, avg_us=prof[name]["avg_us"])
-    ach = nbytes / sec / 1e9
-    return dict(kernel=name, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=ach / HBM_PEAK_GBS, traffic=None, avg_us=prof[name]["avg_us"],
-                algorithmic_bytes=nbytes)
+    r = roofline_entry(name, prof, case)
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            t = json.load(fh).get(case.get("_name", ""), {}).get(name)
+        if t:
+            r["traffic"] = t["bytes_per_launch"]
+    except (OSError, ValueError):
+        pass
+    return r
+
+
+def all_rooflines(prof, case):
+    return [roofline_entry(k, prof, case) for k in sorted(prof, key=lambda k: -prof[k]["total_ms"])
+            if algorithmic_work(k, case) is not None]
 
 
 def cpu_baseline(name, budget_s):
@@ -245,6 +283,7 @@ def main():
         "timesteps_per_s": wl.timesteps_per_step * steps / wall,
         "gpu_event_ms_per_step": 1e3 * gpu_s / steps,
         "roofline": roofline_of(prof, wl.case),
+        "rooflines_all_kernels": all_rooflines(prof, wl.case),
         "kernels": {k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3),
                             total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
     }

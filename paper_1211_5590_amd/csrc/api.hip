@@ -5,6 +5,7 @@
 #include "../../include/rnn.h"
 
 #include "internal.hpp"
+#include "prof.hpp"
 
 namespace {
 
@@ -175,7 +176,7 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         g.A = static_cast<const float*>(x); g.B = P->Wx; g.C = at<float>(ws, pl.U);
         g.M = (int)z.N; g.N = z.H; g.K = z.NVin;
         g.lda = z.NVin; g.ldb = z.NVin; g.ldc = z.H;
-        g.a_t = false; g.b_t = true; g.bias_n = P->b; g.beta = 0;
+        g.a_t = false; g.b_t = true; g.bias_n = P->b; g.beta = 0; g.prof_id = K_GEMM_U;
         g.splitk_ws = at<float>(ws, pl.splitk);
         RNN_TRY(launch_gemm(g, s));
         a.x = nullptr;
@@ -232,7 +233,7 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
     g.B = P->V; g.C = Z;
     g.M = N; g.N = z.O; g.K = z.H;
     g.lda = z.H; g.ldb = z.O; g.ldc = z.O;
-    g.a_t = false; g.b_t = false; g.bias_n = P->c; g.beta = 0;
+    g.a_t = false; g.b_t = false; g.bias_n = P->c; g.beta = 0; g.prof_id = K_GEMM_LOGITS;
     g.splitk_ws = at<float>(ws, pl.splitk);
     RNN_TRY(launch_gemm(g, s));
     float* rowloss = at<float>(ws, pl.rowloss);
@@ -290,7 +291,7 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         g.A = Hs; g.B = Z; g.C = Gr->dV;
         g.M = H; g.N = O; g.K = N;
         g.lda = H; g.ldb = O; g.ldc = O;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DV;
         RNN_TRY(launch_gemm(g, s));
     }
     // G = dZ V^T
@@ -299,7 +300,7 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         g.A = Z; g.B = P->V; g.C = G;
         g.M = N; g.N = H; g.K = O;
         g.lda = O; g.ldb = O; g.ldc = H;
-        g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk;
+        g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk; g.prof_id = K_GEMM_G;
         RNN_TRY(launch_gemm(g, s));
     }
     // reverse-time loop
@@ -331,7 +332,7 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         g.A = Delta; g.B = h_all; g.C = Gr->dWh;
         g.M = H; g.N = H; g.K = N;
         g.lda = H; g.ldb = H; g.ldc = H;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWH;
         RNN_TRY(launch_gemm(g, s));
     }
     // db = column sums of Delta
@@ -349,7 +350,7 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;
         g.M = H; g.N = z.NVin; g.K = N;
         g.lda = H; g.ldb = z.NVin; g.ldc = z.NVin;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWX;
         RNN_TRY(launch_gemm(g, s));
     }
     return hipSuccess;

@@ -35,6 +35,7 @@ struct GemmParams {
     int beta;
     int splits;
     int tiles_m, tiles_n;
+    int prof_id;
 };
 
 // One operand tile of R rows (R = BM or BN) by BK columns of K, fetched into registers.
@@ -267,7 +268,7 @@ SplitPlan plan_split(int M, int N, int K) {
 template <int BM, int BN, bool AT, bool BT, bool VEC>
 hipError_t launch_variant(const GemmParams& p, hipStream_t s) {
     dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
-    ProfileScope ps(AT ? (BT ? K_GEMM_TT : K_GEMM_TN) : (BT ? K_GEMM_NT : K_GEMM_NN), s);
+    ProfileScope ps(p.prof_id, s);
     hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, AT, BT, VEC>), grid, dim3(NT), 0, s, p);
     return hipGetLastError();
 }
@@ -291,7 +292,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.lda = g.lda; p.ldb = g.ldb;
-    p.kchunk = sp.kchunk; p.beta = g.beta; p.splits = sp.splits;
+    p.kchunk = sp.kchunk; p.beta = g.beta; p.splits = sp.splits; p.prof_id = g.prof_id;
     p.tiles_m = (g.M + bm - 1) / bm;
     p.tiles_n = (g.N + bn - 1) / bn;
     if (sp.splits > 1) { p.C = g.splitk_ws; p.ldc = g.N; } else { p.C = g.C; p.ldc = g.ldc; }

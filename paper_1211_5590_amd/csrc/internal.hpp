@@ -21,6 +21,7 @@ struct GemmArgs {
     const float* bias_n;  // nullable, length N
     int beta;             // 0 overwrite, 1 accumulate
     float* splitk_ws;     // nullable when gemm_splitk_floats == 0
+    int prof_id;          // kernel id under which the profiler books this product (prof.hpp)
 };
 size_t gemm_splitk_floats(int M, int N, int K);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);

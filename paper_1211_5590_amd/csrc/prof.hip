@@ -24,7 +24,8 @@ hipEvent_t take_event() {
     return e;
 }
 const char* const kNames[K_COUNT] = {
-    "gemm_nn", "gemm_tn", "gemm_nt", "gemm_tt", "splitk_reduce", "transpose",
+    "gemm_logits", "gemm_dV", "gemm_G", "gemm_dWh", "gemm_U", "gemm_dWx", "gemm_dh0",
+    "splitk_reduce", "transpose",
     "rec_fwd", "rec_bwd", "ce_row_stats", "mse_row_loss", "loss_reduce", "dz",
     "colsum_partial", "colsum_finish", "dwx_tokens", "check_tokens",
     "skinny_logits", "skinny_back", "skinny_reverse", "misc"};

@@ -8,7 +8,8 @@
 namespace rnn {
 
 enum KernelId : int {
-    K_GEMM_NN = 0, K_GEMM_TN, K_GEMM_NT, K_GEMM_TT, K_SPLITK_REDUCE, K_TRANSPOSE,
+    K_GEMM_LOGITS = 0, K_GEMM_DV, K_GEMM_G, K_GEMM_DWH, K_GEMM_U, K_GEMM_DWX, K_GEMM_DH0,
+    K_SPLITK_REDUCE, K_TRANSPOSE,
     K_REC_FWD, K_REC_BWD, K_CE_ROW_STATS, K_MSE_ROW_LOSS, K_LOSS_REDUCE, K_DZ,
     K_COLSUM_PARTIAL, K_COLSUM_FINISH, K_DWX_TOKENS, K_CHECK_TOKENS,
     K_SKINNY_LOGITS, K_SKINNY_BACK, K_SKINNY_REVERSE, K_MISC,

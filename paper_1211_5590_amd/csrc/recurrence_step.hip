@@ -251,7 +251,7 @@ hipError_t run_rec_bwd_stepwise(const RecBwdArgs& a, hipStream_t s) {
         g.M = a.B; g.N = a.H; g.K = a.H;
         g.lda = a.H; g.ldb = a.H; g.ldc = a.H;
         g.a_t = false; g.b_t = false;
-        g.splitk_ws = a.splitk_ws;
+        g.splitk_ws = a.splitk_ws; g.prof_id = K_GEMM_DH0;
         return launch_gemm(g, s);
     }
     return hipSuccess;
