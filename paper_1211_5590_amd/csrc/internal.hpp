@@ -56,7 +56,7 @@ struct RecResArgs {
     const float* Wh;
     int H, T, B, act;
     int P, R, L, ldw, w_floats;  // filled from the plan by the launcher
-    int bI, bQ, bKC;             // reverse product: lanes per k-range, k-ranges, k per range
+    int nq4, hpad;               // float4 per lane of a row, zero-padded row/vector length
     int32_t* flags;              // [B][P] step counters in the workspace (P > 1)
     int32_t* status;             // device status word: set to 1 when a bounded wait expires
     int spin_limit;              // <= 0: default
@@ -70,7 +70,7 @@ struct RecResArgs {
     // per-strip partial G [strips][T*B][H] to be summed into Gw before the loop (nullable)
     const float* gpart; int gstrips; float* Gw;
 };
-struct RecResPlan { int P, R, L, ldw, w_floats, bI, bQ, bKC; size_t smem; };
+struct RecResPlan { int P, R, L, ldw, w_floats, nq4, hpad; size_t smem; };
 bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan* out);
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s);
 

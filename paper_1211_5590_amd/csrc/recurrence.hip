@@ -8,13 +8,10 @@
 // epilogue, and the store of the new state.
 //
 // Work split: P workgroups per batch row, each owning R = ceil(H/P) outputs and holding the
-// matching slice of Wh in LDS for the whole launch (loaded once, always with coalesced global
-// reads and conflict-free LDS writes):
-//   forward  slice = rows of Wh, LDS layout [row][k]; a row's dot product is shared by L lanes
-//            that read row and state as float4 and combine with wavefront shuffles;
-//   reverse  slice = columns of Wh, LDS layout [k][column] (the natural layout again, so no
-//            transposed copy is ever made); a column is owned by one lane per k-range, the
-//            Q k-ranges combine through LDS.
+// matching slice of Wh (forward: rows; reverse: columns, transposed while loading) in LDS for
+// the whole launch as zero-padded rows [output][k].  An output's dot product is shared by L
+// adjacent lanes that read row and state as float4 (all reads in flight before the first
+// multiply-add) and combine with DPP lane permutations.
 // P = 1: the state lives in LDS and a step costs workgroup barriers that order LDS only.
 // P > 1: every workgroup stores its slice of the new state to global memory, publishes a
 // per-workgroup step counter with release semantics, waits (bounded) for the other P-1
@@ -82,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     const int tid = threadIdx.x;
     const int r0 = p * R;
     const int rows = max(0, min(R, H - r0));
-    const int H4 = (H + 3) / 4, Hp = H4 * 4;
+    const int Hp = a.hpad;                    // padded vector length: 4 * L * nq4 >= H
     const float invH = 1.0f / (float)H;
     // LDS carve-up
     float* W = smem;                          // forward [R][ldw]; reverse [H][ldw]
@@ -93,10 +90,6 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     float* Hl = Dl + T * H;
 
     // thread roles
-    // Layout of the resident slice: [output][k] with float4 reads for the forward loop and for
-    // the multi-workgroup reverse loop (long-running, so a one-off transposing load pays off);
-    // [k][output] for the single-workgroup reverse loop, whose launches are short.
-    const bool rowmajor = !BWD || P > 1;
     const int q = tid % L;                               // which share of the k range
     const int own = tid / L;                             // which output of the slice
     const bool lead = (q == 0) && own < rows;            // finishes output r0 + own
@@ -139,8 +132,42 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     if (tid == 0) s_abort = 0;
     if (BWD && a.fuse_post && tid < T) s_ids[tid] = a.x[tid];
 
-    // ---- weight slice into LDS ----------------------------------------------------------------
-    if (!BWD) {
+    // ---- weight slice: registers when a lane's share is at most 8 float4, else LDS -------------
+    // Weights never change during the launch, so the small-slice case keeps each lane's strip
+    // of its row in 32 VGPRs, loaded straight from global memory (no staging, no LDS traffic
+    // per step); larger slices stay in LDS as zero-padded rows.
+    const bool wreg_mode = a.nq4 <= 8;
+    float4 wreg[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) wreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (wreg_mode) {
+        if (own < rows) {
+            const int j = r0 + own;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = 4 * (q + u * L);
+                if (u < a.nq4 && k < H) {
+                    if (!BWD) {
+                        const float* src = a.Wh + (size_t)j * H + k;
+                        if ((H & 3) == 0) {
+                            wreg[u] = *reinterpret_cast<const float4*>(src);
+                        } else {
+                            wreg[u].x = src[0];
+                            if (k + 1 < H) wreg[u].y = src[1];
+                            if (k + 2 < H) wreg[u].z = src[2];
+                            if (k + 3 < H) wreg[u].w = src[3];
+                        }
+                    } else {  // column j of Wh
+                        const float* src = a.Wh + (size_t)k * H + j;
+                        wreg[u].x = src[0];
+                        if (k + 1 < H) wreg[u].y = src[(size_t)H];
+                        if (k + 2 < H) wreg[u].z = src[(size_t)2 * H];
+                        if (k + 3 < H) wreg[u].w = src[(size_t)3 * H];
+                    }
+                }
+            }
+        }
+    } else if (!BWD) {
         const int n = rows * H;  // rows r0.. are one contiguous block of Wh
         for (int base = tid; base < n; base += NL * kThreads) {
             float t[NL];
@@ -164,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                 const int r = i / padw;
                 W[r * ldw + H + (i - r * padw)] = 0.f;
             }
-    } else if (rowmajor) {
+    } else {
         const int n = H * rows;  // W[c][k] = Wh[k][r0 + c]: coalesced reads, transposing LDS writes
         const float invR = 1.0f / (float)(rows > 0 ? rows : 1);
         for (int base = tid; base < n; base += NL * kThreads) {
@@ -193,29 +220,6 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                 const int r = i / padw;
                 W[r * ldw + H + (i - r * padw)] = 0.f;
             }
-    } else {
-        const int n = H * rows;  // W[k][c] = Wh[k][r0 + c]; for P == 1 a plain copy
-        const float invR = 1.0f / (float)(rows > 0 ? rows : 1);
-        for (int base = tid; base < n; base += NL * kThreads) {
-            float t[NL];
-#pragma unroll
-            for (int u = 0; u < NL; ++u) {
-                const int i = base + u * kThreads;
-                t[u] = 0.f;
-                if (i < n) {
-                    const int k = fast_div(i, rows, invR);
-                    t[u] = a.Wh[(size_t)k * H + r0 + (i - k * rows)];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < NL; ++u) {
-                const int i = base + u * kThreads;
-                if (i < n) {
-                    const int k = fast_div(i, rows, invR);
-                    W[k * ldw + (i - k * rows)] = t[u];
-                }
-            }
-        }
     }
     for (int i = tid; i < 2 * Hp; i += kThreads) vbuf[i] = 0.f;
 
@@ -303,59 +307,72 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     __syncthreads();
 
     // One product of the resident slice with the vector v: every lane of an output's group gets
-    // the full sum.  LDS reads are issued eight at a time before the multiply-adds, so a step
-    // pays for one or two LDS round trips instead of one per element.
-    auto slice_dot = [&](const float* v) -> float {
+    // the full sum.  Rows and vector are zero padded to nq4 float4 per lane, so the common sizes
+    // (nq4 <= 8, weights in registers) run fully unrolled without predicates: all LDS reads of the
+    // state are issued before the first multiply-add, and a step pays for one LDS round trip.
+    const float4* w4 = reinterpret_cast<const float4*>(W + min(own, R - 1) * ldw) + q;
+    auto dot_fixed = [&](const float4* v4, auto count) -> float {
+        constexpr int U = decltype(count)::value;
+        float4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = v4[u * L];
         float acc0 = 0.f, acc1 = 0.f;
-        if (rowmajor) {
-            const float4* w4 = reinterpret_cast<const float4*>(W + min(own, R - 1) * ldw);
-            const float4* v4 = reinterpret_cast<const float4*>(v);
-            for (int c0 = q; c0 < H4; c0 += 8 * L) {
-                float4 w[8], x[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int c = c0 + u * L;
-                    const bool ok = c < H4;
-                    w[u] = ok ? w4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-                    x[u] = ok ? v4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
+        for (int u = 0; u < U; ++u) {
+            float& acc = (u & 1) ? acc1 : acc0;
+            acc = fmaf(wreg[u].x, x[u].x, acc);
+            acc = fmaf(wreg[u].y, x[u].y, acc);
+            acc = fmaf(wreg[u].z, x[u].z, acc);
+            acc = fmaf(wreg[u].w, x[u].w, acc);
+        }
+        return acc0 + acc1;
+    };
+    auto slice_dot = [&](const float* v) -> float {
+        const float4* v4 = reinterpret_cast<const float4*>(v) + q;
+        float acc;
+        switch (a.nq4) {
+            case 1: acc = dot_fixed(v4, std::integral_constant<int, 1>{}); break;
+            case 2: acc = dot_fixed(v4, std::integral_constant<int, 2>{}); break;
+            case 3: acc = dot_fixed(v4, std::integral_constant<int, 3>{}); break;
+            case 4: acc = dot_fixed(v4, std::integral_constant<int, 4>{}); break;
+            case 5: acc = dot_fixed(v4, std::integral_constant<int, 5>{}); break;
+            case 6: acc = dot_fixed(v4, std::integral_constant<int, 6>{}); break;
+            case 7: acc = dot_fixed(v4, std::integral_constant<int, 7>{}); break;
+            case 8: acc = dot_fixed(v4, std::integral_constant<int, 8>{}); break;
+            default: {  // long rows: batches of eight
+                acc = 0.f;
+                for (int u0 = 0; u0 < a.nq4; u0 += 8) {
+                    float4 w[8], x[8];
 #pragma unroll
-                for (int u = 0; u < 8; u += 2) {
-                    acc0 = fmaf(w[u].x, x[u].x, acc0);
-                    acc1 = fmaf(w[u + 1].x, x[u + 1].x, acc1);
-                    acc0 = fmaf(w[u].y, x[u].y, acc0);
-                    acc1 = fmaf(w[u + 1].y, x[u + 1].y, acc1);
-                    acc0 = fmaf(w[u].z, x[u].z, acc0);
-                    acc1 = fmaf(w[u + 1].z, x[u + 1].z, acc1);
-                    acc0 = fmaf(w[u].w, x[u].w, acc0);
-                    acc1 = fmaf(w[u + 1].w, x[u + 1].w, acc1);
-                }
-            }
-        } else {
-            // lane q of the group owns k in [q*KC, (q+1)*KC); column `own` of the slice
-            const int k0 = q * a.bKC, k1 = min(H, k0 + a.bKC);
-            const float* wc = W + min(own, R - 1);
-            for (int kb = k0; kb < k1; kb += 8) {
-                float w[8], x[8];
+                    for (int u = 0; u < 8; ++u) {
+                        const int uu = min(u0 + u, a.nq4 - 1);  // clamp: duplicates are masked below
+                        w[u] = w4[uu * L];
+                        x[u] = v4[uu * L];
+                    }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const bool ok = kb + u < k1;
-                    w[u] = ok ? wc[(kb + u) * ldw] : 0.f;
-                    x[u] = ok ? v[kb + u] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; u += 2) {
-                    acc0 = fmaf(w[u], x[u], acc0);
-                    acc1 = fmaf(w[u + 1], x[u + 1], acc1);
+                    for (int u = 0; u < 8; ++u) {
+                        if (u0 + u < a.nq4) {
+                            acc = fmaf(w[u].x, x[u].x, acc);
+                            acc = fmaf(w[u].y, x[u].y, acc);
+                            acc = fmaf(w[u].z, x[u].z, acc);
+                            acc = fmaf(w[u].w, x[u].w, acc);
+                        }
+                    }
                 }
             }
         }
-        return group_sum(acc0 + acc1, L);
+        return group_sum(acc, L);
     };
 
     // Steps.  forward: s = 0..T-1 computes h_s from h_{s-1}.  reverse: s = 0..T-2 computes
     // delta_t for t = T-2-s from delta_{t+1}.
     int cur = 0;
+    // destination row of the step's result: a pointer that is bumped, not recomputed
+    const ptrdiff_t out_stride = BWD ? -(ptrdiff_t)B * H : (ptrdiff_t)B * H;
+    float* out_ptr = BWD ? a.Delta + ((size_t)max(T - 2, 0) * B + bb) * H
+                         : a.hist + ((size_t)B + bb) * H;          // slot 1 = result of step 0
+    float* const out_even = BWD ? nullptr : a.hist + (size_t)bb * H;               // ring slot 0
+    float* const out_odd = BWD ? nullptr : a.hist + ((size_t)B + bb) * H;          // ring slot 1
     for (int s = 0; s < nsteps; ++s) {
         const int chunk = s / TC, su = s - chunk * TC;
         float* st = stash + (size_t)(chunk & 1) * TC * 2 * R;
@@ -370,8 +387,8 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         const float* v = vbuf + cur * Hp;
         float* vnext = vbuf + (cur ^ 1) * Hp;
         const int t = BWD ? T - 2 - s : s;
-        float* out_row = BWD ? a.Delta + ((size_t)t * B + bb) * H
-                             : a.hist + ((size_t)(a.ring ? ((s + 1) & 1) : (s + 1)) * B + bb) * H;
+        float* out_row = (!BWD && a.ring) ? ((s & 1) ? out_even : out_odd) : out_ptr;
+        out_ptr += out_stride;
         // one pass covers every output of the slice: each output has its own lane group
         {
             const int j = r0 + own;
@@ -518,7 +535,6 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
     if (B > 4 || H > 4096) return false;
     if (fuse_post && (B != 1 || T > kFuseMaxT || !bwd)) return false;
     constexpr size_t kLdsBudget = 150 * 1024;  // of 160 KB per CU
-    const int Hp = (H + 3) / 4 * 4;
     for (int P = 1; P <= 128; P *= 2) {
         if (P * B > 128) break;
         const int R = (H + P - 1) / P;
@@ -528,27 +544,15 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
         int L = pow2_floor(kThreads / R);  // lanes sharing one output; R * L <= kThreads
         if (L > 64) L = 64;
         pl.L = L;
-        size_t w_floats;
-        if (!bwd || P > 1) {
-            // rows of float4: lanes of a group read 4L consecutive words, groups should start
-            // 4L banks apart
-            int ldw = Hp;
-            if (L < 8) while (ldw % 32 != (4 * L) % 32) ldw += 4;
-            pl.ldw = ldw;
-            pl.bKC = 0;
-            w_floats = (size_t)R * ldw;
-        } else {
-            // [k][column] with scalar reads: a wavefront touches 64/L consecutive columns in L
-            // different k rows, which should start 64/L banks apart
-            int ldw = R;
-            if (L >= 2) while (ldw % 32 != (64 / L) % 32) ldw += 1;
-            pl.ldw = ldw;
-            pl.bKC = (H + L - 1) / L;
-            w_floats = (size_t)H * ldw;
-        }
-        pl.bI = 0; pl.bQ = 0;
-        w_floats = (w_floats + 3) / 4 * 4;  // keeps the state vectors 16-byte aligned
-        size_t floats = w_floats + 2 * (size_t)Hp + (size_t)2 * TC * 2 * R;
+        const int H4 = (H + 3) / 4;
+        pl.nq4 = (H4 + L - 1) / L;         // float4 per lane
+        pl.hpad = 4 * L * pl.nq4;          // zero-padded row / vector length
+        // lanes of a group read 4L consecutive words, so groups should start 4L banks apart
+        int ldw = pl.hpad;
+        if (L < 8) while (ldw % 32 != (4 * L) % 32) ldw += 4;
+        pl.ldw = ldw;
+        size_t w_floats = pl.nq4 <= 8 ? 0 : (size_t)R * ldw;   // small slices live in registers
+        size_t floats = w_floats + 2 * (size_t)pl.hpad + (size_t)2 * TC * 2 * R;
         if (fuse_post) floats += (size_t)3 * T * H;
         if (floats * 4 <= kLdsBudget) {
             pl.w_floats = (int)w_floats; pl.smem = floats * 4;
@@ -562,7 +566,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
 
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s) {
     a.P = pl.P; a.R = pl.R; a.L = pl.L; a.ldw = pl.ldw; a.w_floats = pl.w_floats;
-    a.bI = pl.bI; a.bQ = pl.bQ; a.bKC = pl.bKC;
+    a.nq4 = pl.nq4; a.hpad = pl.hpad;
     if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
     if (pl.P > 1) {
         hipError_t e = launch_zero_words(a.flags, pl.P * a.B, s);

@@ -9,14 +9,15 @@
 // work stays fused into the producing kernel and the host does nothing between steps but
 // enqueue.
 //
-// Tiling of a step: a workgroup of 4 wavefronts owns 64 batch rows x 16 output columns (for
-// the 64 x 1024 x 1024 step that is 64 workgroups, each streaming its 64 KB slice of Wh and the
-// 256 KB state through LDS in K-chunks of 64, double buffered; the forward loop uses a
+// Tiling of a step: a workgroup of 4 wavefronts owns 16 batch rows x 16 output columns (for
+// the 64 x 1024 x 1024 step that is 256 workgroups, one per CU, each streaming its 64 KB slice
+// of Wh and 64 KB of state through LDS in K-chunks of 128, double buffered (few, large chunks: every
+// chunk costs one L2 round trip that the little arithmetic of a chunk cannot hide); the forward loop uses a
 // transposed copy of Wh made once per call so that both directions read the matrix as [k][n]
-// and neighbouring workgroups touch neighbouring bytes); wavefront w owns rows
-// 16w..16w+15 as one v_mfma_f32_16x16x4_f32 accumulator pair.  Inside a chunk K is walked in
-// a permuted order (lane group g takes k in [16g, 16g+16)), so a lane's 16 A and 16 B operands
-// are 64 contiguous bytes of LDS each.
+// and neighbouring workgroups touch neighbouring bytes); a wavefront owns a quarter
+// of K as a v_mfma_f32_16x16x4_f32 accumulator pair; the halves meet in LDS.  Inside a chunk K is walked in
+// a permuted order (lane group g takes k in [32g, 32g+32)), so a lane's 32 A and 32 B operands
+// are 128 contiguous bytes of LDS each.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -26,7 +27,13 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int SM = 64, SN = 16, SK = 64, SLD = SK + 4, NT = 256;
+constexpr int SM = 16, SN = 16, SK = 128, SLD = SK + 4, NT = 256;
+constexpr int KG = SK / 4;                 // k per lane group inside a chunk
+constexpr int RT = SM / 16;                // 16-row tiles per workgroup
+constexpr int KSPL = 4 / RT;               // wavefronts sharing a row tile, each a slice of K
+constexpr int KW = KG / KSPL;              // k-steps per wavefront per chunk
+constexpr int NA4 = SM * SK / 4 / NT;      // float4 of the state chunk per thread (8)
+constexpr int NB4 = SN * SK / 4 / NT;      // float4 of the matrix chunk per thread (2)
 
 struct StepArgs {
     const float* A;      // [M,H] previous state (forward) or delta_{t+1} (reverse)
@@ -42,13 +49,15 @@ template <int ACT, bool BWD, bool VEC>
 __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
     __shared__ __attribute__((aligned(16))) float As[2][SM][SLD];
     __shared__ __attribute__((aligned(16))) float Bs[2][SN][SLD];
+    __shared__ float red[4][kWave][4];          // partial tiles of the kh > 0 wavefronts
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int g = lane / 16, nn = lane % 16;
+    const int rt = wave % RT, kh = wave / RT;  // row tile of 16, slice of each lane group's k range
     const int n0 = blockIdx.x * SN, m0 = blockIdx.y * SM;
     const int H = p.H, M = p.M;
     const int nk = (H + SK - 1) / SK;
 
-    float4 ra[4], rb;
+    float4 ra[NA4], rb[NB4];
     auto load4 = [&](const float* base, int k, int klim) -> float4 {  // 4 floats along k
         float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
         if (VEC && k + 3 < klim) return *reinterpret_cast<const float4*>(base + k);
@@ -61,29 +70,34 @@ __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
     auto fetch = [&](int kc) {
         const int k0 = kc * SK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + NT * i, r = idx / 16, kq = (idx % 16) * 4;
+        for (int i = 0; i < NA4; ++i) {
+            const int idx = tid + NT * i, r = idx / (SK / 4), kq = (idx % (SK / 4)) * 4;
             ra[i] = (m0 + r < M) ? load4(p.A + (size_t)(m0 + r) * H, k0 + kq, H)
                                  : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        {   // Bs[n][k] = Wm[k0+k][n0+n]: 4 consecutive n of one k; neighbouring workgroups read
-            // neighbouring 64-byte pieces of the same matrix rows
-            const int k = tid / 4, nq = (tid % 4) * 4;
-            rb = (k0 + k < H) ? load4(p.Wm + (size_t)(k0 + k) * H, n0 + nq, H)
-                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        // Bs[n][k] = Wm[k0+k][n0+n]: 4 consecutive n of one k; neighbouring workgroups read
+        // neighbouring 64-byte pieces of the same matrix rows
+#pragma unroll
+        for (int i = 0; i < NB4; ++i) {
+            const int idx = tid + NT * i, k = idx / 4, nq = (idx % 4) * 4;
+            rb[i] = (k0 + k < H) ? load4(p.Wm + (size_t)(k0 + k) * H, n0 + nq, H)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
     auto park = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + NT * i, r = idx / 16, kq = (idx % 16) * 4;
+        for (int i = 0; i < NA4; ++i) {
+            const int idx = tid + NT * i, r = idx / (SK / 4), kq = (idx % (SK / 4)) * 4;
             *reinterpret_cast<float4*>(&As[buf][r][kq]) = ra[i];
         }
-        const int k = tid / 4, nq = (tid % 4) * 4;
-        Bs[buf][nq + 0][k] = rb.x;
-        Bs[buf][nq + 1][k] = rb.y;
-        Bs[buf][nq + 2][k] = rb.z;
-        Bs[buf][nq + 3][k] = rb.w;
+#pragma unroll
+        for (int i = 0; i < NB4; ++i) {
+            const int idx = tid + NT * i, k = idx / 4, nq = (idx % 4) * 4;
+            Bs[buf][nq + 0][k] = rb[i].x;
+            Bs[buf][nq + 1][k] = rb[i].y;
+            Bs[buf][nq + 2][k] = rb[i].z;
+            Bs[buf][nq + 3][k] = rb[i].w;
+        }
     };
 
     // Epilogue operands do not depend on the product: request them before the K loop so their
@@ -94,7 +108,7 @@ __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
         const int cc = min(col, H - 1);
         int rr[4], id[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rr[i] = min(m0 + 16 * wave + 4 * g + i, M - 1);
+        for (int i = 0; i < 4; ++i) rr[i] = min(m0 + 16 * rt + 4 * g + i, M - 1);
         if (!BWD && p.ids) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) id[i] = p.ids[rr[i]];
@@ -117,17 +131,17 @@ __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
     for (int kc = 0; kc < nk; ++kc) {
         const int cur = kc & 1;
         if (kc + 1 < nk) fetch(kc + 1);
-        float a[16], b[16];
-        const float4* pa = reinterpret_cast<const float4*>(&As[cur][16 * wave + nn][16 * g]);
-        const float4* pb = reinterpret_cast<const float4*>(&Bs[cur][nn][16 * g]);
+        float a[KW], b[KW];
+        const float4* pa = reinterpret_cast<const float4*>(&As[cur][16 * rt + nn][KG * g + KW * kh]);
+        const float4* pb = reinterpret_cast<const float4*>(&Bs[cur][nn][KG * g + KW * kh]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < KW / 4; ++i) {
             const float4 va = pa[i], vb = pb[i];
             a[4 * i] = va.x; a[4 * i + 1] = va.y; a[4 * i + 2] = va.z; a[4 * i + 3] = va.w;
             b[4 * i] = vb.x; b[4 * i + 1] = vb.y; b[4 * i + 2] = vb.z; b[4 * i + 3] = vb.w;
         }
 #pragma unroll
-        for (int s = 0; s < 16; s += 2) {
+        for (int s = 0; s < KW; s += 2) {
             acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[s], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s + 1], b[s + 1], acc1, 0, 0, 0);
         }
@@ -135,11 +149,20 @@ __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
         __syncthreads();
     }
 
+    // the K slices of a row tile meet in LDS; the kh = 0 wavefront finishes the tile
+    if (kh > 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[wave][lane][i] = acc0[i] + acc1[i];
+    }
+    __syncthreads();
+    if (kh > 0) return;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = m0 + 16 * wave + 4 * g + i;
+        const int row = m0 + 16 * rt + 4 * g + i;
         if (row >= M || col >= H) continue;
-        const float v = acc0[i] + acc1[i];
+        float v = acc0[i] + acc1[i];
+#pragma unroll
+        for (int w = 1; w < KSPL; ++w) v += red[rt + RT * w][lane][i];
         const float out = BWD ? (v + x0[i]) * act_grad<ACT>(x1[i]) : activate<ACT>(v + x0[i]);
         p.C[(size_t)row * H + col] = out;
     }
