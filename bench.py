@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run a plain 64 MiB device copy (known traffic) to scale profiler counters by")
     return ap.parse_args()
 
 
@@ -282,6 +284,14 @@ def main():
     default_warm = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
     steps = a.steps if a.steps is not None else default_steps[a.workload]
     warm = a.warmup if a.warmup is not None else default_warm[a.workload]
+
+    if a.calibration_copy:
+        src = torch.ones(16 << 20, device="cuda")          # 64 MiB read + 64 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = Workload(a.workload, flags, a.windows)
     wall, gpu_s = wl.time_steps(steps, warm)
