@@ -153,7 +153,7 @@ const char *rnn_strerror(int code);
 /* Name of the recurrence kernel family the dispatcher picks for these sizes (host-only; for
  * reports and tests): "wg_resident" (one workgroup per sequence, weights in LDS),
  * "grid_resident" (several cooperating workgroups per sequence), "batch_mfma" (batched,
- * hidden <= 256: one persistent matrix-core workgroup per 16 batch rows, weights in registers),
+ * hidden <= 256: one persistent matrix-core workgroup per 4 batch rows, weights in registers),
  * "step_mfma" (batched, larger hidden: one fused matrix-core launch per step) or "reference". */
 const char *rnn_recurrence_variant(const rnn_dims *dims);
 
