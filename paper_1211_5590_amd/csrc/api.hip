@@ -242,8 +242,9 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
                                     rowloss, N, z.O, s));
         return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
     }
-    RNN_TRY(launch_mse_row_loss(Z, static_cast<const float*>(targets), rowloss, N, z.O, s));
-    return launch_loss_reduce(rowloss, N, (float)(1.0 / ((double)N * (double)z.O)), loss, s);
+    int n_partial = 0;
+    RNN_TRY(launch_mse_partial(Z, static_cast<const float*>(targets), rowloss, N, z.O, &n_partial, s));
+    return launch_loss_reduce(rowloss, n_partial, (float)(1.0 / ((double)N * (double)z.O)), loss, s);
 }
 
 hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const void* targets,

@@ -224,21 +224,58 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         }
 }
 
-// C[m,n] = (beta ? C : 0) + sum_s part[s][m][n] + bias[n], fixed summation order
+// C[m,n] = (beta ? C : 0) + sum_s part[s][m][n] + bias[n], fixed summation order.
+// A workgroup owns 16*VEC consecutive outputs; its 256 threads are 16 output lanes times 16
+// split lanes, every split lane adds the splits s = lane, lane+16, ... (8 loads in flight) and
+// the 16 partial sums are folded through LDS in lane order.
+template <int VEC>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
                                                             float* __restrict__ C,
                                                             const float* __restrict__ bias, int M,
                                                             int N, int ldc, int splits, int beta) {
+    __shared__ float red[256 * VEC];
+    constexpr int U = 8;
     const size_t total = (size_t)M * N;
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (size_t)gridDim.x * blockDim.x) {
-        const int m = (int)(idx / N), n = (int)(idx % N);
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += part[(size_t)k * total + idx];
-        if (bias) s += bias[n];
-        float* dst = C + (size_t)m * ldc + n;
-        if (beta) s += *dst;
-        *dst = s;
+    const int ox = threadIdx.x & 15, sy = threadIdx.x >> 4;
+    const size_t idx = ((size_t)blockIdx.x * 16 + ox) * VEC;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    if (idx < total) {
+        for (int k0 = sy; k0 < splits; k0 += 16 * U) {
+            float m[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float* src = part + (size_t)min(k0 + 16 * u, splits - 1) * total + idx;
+                if (VEC == 4) {
+                    const float4 a = *reinterpret_cast<const float4*>(src);
+                    m[u][0] = a.x; m[u][1 % VEC] = a.y; m[u][2 % VEC] = a.z; m[u][3 % VEC] = a.w;
+                } else {
+                    m[u][0] = *src;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (k0 + 16 * u < splits)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] += m[u][v];
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[threadIdx.x * VEC + v] = acc[v];
+    __syncthreads();
+    if (sy == 0 && idx < total) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float s = 0.f;
+            for (int r = 0; r < 16; ++r) s += red[(r * 16 + ox) * VEC + v];
+            const size_t e = idx + v;
+            const int m = (int)(e / N), n = (int)(e % N);
+            if (bias) s += bias[n];
+            float* dst = C + (size_t)m * ldc + n;
+            if (beta) s += *dst;
+            *dst = s;
+        }
     }
 }
 
@@ -314,11 +351,16 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
 
     if (sp.splits > 1) {
         const size_t total = (size_t)g.M * g.N;
-        int blocks = (int)((total + 255) / 256);
-        if (blocks > 4096) blocks = 4096;
         ProfileScope ps(K_SPLITK_REDUCE, s);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, s, g.splitk_ws, g.C,
-                           g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
+        if (total % 4 == 0) {  // the partial buffer is 16-byte aligned workspace
+            const unsigned blocks = (unsigned)((total / 4 + 15) / 16);
+            hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3(blocks), dim3(256), 0, s, g.splitk_ws,
+                               g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
+        } else {
+            const unsigned blocks = (unsigned)((total + 15) / 16);
+            hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(blocks), dim3(256), 0, s, g.splitk_ws,
+                               g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
+        }
         e = hipGetLastError();
     }
     return e;

@@ -106,8 +106,9 @@ hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s);
 // Output layer element-wise / row-wise kernels
 hipError_t launch_ce_row_stats(const float* Z, const int32_t* y, float* lse, float* rowloss,
                                int N, int O, hipStream_t s);
-hipError_t launch_mse_row_loss(const float* Z, const float* Y, float* rowloss, int N, int O,
-                               hipStream_t s);
+// squared-error partial sums over the flat [N*O] arrays: *n_partial (<= N) floats in `partial`
+hipError_t launch_mse_partial(const float* Z, const float* Y, float* partial, int N, int O,
+                              int* n_partial, hipStream_t s);
 hipError_t launch_loss_reduce(const float* rowloss, int N, float scale, float* loss, hipStream_t s);
 // Z -> dZ in place, plus per-row-chunk column sums into part[chunks][O]
 int colsum_chunks(int N);
