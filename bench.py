@@ -23,6 +23,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_MFMA_PEAK_TFLOPS = 157.3
+N_CU = 256
+LDS_PEAK_GBS_PER_CU = 256 * 2.4   # 16-byte LDS reads: 256 B/clk per compute unit at 2.4 GHz
 
 
 def parse():
@@ -76,6 +78,7 @@ class Workload:
         self.y_stride = self.y[0].numel() * self.y.element_size() * self.T
         case["_name"] = name
         case["_variant"] = rnn.rnn_recurrence_variant(self.dims)
+        case["_workgroups"] = rnn.rnn_recurrence_workgroups(self.dims)
         self.tokens_per_step = self.T * self.B * self.windows
         self.timesteps_per_step = self.T * self.windows
 
@@ -181,7 +184,43 @@ def algorithmic_work(kernel, c):
 RIDGE = FP32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte
 
 
+def on_chip_roofline(name, us, c):
+    """The time loops keep the recurrent matrix on chip, so HBM says little about them: their
+    own ceiling is the on-chip rate of the compute units they occupy (one workgroup per unit).
+    Weights resident in LDS/registers and used once per step (batch rows do not share a
+    workgroup): LDS read bandwidth of those units against T*B*H*H*4 bytes per launch.
+    Matrix-core loops: the fp32 MFMA rate of those units against 2*rows*H*H flop per launch."""
+    if name not in ("rec_fwd", "rec_bwd"):
+        return None
+    T, B, H = c["seq_len"], c["batch"], c["hidden"]
+    variant, wgs = c.get("_variant", ""), c.get("_workgroups", 0)
+    n_cu = min(N_CU, wgs)
+    sec = us * 1e-6
+    if n_cu <= 0 or variant == "reference":
+        return None
+    if variant in ("wg_resident", "grid_resident"):
+        nbytes = 4.0 * T * B * H * H
+        peak = n_cu * LDS_PEAK_GBS_PER_CU
+        ach = nbytes / sec / 1e9
+        return dict(bound="lds", n_cu=n_cu, achieved=ach, peak=peak, unit="GB/s", frac=ach / peak,
+                    on_chip_bytes=nbytes)
+    rows = B if variant == "step_mfma" else T * B      # one launch = one step, or all of them
+    flops = 2.0 * rows * H * H
+    peak = FP32_MFMA_PEAK_TFLOPS * n_cu / N_CU
+    ach = flops / sec / 1e12
+    return dict(bound="mfma", n_cu=n_cu, achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                flops=flops)
+
+
 def roofline_entry(name, prof, case):
+    r = _roofline_entry(name, prof, case)
+    oc = on_chip_roofline(name, prof[name]["avg_us"], case)
+    if oc:
+        r["on_chip"] = oc
+    return r
+
+
+def _roofline_entry(name, prof, case):
     work = algorithmic_work(name, case)
     us = prof[name]["avg_us"]
     if work is None:
@@ -229,10 +268,11 @@ def cpu_baseline(name, budget_s):
     cores = oracle.num_threads()
     cfg = ri.CONFIGS[name]
     if cfg["windows"] > 1:
-        case = ri.make_config(name, windows=64)
+        cap = min(cfg["windows"], 4096)
+        case = ri.make_config(name, windows=cap)
         t0 = time.perf_counter()
         h, done = None, 0
-        while done < 64 and (done < 4 or time.perf_counter() - t0 < budget_s):
+        while done < cap and (done < 4 or time.perf_counter() - t0 < budget_s):
             r = oracle.fwd_bptt(ri.window(case, done), h0=h)
             h = r["h_all"][-1]
             done += 1

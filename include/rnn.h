@@ -157,6 +157,11 @@ const char *rnn_strerror(int code);
  * "step_mfma" (batched, larger hidden: one fused matrix-core launch per step) or "reference". */
 const char *rnn_recurrence_variant(const rnn_dims *dims);
 
+/* Number of workgroups (= compute units occupied, one workgroup per unit) of one launch of the
+ * forward time-loop kernel for these sizes, or RNN_EINVAL (host-only; roofline reports state
+ * the loop's rate against the on-chip bandwidth or matrix rate of exactly these units). */
+int rnn_recurrence_workgroups(const rnn_dims *dims);
+
 /*
  * Per-kernel timing for roofline reports (the paper keeps a synchronous mode "for profiling
  * execution time of the different GPU kernels"; this is the asynchronous equivalent).  Between

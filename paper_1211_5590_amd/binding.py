@@ -18,7 +18,7 @@ LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
 FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 4, 8
 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
-           "rnn_strerror", "rnn_recurrence_variant", "rnn_profile_begin", "rnn_profile_end",
+           "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
            "rnn_workspace_status")
 
@@ -74,6 +74,8 @@ def lib():
         L.rnn_strerror.restype = ctypes.c_char_p
         L.rnn_recurrence_variant.argtypes = [ctypes.POINTER(Dims)]
         L.rnn_recurrence_variant.restype = ctypes.c_char_p
+        L.rnn_recurrence_workgroups.argtypes = [ctypes.POINTER(Dims)]
+        L.rnn_recurrence_workgroups.restype = ctypes.c_int
         L.rnn_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
         L.rnn_workspace_status.argtypes = [ctypes.POINTER(Dims), vp, sz, vp, ctypes.POINTER(ctypes.c_int32)]
         L.rnn_workspace_init.restype = ctypes.c_int
@@ -124,6 +126,13 @@ def rnn_strerror(code: int) -> str:
 
 def rnn_recurrence_variant(dims: Dims) -> str:
     return lib().rnn_recurrence_variant(ctypes.byref(dims)).decode()
+
+
+def rnn_recurrence_workgroups(dims: Dims) -> int:
+    n = lib().rnn_recurrence_workgroups(ctypes.byref(dims))
+    if n < 0:
+        raise RnnError(n, rnn_strerror(n))
+    return n
 
 
 def rnn_workspace_bytes(dims: Dims) -> int:

@@ -449,6 +449,16 @@ const char* rnn_recurrence_variant(const rnn_dims* dims) {
     return v.fwd.P == 1 ? "wg_resident" : "grid_resident";
 }
 
+int rnn_recurrence_workgroups(const rnn_dims* dims) {
+    if (!dims_valid(dims)) return RNN_EINVAL;
+    const Variant v = pick_variant(dims);
+    const Sizes s = sizes_of(dims);
+    if (v.batch_mfma) return (s.B + 3) / 4;
+    if (v.stepwise) return ((s.H + 15) / 16) * ((s.B + 15) / 16);   // tiles of one step launch
+    if (!v.resident) return s.B;
+    return v.fwd.P * s.B;
+}
+
 int rnn_workspace_status(const rnn_dims* dims, const void* workspace, size_t workspace_bytes,
                          void* hip_stream, int32_t* status_host) {
     if (!dims_valid(dims) || !status_host) return RNN_EINVAL;

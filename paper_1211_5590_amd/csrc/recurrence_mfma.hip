@@ -62,8 +62,15 @@ __global__ __launch_bounds__(2 * HP) void rec_batch_mfma_kernel(RecMfmaArgs a) {
     for (int j = 0; j < HP / 2; ++j) {
         const int k = 64 * (j / 32) + 32 * hf + (j % 32);
         const int kc = min(k, H - 1);
-        const float w = BWD ? a.Wh[(size_t)kc * H + colc] : a.Wh[(size_t)colc * H + kc];
-        wreg[j] = (col < H && k < H) ? w : 0.f;
+        wreg[j] = BWD ? a.Wh[(size_t)kc * H + colc] : a.Wh[(size_t)colc * H + kc];
+    }
+    // Zero the padding in a second pass, by multiplication: a select would make every load
+    // above conditional and serialise them behind a wait each.
+    const float colmask = col < H ? 1.f : 0.f;
+#pragma unroll
+    for (int j = 0; j < HP / 2; ++j) {
+        const int k = 64 * (j / 32) + 32 * hf + (j % 32);
+        wreg[j] *= k < H ? colmask : 0.f;
     }
 
     // ---- initial state tile ------------------------------------------------------------------
