@@ -116,7 +116,7 @@ Plan make_plan(const rnn_dims* d) {
     p.part = take((size_t)colsum_chunks((int)N) * widest * 4);
     p.splitk = take(max_splitk_floats(s) * 4);
     p.scratch = take(256);
-    p.flags = take(4096);
+    p.flags = take(4096 + 16 * B * H);   // state-exchange boxes of the multi-workgroup loops
     const size_t strips = (size_t)skinny_strips(s.O);
     const bool small = N <= 32;
     p.pm = take(small ? N * strips * 4 : 0);

@@ -57,7 +57,7 @@ struct RecResArgs {
     int H, T, B, act;
     int P, R, L, ldw, w_floats;  // filled from the plan by the launcher
     int nq4, hpad;               // float4 per lane of a row, zero-padded row/vector length
-    int32_t* flags;              // [B][P] step counters in the workspace (P > 1)
+    int32_t* flags;              // exchange boxes in the workspace (P > 1): [2][B][H] 64-bit words, 8-byte aligned
     int32_t* status;             // device status word: set to 1 when a bounded wait expires
     int spin_limit;              // <= 0: default
     // forward

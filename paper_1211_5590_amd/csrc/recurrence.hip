@@ -13,11 +13,11 @@
 // adjacent lanes that read row and state as float4 (all reads in flight before the first
 // multiply-add) and combine with DPP lane permutations.
 // P = 1: the state lives in LDS and a step costs workgroup barriers that order LDS only.
-// P > 1: every workgroup stores its slice of the new state to global memory, publishes a
-// per-workgroup step counter with release semantics, waits (bounded) for the other P-1
-// counters, and re-reads the full vector.  The launch is cooperative, so all P*B workgroups
-// are co-resident; a wait that exceeds its spin limit sets the status word and makes the
-// whole workgroup leave, so every wavefront terminates whatever happens.
+// P > 1: every workgroup publishes its slice of the new state as self-validating 64-bit words
+// {step tag, value} (relaxed device-scope atomic stores) and polls the other slices the same
+// way: one memory round trip per step, no fences.  The launch is cooperative, so all P*B
+// workgroups are co-resident; a wait that exceeds its spin limit sets the status word and
+// makes the whole workgroup leave, so every wavefront terminates whatever happens.
 //
 // Global-memory latency is kept off the dependent chain: everything the setup needs is
 // requested before anything is waited for, and the per-step epilogue operands (forward: the
@@ -390,6 +390,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         float* out_row = (!BWD && a.ring) ? ((s & 1) ? out_even : out_odd) : out_ptr;
         out_ptr += out_stride;
         // one pass covers every output of the slice: each output has its own lane group
+        float val = 0.f;
         {
             const int j = r0 + own;
             float x0 = 0.f, x1 = 0.f;
@@ -399,34 +400,47 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
             }
             const float acc = slice_dot(v);
             if (lead) {
-                const float val = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
+                val = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
                 out_row[j] = val;
                 vnext[j] = val;
                 if (BWD && a.fuse_post) Dl[t * H + j] = val;
             }
         }
         if (P > 1) {
-            const int step = s + 1;
-            __threadfence();
-            lds_barrier();
-            int32_t* fl = a.flags + (size_t)bb * P;
-            if (tid == 0) __hip_atomic_store(fl + p, step, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            if (tid < P) {
+            // Exchange of the new state between the P workgroups of this sequence.  Every value
+            // travels as one 64-bit word {step tag, value}, written and polled with relaxed
+            // device-scope atomics: the tag makes each word self-validating, so there is no
+            // separate flag, no fence and a single memory round trip per step.  Two boxes
+            // alternate by step parity; a box is overwritten two steps later, and by then every
+            // workgroup has read it (nobody publishes step s+1 before its own barrier below,
+            // and step s+2 needs everybody's step s+1).  The boxes start zeroed: tags are >= 1.
+            const unsigned tag = (unsigned)(s + 1);
+            unsigned long long* box = reinterpret_cast<unsigned long long*>(a.flags) +
+                                      ((size_t)(s & 1) * B + bb) * H;
+            if (lead) {
+                const int j = r0 + own;
+                const unsigned long long w =
+                    ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(val);
+                __hip_atomic_store(box + j, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            for (int j = tid; j < H; j += kThreads) {
+                if (j >= r0 && j < r0 + rows) continue;   // own slice: already in LDS
                 int spins = 0;
-                while (__hip_atomic_load(fl + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < step) {
+                unsigned long long w;
+                while ((unsigned)((w = __hip_atomic_load(box + j, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
                     if (++spins > a.spin_limit) { s_abort = 1; break; }
-                    __builtin_amdgcn_s_sleep(1);
                 }
+                vnext[j] = __uint_as_float((unsigned)w);
             }
             lds_barrier();
             if (s_abort) {
                 if (tid == 0) atomicExch(a.status, 1);
                 return;  // uniform: the whole workgroup leaves
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            for (int j = tid; j < H; j += kThreads) vnext[j] = out_row[j];
+        } else {
+            lds_barrier();
         }
-        lds_barrier();
         cur ^= 1;
     }
     __syncthreads();
@@ -535,6 +549,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
     if (B > 4 || H > 4096) return false;
     if (fuse_post && (B != 1 || T > kFuseMaxT || !bwd)) return false;
     constexpr size_t kLdsBudget = 150 * 1024;  // of 160 KB per CU
+    bool found = false;
     for (int P = 1; P <= 128; P *= 2) {
         if (P * B > 128) break;
         const int R = (H + P - 1) / P;
@@ -557,11 +572,15 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
         if (floats * 4 <= kLdsBudget) {
             pl.w_floats = (int)w_floats; pl.smem = floats * 4;
             *out = pl;
-            return true;
+            found = true;
+            // A single workgroup pays no exchange; once the state is exchanged anyway, more
+            // workgroups are cheap, so keep splitting until the slice fits in registers.
+            if (P == 1 || pl.nq4 <= 8) return true;
+            continue;
         }
         if (fuse_post) return false;  // the fused tail needs the single-workgroup form
     }
-    return false;
+    return found;
 }
 
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s) {
@@ -569,7 +588,8 @@ hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hip
     a.nq4 = pl.nq4; a.hpad = pl.hpad;
     if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
     if (pl.P > 1) {
-        hipError_t e = launch_zero_words(a.flags, pl.P * a.B, s);
+        // exchange boxes: 2 parities x B rows x H words of 64 bits
+        hipError_t e = launch_zero_words(a.flags, 4 * a.B * a.H, s);
         if (e != hipSuccess) return e;
     }
     const void* fn;
