@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
             const float acc = slice_dot(v);
             if (lead) {
                 val = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
-                out_row[j] = val;
+                if (P == 1) out_row[j] = val;   // P > 1: after the exchange, off its critical path
                 vnext[j] = val;
                 if (BWD && a.fuse_post) Dl[t * H + j] = val;
             }
@@ -433,6 +433,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                 }
                 vnext[j] = __uint_as_float((unsigned)w);
             }
+            if (lead) out_row[r0 + own] = val;
             lds_barrier();
             if (s_abort) {
                 if (tid == 0) atomicExch(a.status, 1);
