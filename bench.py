@@ -70,6 +70,7 @@ class Workload:
         self.carry = torch.zeros((2, self.B, self.H), device="cuda")
         self.loss = torch.zeros((max(self.windows, 1),), device="cuda")
         self.ws = torch.empty(rnn.rnn_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
+        rnn.rnn_workspace_init(self.dims, self.ws)
         # pre-marshalled arguments: plain ints and ctypes structs, no per-call Python objects
         self.L = rnn.lib()
         self.P = rnn.Params(*[self.p[k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])

@@ -135,12 +135,19 @@ int rnn_check_tokens(const void *ids, int64_t n, int32_t limit, int32_t *bad_cou
                      void *hip_stream);
 
 /*
- * Device status word kept in the workspace.  The multi-workgroup persistent loops wait for
- * each other with a bounded spin; if a wait ever expires (which needs the GPU to be shared in a
- * way that defeats the cooperative launch) the kernel sets the word to 1, every workgroup
- * leaves, and the results of that call are invalid.  rnn_workspace_init clears the word
- * (asynchronous; call it once after allocating a workspace if the word will be read);
- * rnn_workspace_status copies it to *status_host and synchronises the stream.
+ * Workspace set-up and the device status word.
+ *
+ * rnn_workspace_init must be called once on a newly allocated workspace (and again whenever
+ * the memory has been used for anything else) before the first rnn_forward / rnn_loss /
+ * rnn_bptt with these dims: kernels of one launch pass small results to each other as words
+ * that carry a per-call tag, and a cleared word is what "not written yet" looks like.  The call
+ * is asynchronous on hip_stream and also clears the status word.
+ *
+ * Status word: the kernels that wait for other workgroups of their launch do so with a bounded
+ * spin; if a wait ever expires (which needs the GPU to be shared in a way that keeps those
+ * workgroups from running together) the kernel sets the word to 1, stops waiting, and the
+ * results of that call are invalid.  rnn_workspace_status copies the word to *status_host and
+ * synchronises the stream.
  */
 int rnn_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
                        void *hip_stream);

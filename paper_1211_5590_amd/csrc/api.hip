@@ -4,6 +4,8 @@
 // and does O(1) host work whatever the sequence length (its trusted-input switch).
 #include "../../include/rnn.h"
 
+#include <atomic>
+
 #include "internal.hpp"
 #include "prof.hpp"
 
@@ -11,12 +13,21 @@ namespace {
 
 using namespace rnn;
 
+// Tag of the self-validating words one call exchanges between its workgroups: unique per call
+// in this process, never 0 (the value of a cleared workspace).
+uint32_t next_epoch() {
+    static std::atomic<uint32_t> counter{0};
+    uint32_t e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (e == 0) e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
+    return e;
+}
+
 constexpr size_t kAlign = 256;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     // byte offsets into the workspace
-    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, pm, ps, zy, gpart, seen,
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gpart, seen,
         total;
 };
 
@@ -119,9 +130,7 @@ Plan make_plan(const rnn_dims* d) {
     p.flags = take(4096 + 16 * B * H);   // state-exchange boxes of the multi-workgroup loops
     const size_t strips = (size_t)skinny_strips(s.O);
     const bool small = N <= 32;
-    p.pm = take(small ? N * strips * 4 : 0);
-    p.ps = take(small ? N * strips * 4 : 0);
-    p.zy = take(small ? N * 4 : 0);
+    p.statbox = take(small ? skinny_stat_box_bytes((int)N, s.O) : 0);
     p.gpart = take(small ? strips * N * H * 4 : 0);
     p.seen = take(s.tokens && N >= 2048 ? (size_t)32 * s.NVin * 4 : 0);
     p.total = off;
@@ -212,8 +221,9 @@ SkinnyArgs skinny_args(const rnn_dims* d, const rnn_params* P, const float* h_al
     SkinnyArgs k{};
     k.Hs = h_all + (size_t)z.B * z.H; k.V = P->V; k.c = P->c;
     k.y = static_cast<const int32_t*>(targets);
-    k.Z = at<float>(ws, pl.Z); k.pm = at<float>(ws, pl.pm); k.ps = at<float>(ws, pl.ps);
-    k.zy = at<float>(ws, pl.zy); k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart);
+    k.Z = at<float>(ws, pl.Z); k.stat_box = at<unsigned long long>(ws, pl.statbox);
+    k.status = at<int32_t>(ws, pl.scratch) + 1;
+    k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart);
     k.H = z.H; k.O = z.O; k.N = (int)z.N; k.NV = z.NVin;
     return k;
 }
@@ -223,9 +233,10 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
     const Sizes z = sizes_of(d);
     const int N = (int)z.N;
     if (pick_variant(d).skinny) {
-        const SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
-        RNN_TRY(launch_skinny_logits(k, s));
-        return launch_skinny_loss(k, loss, s);
+        SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
+        k.epoch = next_epoch();
+        k.loss = loss;
+        return launch_skinny_logits(k, s);
     }
     float* Z = at<float>(ws, pl.Z);
     GemmArgs g{};
@@ -478,7 +489,14 @@ int rnn_workspace_init(const rnn_dims* dims, void* workspace, size_t workspace_b
     const int rc = check_ws(dims, workspace, workspace_bytes, &pl);
     if (rc != RNN_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    return launch_zero_words(at<int32_t>(workspace, pl.scratch), 64, s) == hipSuccess ? RNN_OK : RNN_EHIP;
+    if (launch_zero_words(at<int32_t>(workspace, pl.scratch), 64, s) != hipSuccess) return RNN_EHIP;
+    // exchange words start cleared: tag 0 is never a valid tag
+    const Sizes z = sizes_of(dims);
+    if (z.N <= 32) {
+        const size_t words = skinny_stat_box_bytes((int)z.N, z.O) / 4;
+        if (launch_zero_words(at<int32_t>(workspace, pl.statbox), (int)words, s) != hipSuccess) return RNN_EHIP;
+    }
+    return RNN_OK;
 }
 
 }  // extern "C"

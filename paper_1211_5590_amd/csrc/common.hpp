@@ -54,4 +54,35 @@ __device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2
     s = a + b;
 }
 
+// ---------------------------------------------------------------------------------------
+// Self-validating words for exchanges between workgroups of one launch.  A 32-bit value
+// travels with a 32-bit tag in one naturally aligned 64-bit word that is written and read with
+// relaxed device-scope atomics, so a reader that sees the expected tag has the value that was
+// written with it: no separate flag, no fence, one memory round trip.  A tag is never 0
+// (cleared memory) and is unique to the launch or step that writes it.
+__device__ __forceinline__ void tagged_store(unsigned long long* p, unsigned tag, float v) {
+    __hip_atomic_store(p, ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long tagged_load(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool tagged_ok(unsigned long long w, unsigned tag) {
+    return (unsigned)(w >> 32) == tag;
+}
+__device__ __forceinline__ float tagged_value(unsigned long long w) {
+    return __uint_as_float((unsigned)w);
+}
+// polls until the tag shows up; false when the bounded wait expires
+__device__ __forceinline__ bool tagged_wait(const unsigned long long* p, unsigned tag, int spin_limit,
+                                            float& v) {
+    unsigned long long w = tagged_load(p);
+    for (int spins = 0; !tagged_ok(w, tag); ++spins) {
+        if (spins > spin_limit) return false;
+        w = tagged_load(p);
+    }
+    v = tagged_value(w);
+    return true;
+}
+
 }  // namespace rnn

@@ -126,8 +126,10 @@ struct SkinnyArgs {
     const float* c;       // [O]
     const int32_t* y;     // [N]
     float* Z;             // [N,O] logits (workspace)
-    float* pm; float* ps; // [N][strips] strip max / sum exp
-    float* zy;            // [N] target logits
+    unsigned long long* stat_box;  // tagged words: [N][strips][2] strip max / sum exp, then [N] target logits
+    uint32_t epoch;       // tag of this call's words (never 0)
+    int32_t* status;      // device status word: set to 1 when a bounded wait expires
+    float* loss;          // device scalar written by the merging workgroup (logits kernel)
     float* lse;           // [N]
     float* dV; float* dc; // gradients
     float* gpart;         // [strips][N][H]
@@ -136,8 +138,8 @@ struct SkinnyArgs {
 };
 int skinny_strips(int O);
 bool skinny_supported(int N, int H, int O);
-hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);
-hipError_t launch_skinny_loss(const SkinnyArgs& a, float* loss, hipStream_t s);
+size_t skinny_stat_box_bytes(int N, int O);
+hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);   // logits, statistics and loss
 hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------

@@ -4,8 +4,9 @@
 // kernels in which every workgroup owns a strip of 128 vocabulary columns, reads its strip of
 // V once per kernel with 16-byte loads, and keeps the N hidden rows in LDS.
 //
-//   skinny_logits : Z strip = Hs V + c, per-row (max, sum exp) of the strip, target logit
-//   skinny_loss   : merges the strip statistics -> lse per row, loss
+//   skinny_logits : Z strip = Hs V + c, per-row (max, sum exp) of the strip, target logit; the
+//                   last strip's workgroup merges the statistics of all strips (passed as
+//                   self-validating tagged words) into lse per row and the loss
 //   skinny_back   : dZ strip from Z and lse (never written back), dc, dV strip = Hs^T dZ,
 //                   partial G = dZ V^T over the strip, and the zero fill of dWx
 // The partial G of all strips is summed, in strip order, by the reverse-loop kernel.
@@ -128,39 +129,86 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
             const float e = __expf(z0 - m) + __expf(z1 - m);  // exp(-inf) = 0 for padding
             const float s = wave_sum(e);
             if (lane == 0) {
-                a.pm[(size_t)(n0 + r) * gridDim.x + blockIdx.x] = m;
-                a.ps[(size_t)(n0 + r) * gridDim.x + blockIdx.x] = s;
+                unsigned long long* st = a.stat_box + ((size_t)(n0 + r) * gridDim.x + blockIdx.x) * 2;
+                tagged_store(st, a.epoch, m);
+                tagged_store(st + 1, a.epoch, s);
                 const int y = a.y[n0 + r] - blockIdx.x * CW;
-                if (y >= 0 && y < CW) a.zy[n0 + r] = red[r * CW + y];
+                if (y >= 0 && y < CW)
+                    tagged_store(a.stat_box + (size_t)N * gridDim.x * 2 + n0 + r, a.epoch, red[r * CW + y]);
             }
         }
     }
-}
 
-// one wavefront per row merges the strip statistics; thread 0 then averages the row losses
-__global__ __launch_bounds__(NTH) void skinny_loss_kernel(SkinnyArgs a, int strips, float* loss) {
+    // The last strip (usually a short one) merges the statistics of all strips as they arrive:
+    // one wavefront per row, lanes over the strips, then the mean row loss.  Only this
+    // workgroup waits, and nobody waits for it, so the launch cannot deadlock; the waits are
+    // bounded all the same.
+    if (blockIdx.x != gridDim.x - 1) return;
     __shared__ float rl[32];
-    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    for (int n = wave; n < a.N; n += NWV) {
-        float m = -INFINITY, s = 0.f;
-        for (int g = lane; g < strips; g += kWave)
-            lse_merge(m, s, a.pm[(size_t)n * strips + g], a.ps[(size_t)n * strips + g]);
+    __shared__ int s_fail;
+    if (tid == 0) s_fail = 0;
+    __syncthreads();                     // also: `red` is free from here on
+    const int strips = gridDim.x;
+    const int spin_limit = 1 << 22;
+    const unsigned epoch = a.epoch;
+    // All words of a group of rows are requested at once (four per thread in flight), parked in
+    // LDS, and merged from there: the waiting costs about one memory round trip in total.
+    float* stage = red;                  // NWV*NR*CW floats >= 2*strips (checked by the host)
+    __shared__ float zys[32];
+    const unsigned long long* zybox = a.stat_box + (size_t)N * strips * 2;
+    unsigned long long wz = tid < N ? tagged_load(zybox + tid) : 0ull;   // in flight with the rest
+    const int rows_per_pass = max(1, (NWV * NR * CW) / (2 * strips));
+    for (int n_lo = 0; n_lo < N; n_lo += rows_per_pass) {
+        const int n_hi = min(N, n_lo + rows_per_pass);
+        const int cnt = (n_hi - n_lo) * strips * 2;
+        const unsigned long long* src = a.stat_box + (size_t)n_lo * strips * 2;
+        for (int w0 = tid; w0 < cnt; w0 += 4 * NTH) {
+            unsigned long long w[4];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const float m2 = __shfl_xor(m, off, kWave), s2 = __shfl_xor(s, off, kWave);
-            lse_merge(m, s, m2, s2);
+            for (int u = 0; u < 4; ++u) w[u] = tagged_load(src + min(w0 + u * NTH, cnt - 1));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = w0 + u * NTH;
+                if (idx >= cnt) continue;
+                for (int spins = 0; !tagged_ok(w[u], epoch); ++spins) {
+                    if (spins > spin_limit) { s_fail = 1; break; }
+                    w[u] = tagged_load(src + idx);
+                }
+                stage[idx] = tagged_value(w[u]);
+            }
         }
-        if (lane == 0) {
-            const float l = m + logf(s);
-            a.lse[n] = l;
-            rl[n] = l - a.zy[n];
+        if (n_lo == 0 && tid < N) {
+            for (int spins = 0; !tagged_ok(wz, epoch); ++spins) {
+                if (spins > spin_limit) { s_fail = 1; break; }
+                wz = tagged_load(zybox + tid);
+            }
+            zys[tid] = tagged_value(wz);
         }
+        __syncthreads();
+        for (int n = n_lo + wave; n < n_hi; n += NWV) {
+            float m = -INFINITY, sum = 0.f;
+            for (int g = lane; g < strips; g += kWave) {
+                const float* st = stage + ((size_t)(n - n_lo) * strips + g) * 2;
+                lse_merge(m, sum, st[0], st[1]);
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const float m2 = __shfl_xor(m, off, kWave), s2 = __shfl_xor(sum, off, kWave);
+                lse_merge(m, sum, m2, s2);
+            }
+            if (lane == 0) {
+                const float l = m + logf(sum);
+                a.lse[n] = l;
+                rl[n] = l - zys[n];
+            }
+        }
+        __syncthreads();
     }
-    __syncthreads();
     if (tid == 0) {
+        if (s_fail) atomicExch(a.status, 1);
         float t = 0.f;
-        for (int n = 0; n < a.N; ++n) t += rl[n];
-        *loss = t / (float)a.N;
+        for (int n = 0; n < N; ++n) t += rl[n];
+        *a.loss = t / (float)N;
     }
 }
 
@@ -317,8 +365,11 @@ size_t back_smem(int H) { return ((size_t)H * NR + (size_t)NR * CW + (size_t)NR 
 
 int skinny_strips(int O) { return (O + CW - 1) / CW; }
 
+size_t skinny_stat_box_bytes(int N, int O) { return ((size_t)2 * N * skinny_strips(O) + N) * 8; }
+
 bool skinny_supported(int N, int H, int O) {
     if (N > 32 || N < 1 || O % 4 != 0) return false;
+    if (2 * skinny_strips(O) > NWV * NR * CW) return false;   // one row of strip statistics fits the LDS stage
     return back_smem(H) <= 64 * 1024 && logits_smem(H) <= 140 * 1024;
 }
 
@@ -333,12 +384,6 @@ hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s) {
     }
     ProfileScope ps(K_SKINNY_LOGITS, s);
     hipLaunchKernelGGL(skinny_logits_kernel, dim3(skinny_strips(a.O)), dim3(NTH), logits_smem(a.H), s, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_skinny_loss(const SkinnyArgs& a, float* loss, hipStream_t s) {
-    ProfileScope ps(K_LOSS_REDUCE, s);
-    hipLaunchKernelGGL(skinny_loss_kernel, dim3(1), dim3(NTH), 0, s, a, skinny_strips(a.O), loss);
     return hipGetLastError();
 }
 

@@ -44,7 +44,9 @@ class Runner:
         self.grads = {"d" + k: torch.full_like(v, float("nan")) for k, v in self.params.items()}
         self.dh0 = torch.full((B, H), float("nan"), device="cuda")
         nbytes = rnn.rnn_workspace_bytes(self.dims)
-        self.ws = torch.empty(nbytes + 64, dtype=torch.uint8, device="cuda")
+        # 0xA5 fill: a workspace is arbitrary memory until rnn_workspace_init has run on it
+        self.ws = torch.full((nbytes + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        rnn.rnn_workspace_init(self.dims, self.ws)
 
     def set_flags(self, flags):
         self.dims.flags = flags
