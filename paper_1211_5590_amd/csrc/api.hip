@@ -27,7 +27,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     // byte offsets into the workspace
-    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gpart, seen,
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gpart, vy, seen,
         total;
 };
 
@@ -93,8 +93,8 @@ Variant pick_variant(const rnn_dims* d) {
     const Sizes s = sizes_of(d);
     Variant v{};
     if (d->flags & RNN_FLAG_REFERENCE_KERNELS) return v;
-    v.resident = rec_resident_plan(s.H, s.B, s.T, false, false, &v.fwd) &&
-                 rec_resident_plan(s.H, s.B, s.T, true, false, &v.bwd);
+    v.resident = rec_resident_plan(s.H, s.B, s.T, false, false, 0, &v.fwd) &&
+                 rec_resident_plan(s.H, s.B, s.T, true, false, 0, &v.bwd);
     if (!v.resident) {
         v.batch_mfma = rec_batch_mfma_supported(s.H, s.B);
         v.stepwise = !v.batch_mfma && s.B > 4;
@@ -102,7 +102,7 @@ Variant pick_variant(const rnn_dims* d) {
     }
     RecResPlan fused;
     if (s.tokens && s.ce && s.B == 1 && skinny_supported((int)s.N, s.H, s.O) &&
-        rec_resident_plan(s.H, s.B, s.T, true, true, &fused)) {
+        rec_resident_plan(s.H, s.B, s.T, true, true, skinny_strips(s.O), &fused)) {
         v.skinny = true;
         v.bwd = fused;
     }
@@ -132,6 +132,7 @@ Plan make_plan(const rnn_dims* d) {
     const bool small = N <= 32;
     p.statbox = take(small ? skinny_stat_box_bytes((int)N, s.O) : 0);
     p.gpart = take(small ? strips * N * H * 4 : 0);
+    p.vy = take(small ? N * H * 4 : 0);
     p.seen = take(s.tokens && N >= 2048 ? (size_t)32 * s.NVin * 4 : 0);
     p.total = off;
     return p;
@@ -223,7 +224,7 @@ SkinnyArgs skinny_args(const rnn_dims* d, const rnn_params* P, const float* h_al
     k.y = static_cast<const int32_t*>(targets);
     k.Z = at<float>(ws, pl.Z); k.stat_box = at<unsigned long long>(ws, pl.statbox);
     k.status = at<int32_t>(ws, pl.scratch) + 1;
-    k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart);
+    k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart); k.vy = at<float>(ws, pl.vy);
     k.H = z.H; k.O = z.O; k.N = (int)z.N; k.NV = z.NVin;
     return k;
 }
@@ -284,11 +285,12 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
         k.dV = Gr->dV; k.dc = Gr->dc; k.beta = beta;
         k.dWx_zero = beta ? nullptr : Gr->dWx;
-        RNN_TRY(launch_skinny_back(k, s));
+        k.xids = static_cast<const int32_t*>(x);
         r.gpart = k.gpart; r.gstrips = skinny_strips(O); r.Gw = G;
+        r.stat_box = k.stat_box; r.lse = k.lse; r.vy = k.vy;
         r.fuse_post = 1; r.x = static_cast<const int32_t*>(x);
         r.dWh = Gr->dWh; r.db = Gr->db; r.dWx = Gr->dWx; r.beta = beta;
-        return launch_rec_resident(r, v.bwd, true, s);
+        return launch_rec_bwd_with_strips(r, v.bwd, k, s);
     }
 
     // logits -> d loss / d logits (in place) and dc

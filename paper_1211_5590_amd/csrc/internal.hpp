@@ -67,12 +67,20 @@ struct RecResArgs {
     const float* G; const float* h_all; const float* dh_last; float* Delta; float* dh0;
     // fused weight gradients of a short single sequence (reverse, P == 1, B == 1)
     int fuse_post; float* dWh; float* db; float* dWx; int beta;
-    // per-strip partial G [strips][T*B][H] to be summed into Gw before the loop (nullable)
+    // Short single sequence (fuse_post): the strips' shares of G [strips][T][H], relative to
+    // each strip's maximum, with the strip statistics, lse and the target columns of V that
+    // turn them into G before the loop (gpart nullable = G is given)
     const float* gpart; int gstrips; float* Gw;
+    const unsigned long long* stat_box; const float* lse; const float* vy;
 };
 struct RecResPlan { int P, R, L, ldw, w_floats, nq4, hpad; size_t smem; };
-bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan* out);
+// strips: column strips of the short-sequence output layer (fuse_post only, else 0)
+bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips, RecResPlan* out);
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s);
+struct SkinnyArgs;
+// reverse loop with fused weight gradients (workgroup 0) and the output layer's backward strips
+// (one workgroup per strip) in one launch; a must have fuse_post set
+hipError_t launch_rec_bwd_with_strips(RecResArgs a, const RecResPlan& pl, const SkinnyArgs& k, hipStream_t s);
 
 // Batched recurrence run as one fused GEMM launch per time step (recurrence_step.hip); serves
 // the shapes the resident-weight kernels do not cover (batch > 4).
@@ -134,13 +142,14 @@ struct SkinnyArgs {
     float* dV; float* dc; // gradients
     float* gpart;         // [strips][N][H]
     float* dWx_zero;      // token-gradient matrix to zero fill, or NULL
+    const int32_t* xids;  // [N] input token ids (rows of dWx the reverse loop's workgroup writes itself)
+    float* vy;            // [N][H] column y_n of V per row (workspace)
     int H, O, N, NV, beta;
 };
 int skinny_strips(int O);
 bool skinny_supported(int N, int H, int O);
 size_t skinny_stat_box_bytes(int N, int O);
 hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);   // logits, statistics and loss
-hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // Token-keyed gradient of the input matrix and id validation

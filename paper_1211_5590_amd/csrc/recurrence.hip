@@ -25,6 +25,7 @@
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
+#include "skinny_dev.hpp"
 
 #include <type_traits>
 
@@ -69,13 +70,12 @@ __device__ __forceinline__ float group_sum(float v, int L) {
 }
 
 template <int ACT, bool BWD>
-__global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
+__device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int p, const int bb,
+                                                  float* smem) {
     __shared__ int s_abort;
     __shared__ int s_ids[kFuseMaxT];
     __shared__ int s_first[kFuseMaxT];
     const int H = a.H, P = a.P, R = a.R, ldw = a.ldw, L = a.L, B = a.B, T = a.T;
-    const int p = blockIdx.x, bb = blockIdx.y;
     const int tid = threadIdx.x;
     const int r0 = p * R;
     const int rows = max(0, min(R, H - r0));
@@ -88,6 +88,7 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     float* Gl = stash + 2 * TC * 2 * R;       // fused tail only: [T][H] G, delta, h_{t-1}
     float* Dl = Gl + T * H;
     float* Hl = Dl + T * H;
+    float* wl = Hl + T * H;                   // fused tail only: [T][strips] weights of the strips' G shares
 
     // thread roles
     const int q = tid % L;                               // which share of the k range
@@ -236,17 +237,26 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
         }
     }
     if (BWD && a.gpart) {
-        // Sum of the per-strip partial G.  The order is fixed (a strip range per lane, then a
-        // shuffle tree), so results repeat bit for bit.  Only used with the fused tail (B == 1).
-        const int n = T * H;
-        if ((n & 3) == 0) {
-            const int n4 = n / 4;
+        // G = (sum over strips of w * share - V[:, y]) / N with w = exp(strip max - lse): the
+        // output-layer kernel left every strip's share of the softmax part relative to the
+        // strip's own maximum.  The order is fixed (a strip range per lane, then a shuffle
+        // tree), so results repeat bit for bit.  Only used with the fused tail (B == 1).
+        const int n = T * H, S = a.gstrips;
+        const float invN = 1.0f / (float)T;
+        for (int i = tid; i < T * S; i += kThreads) {
+            const int t = i / S;
+            wl[i] = __expf(tagged_value(a.stat_box[(size_t)i * 2]) - a.lse[t]);
+        }
+        __syncthreads();
+        if ((H & 3) == 0) {
+            const int n4 = n / 4, H4 = H / 4;
             int parts = 1;
             while (parts < 8 && parts * 2 * n4 <= kThreads) parts *= 2;
             const int part_id = tid % parts;
-            const int per = (a.gstrips + parts - 1) / parts;
-            const int sb = part_id * per, se = min(a.gstrips, sb + per);
+            const int per = (S + parts - 1) / parts;
+            const int sb = part_id * per, se = min(S, sb + per);
             for (int e = tid / parts; e < n4; e += kThreads / parts) {
+                const float* w = wl + (e / H4) * S;
                 float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
                 for (int s0 = sb; s0 < se; s0 += 20) {
                     float4 t[20];
@@ -256,7 +266,11 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                                    ? reinterpret_cast<const float4*>(a.gpart + (size_t)(s0 + u) * n)[e]
                                    : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                    for (int u = 0; u < 20; ++u) { g.x += t[u].x; g.y += t[u].y; g.z += t[u].z; g.w += t[u].w; }
+                    for (int u = 0; u < 20; ++u) {
+                        const float wu = (s0 + u < se) ? w[s0 + u] : 0.f;
+                        g.x = fmaf(wu, t[u].x, g.x); g.y = fmaf(wu, t[u].y, g.y);
+                        g.z = fmaf(wu, t[u].z, g.z); g.w = fmaf(wu, t[u].w, g.w);
+                    }
                 }
                 for (int off = 1; off < parts; off <<= 1) {
                     g.x += __shfl_xor(g.x, off, kWave);
@@ -264,20 +278,25 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
                     g.z += __shfl_xor(g.z, off, kWave);
                     g.w += __shfl_xor(g.w, off, kWave);
                 }
-                if (part_id == 0) reinterpret_cast<float4*>(Gl)[e] = g;
+                if (part_id == 0) {
+                    const float4 vy = reinterpret_cast<const float4*>(a.vy)[e];
+                    reinterpret_cast<float4*>(Gl)[e] = make_float4((g.x - vy.x) * invN, (g.y - vy.y) * invN,
+                                                                   (g.z - vy.z) * invN, (g.w - vy.w) * invN);
+                }
             }
         } else {
             for (int e = tid; e < n; e += kThreads) {
+                const float* w = wl + (e / H) * S;
                 float g = 0.f;
-                for (int s0 = 0; s0 < a.gstrips; s0 += 8) {
+                for (int s0 = 0; s0 < S; s0 += 8) {
                     float t[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
-                        t[u] = (s0 + u < a.gstrips) ? a.gpart[(size_t)(s0 + u) * n + e] : 0.f;
+                        t[u] = (s0 + u < S) ? a.gpart[(size_t)(s0 + u) * n + e] : 0.f;
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) g += t[u];
+                    for (int u = 0; u < 8; ++u) g = fmaf((s0 + u < S) ? w[s0 + u] : 0.f, t[u], g);
                 }
-                Gl[e] = g;
+                Gl[e] = (g - a.vy[e]) * invN;
             }
         }
     }
@@ -528,6 +547,23 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     if (a.beta) tail(std::true_type{}); else tail(std::false_type{});
 }
 
+template <int ACT, bool BWD>
+__global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    rec_resident_body<ACT, BWD>(a, blockIdx.x, blockIdx.y, smem);
+}
+
+// Backward pass of a short single sequence in one launch: workgroup 0 runs the reverse time loop
+// with the fused weight gradients, workgroups 1.. run the backward strips of the output layer
+// (dV, dc, zero fill of dWx).  The two parts share no data inside the launch.
+template <int ACT>
+__global__ __launch_bounds__(kThreads) void rec_bwd_with_strips_kernel(RecResArgs a, SkinnyArgs k) {
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    static_assert(skinny::NTH == kThreads, "both parts use the same workgroup size");
+    if (blockIdx.x == 0) rec_resident_body<ACT, true>(a, 0, 0, smem);
+    else skinny::back_body(k, (int)blockIdx.x - 1, (int)gridDim.x - 1, smem);
+}
+
 __global__ void zero_words_kernel(int32_t* p, int n) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
 }
@@ -540,13 +576,36 @@ int pow2_floor(int v) {
 
 }  // namespace
 
+hipError_t launch_rec_bwd_with_strips(RecResArgs a, const RecResPlan& pl, const SkinnyArgs& k, hipStream_t s) {
+    if (pl.P != 1 || a.B != 1 || !a.fuse_post) return hipErrorInvalidValue;
+    a.P = pl.P; a.R = pl.R; a.L = pl.L; a.ldw = pl.ldw; a.w_floats = pl.w_floats;
+    a.nq4 = pl.nq4; a.hpad = pl.hpad;
+    if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
+    const void* fn = a.act == 0 ? (const void*)rec_bwd_with_strips_kernel<0>
+                                : (const void*)rec_bwd_with_strips_kernel<1>;
+    size_t smem = pl.smem;
+    if (skinny::back_smem(a.H) > smem) smem = skinny::back_smem(a.H);
+    static size_t allowed[2] = {0, 0};
+    const int slot = a.act == 0 ? 0 : 1;
+    if (smem > 64 * 1024 && smem > allowed[slot]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        allowed[slot] = smem;
+    }
+    ProfileScope ps(K_REC_BWD, s);
+    const dim3 grid(1 + skinny_strips(k.O)), block(kThreads);
+    if (a.act == 0) hipLaunchKernelGGL((rec_bwd_with_strips_kernel<0>), grid, block, smem, s, a, k);
+    else hipLaunchKernelGGL((rec_bwd_with_strips_kernel<1>), grid, block, smem, s, a, k);
+    return hipGetLastError();
+}
+
 hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s) {
     ProfileScope ps(K_MISC, s);
     hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }
 
-bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan* out) {
+bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips, RecResPlan* out) {
     if (B > 4 || H > 4096) return false;
     if (fuse_post && (B != 1 || T > kFuseMaxT || !bwd)) return false;
     constexpr size_t kLdsBudget = 150 * 1024;  // of 160 KB per CU
@@ -569,7 +628,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, RecResPlan
         pl.ldw = ldw;
         size_t w_floats = pl.nq4 <= 8 ? 0 : (size_t)R * ldw;   // small slices live in registers
         size_t floats = w_floats + 2 * (size_t)pl.hpad + (size_t)2 * TC * 2 * R;
-        if (fuse_post) floats += (size_t)3 * T * H;
+        if (fuse_post) floats += (size_t)3 * T * H + (size_t)T * strips;
         if (floats * 4 <= kLdsBudget) {
             pl.w_floats = (int)w_floats; pl.smem = floats * 4;
             *out = pl;

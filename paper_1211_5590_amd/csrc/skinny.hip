@@ -6,58 +6,38 @@
 //
 //   skinny_logits : Z strip = Hs V + c, per-row (max, sum exp) of the strip, target logit; the
 //                   last strip's workgroup merges the statistics of all strips (passed as
-//                   self-validating tagged words) into lse per row and the loss
-//   skinny_back   : dZ strip from Z and lse (never written back), dc, dV strip = Hs^T dZ,
-//                   partial G = dZ V^T over the strip, and the zero fill of dWx
-// The partial G of all strips is summed, in strip order, by the reverse-loop kernel.
+//                   self-validating tagged words) into lse per row and the loss; every strip
+//                   also leaves its share of the softmax part of G = dZ V^T, relative to its
+//                   own maximum
+//   backward strips (skinny_dev.hpp, launched together with the reverse time loop): dZ strip
+//                   from Z and lse (never written back), dc, dV strip = Hs^T dZ, zero fill of dWx
+// The reverse-loop workgroup combines the strips' shares of G with the weights
+// exp(strip max - lse), in strip order.
 //
 // Thread layout inside a strip: lane%32 = a quad of 4 adjacent columns, tid/32 = one of 16
 // groups that split the hidden dimension.  Requires NV % 4 == 0 (16-byte column quads).
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
+#include "skinny_dev.hpp"
 
 #include <type_traits>
 
 namespace rnn {
 namespace {
 
-constexpr int NR = 16;    // rows held in registers per pass
-constexpr int CW = 128;   // vocabulary columns per workgroup
-constexpr int NTH = 512;
-constexpr int QW = CW / 4;     // column quads per strip (32)
-constexpr int IG = NTH / QW;   // groups splitting the H dimension (16)
-constexpr int NWV = NTH / 64;  // wavefronts per workgroup (8)
-constexpr int NB = 8;          // independent 16-byte loads in flight per thread
+using namespace skinny;
 
-// hidden rows of one pass into LDS as hs[i][NR] (zero padded rows)
-__device__ __forceinline__ void load_rows(const float* __restrict__ Hs, float* hs, int n0, int N,
-                                          int H, int tid) {
-    const int n = H * NR;
-    for (int base = tid; base < n; base += NB * NTH) {
-        float t[NB];
-#pragma unroll
-        for (int u = 0; u < NB; ++u) {
-            const int e = base + u * NTH;
-            const int r = e / H, i = e - r * H;            // coalesced along i
-            t[u] = (e < n && n0 + r < N) ? Hs[(size_t)(n0 + r) * H + i] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < NB; ++u) {
-            const int e = base + u * NTH;
-            const int r = e / H, i = e - r * H;
-            if (e < n) hs[i * NR + r] = t[u];
-        }
-    }
-}
-
-__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int ES = CW + 4;   // padded LDS row of 128 columns
 
 __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int H = a.H, O = a.O, N = a.N;
     float* hs = smem;                 // [H][NR]
-    float* red = hs + H * NR;         // [NWV][NR][CW]
+    float* red = hs + H * NR;         // [NWV][NR][CW] partial logits; later a stage for the merge
+    float* es = red + NWV * NR * CW;  // [NR][ES] exp(z - strip max), padded rows
+    float* Vs = es + NR * ES;         // [IG*NB][ES] one batch of the strip of V, padded rows
     const int tid = threadIdx.x, kq = tid % QW, ig = tid / QW;
     const int lane = tid % kWave, wave = tid / kWave;
     const int k = blockIdx.x * CW + 4 * kq;
@@ -76,6 +56,8 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     const int kc_own = blockIdx.x * CW + tid % CW;          // column of this thread in the combine
     const float cbias = kc_own < O ? a.c[kc_own] : 0.f;
     const bool one_batch = H <= IG * NB;
+    __shared__ int s_y[32];
+    if (tid < N) s_y[tid] = a.y[tid];
 
     for (int n0 = 0; n0 < N; n0 += NR) {
         __syncthreads();
@@ -122,19 +104,86 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
             if (kc_own < O && n0 + r < N) a.Z[(size_t)(n0 + r) * O + kc_own] = z;
         }
         __syncthreads();
-        // strip statistics: one wavefront per row
-        for (int r = wave; r < NR && n0 + r < N; r += NWV) {
-            const float z0 = red[r * CW + lane], z1 = red[r * CW + 64 + lane];
-            const float m = wave_max(fmaxf(z0, z1));
-            const float e = __expf(z0 - m) + __expf(z1 - m);  // exp(-inf) = 0 for padding
-            const float s = wave_sum(e);
-            if (lane == 0) {
-                unsigned long long* st = a.stat_box + ((size_t)(n0 + r) * gridDim.x + blockIdx.x) * 2;
-                tagged_store(st, a.epoch, m);
-                tagged_store(st + 1, a.epoch, s);
-                const int y = a.y[n0 + r] - blockIdx.x * CW;
-                if (y >= 0 && y < CW)
-                    tagged_store(a.stat_box + (size_t)N * gridDim.x * 2 + n0 + r, a.epoch, red[r * CW + y]);
+        // strip statistics: one wavefront per row; the row's exp(z - strip max) stays in LDS
+        for (int r = wave; r < NR; r += NWV) {
+            float e0 = 0.f, e1 = 0.f;
+            if (n0 + r < N) {
+                const float z0 = red[r * CW + lane], z1 = red[r * CW + 64 + lane];
+                const float m = wave_max(fmaxf(z0, z1));
+                e0 = __expf(z0 - m);          // exp(-inf) = 0 for padding columns
+                e1 = __expf(z1 - m);
+                const float s = wave_sum(e0 + e1);
+                const int y = s_y[n0 + r] - blockIdx.x * CW;
+                const float zy = (y >= 0 && y < CW) ? red[r * CW + y] : 0.f;   // read before the overwrite
+                if (lane == 0) {
+                    unsigned long long* st = a.stat_box + ((size_t)(n0 + r) * gridDim.x + blockIdx.x) * 2;
+                    tagged_store(st, a.epoch, m);
+                    tagged_store(st + 1, a.epoch, s);
+                    if (y >= 0 && y < CW)
+                        tagged_store(a.stat_box + (size_t)N * gridDim.x * 2 + n0 + r, a.epoch, zy);
+                }
+            }
+            es[r * ES + lane] = e0;
+            es[r * ES + 64 + lane] = e1;
+        }
+        __syncthreads();
+        // Backward needs G = (softmax - onehot) V^T / N.  With w = exp(strip max - lse) the softmax
+        // part is sum over strips of w * P, P[r][i] = sum_c exp(z[r][c] - strip max) V[i][c], and P
+        // needs only what this workgroup already holds (its strip of V in registers, the
+        // exponentials in LDS).  Computing it here takes V and the reverse loop's input out of the
+        // backward strip pass, so that pass can run beside the reverse loop instead of before it.
+        // It is a [16 x 128] x [128 x H] product, done on the matrix cores: v_mfma_f32_16x16x4 with
+        // the rows of exponentials as A and the strip of V, parked in LDS one batch of 128 hidden
+        // rows at a time, as B; wavefront w takes the 16 hidden rows 16w.. of the batch.  Lane
+        // group g = lane/16 walks the columns 32g..32g+31, so both operands are 16-byte LDS reads
+        // (rows are ES = CW+4 words apart: 16 rows spread over all banks).
+        {
+            bool any_y = false;            // does a target of this pass fall into this strip?
+            for (int r = 0; r < NR && n0 + r < N; ++r) {
+                const int y = s_y[n0 + r] - blockIdx.x * CW;
+                any_y = any_y || (y >= 0 && y < CW);
+            }
+            const int mrow = lane % 16, g = lane / 16;
+            for (int i0 = 0; i0 < H; i0 += IG * NB) {
+                if (!one_batch) load_v(i0 + ig, v);
+#pragma unroll
+                for (int u = 0; u < NB; ++u)     // rows past H are zeros
+                    *reinterpret_cast<float4*>(Vs + (IG * u + ig) * ES + 4 * kq) = v[u];
+                __syncthreads();
+                if (any_y) {               // column y_n of V for the rows whose target is here
+                    for (int r = 0; r < NR && n0 + r < N; ++r) {
+                        const int y = s_y[n0 + r] - blockIdx.x * CW;
+                        if (y < 0 || y >= CW) continue;
+                        for (int i = tid; i < IG * NB && i0 + i < H; i += NTH)
+                            a.vy[(size_t)(n0 + r) * H + i0 + i] = Vs[i * ES + y];
+                    }
+                }
+                const int itile = i0 + 16 * wave;          // first hidden row of this wavefront's tile
+                if (itile < H) {
+                    float4 av[8], bv[8];
+#pragma unroll
+                    for (int m = 0; m < 8; ++m) {
+                        av[m] = ld4(es + mrow * ES + 32 * g + 4 * m);
+                        bv[m] = ld4(Vs + (16 * wave + mrow) * ES + 32 * g + 4 * m);
+                    }
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int m = 0; m < 8; ++m) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m].x, bv[m].x, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m].y, bv[m].y, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m].z, bv[m].z, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m].w, bv[m].w, acc, 0, 0, 0);
+                    }
+                    const int i = itile + mrow;            // result: rows 4g..4g+3 of hidden column i
+                    if (i < H) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int r = 4 * g + j;
+                            if (n0 + r < N) a.gpart[((size_t)blockIdx.x * N + n0 + r) * H + i] = acc[j];
+                        }
+                    }
+                }
+                __syncthreads();           // the next batch overwrites Vs
             }
         }
     }
@@ -212,154 +261,7 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     }
 }
 
-// Sum p[0..15] over the 32 lanes that share lane/32, leaving the total of row
-// r = 8*b4 + 4*b3 + 2*b2 + b1 (bits of lane%32) in every lane: each stage halves the number of
-// live values, so the whole reduction costs 16 shuffles instead of 80.
-__device__ __forceinline__ float quad_rows_reduce(float (&p)[NR], int lane) {
-    float q8[8], q4[4], q2[2];
-    const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float send = b4 ? p[j] : p[j + 8], keep = b4 ? p[j + 8] : p[j];
-        q8[j] = keep + __shfl_xor(send, 16, kWave);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float send = b3 ? q8[j] : q8[j + 4], keep = b3 ? q8[j + 4] : q8[j];
-        q4[j] = keep + __shfl_xor(send, 8, kWave);
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const float send = b2 ? q4[j] : q4[j + 2], keep = b2 ? q4[j + 2] : q4[j];
-        q2[j] = keep + __shfl_xor(send, 4, kWave);
-    }
-    const float send = b1 ? q2[0] : q2[1], keep = b1 ? q2[1] : q2[0];
-    float v = keep + __shfl_xor(send, 2, kWave);
-    v += __shfl_xor(v, 1, kWave);
-    return v;
-}
-
-__global__ __launch_bounds__(NTH) void skinny_back_kernel(SkinnyArgs a) {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    const int H = a.H, O = a.O, N = a.N;
-    float* hs = smem;                    // [H][NR]
-    float* dzs = hs + H * NR;            // [NR][CW]
-    float* gs = dzs + NR * CW;           // [NR][H] this strip's partial G
-    const int tid = threadIdx.x, kq = tid % QW, ig = tid / QW, lane = tid % kWave;
-    const int k0 = blockIdx.x * CW, k = k0 + 4 * kq;
-    const bool kin = k < O;
-    const float invN = 1.0f / (float)N;
-    const int myrow = ((lane & 16) ? 8 : 0) + ((lane & 8) ? 4 : 0) + ((lane & 4) ? 2 : 0) + ((lane & 2) ? 1 : 0);
-
-    auto load_v = [&](int i0, float4 (&v)[NB]) {
-#pragma unroll
-        for (int u = 0; u < NB; ++u) {
-            const int i = i0 + u * IG;
-            v[u] = (kin && i < H) ? ld4(a.V + (size_t)i * O + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    const bool one_batch = H <= IG * NB;
-    float4 v[NB];
-
-    float4 dc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int n0 = 0; n0 < N; n0 += NR) {
-        // requests first: logits, row statistics and targets of row ig, then the strip of V
-        const int nrow = n0 + ig;                     // IG == NR: group ig produces row ig
-        float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-        float l = 0.f;
-        int y = -1;
-        if (nrow < N && kin) {
-            z = ld4(a.Z + (size_t)nrow * O + k);
-            l = a.lse[nrow];
-            y = a.y[nrow] - k;
-        }
-        if (n0 == 0 || !one_batch) load_v(ig, v);
-        __syncthreads();
-        load_rows(a.Hs, hs, n0, N, H, tid);
-        {
-            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (nrow < N && kin) {
-                d.x = (__expf(z.x - l) - (y == 0 ? 1.f : 0.f)) * invN;
-                d.y = (__expf(z.y - l) - (y == 1 ? 1.f : 0.f)) * invN;
-                d.z = (__expf(z.z - l) - (y == 2 ? 1.f : 0.f)) * invN;
-                d.w = (__expf(z.w - l) - (y == 3 ? 1.f : 0.f)) * invN;
-            }
-            *reinterpret_cast<float4*>(dzs + ig * CW + 4 * kq) = d;
-        }
-        __syncthreads();
-        float4 dz[NR];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) dz[r] = ld4(dzs + r * CW + 4 * kq);
-        if (ig == 0) {
-#pragma unroll
-            for (int r = 0; r < NR; ++r) { dc.x += dz[r].x; dc.y += dz[r].y; dc.z += dz[r].z; dc.w += dz[r].w; }
-        }
-        // Overwrite and accumulate are separate instantiations: a load of the old dV inside the
-        // storing loop would make every iteration wait for the previous store's acknowledgement.
-        auto products = [&](auto accumulate) {
-            constexpr bool ACC = decltype(accumulate)::value;
-            for (int i0 = ig; i0 < H; i0 += IG * NB) {
-                if (i0 != ig) load_v(i0, v);
-#pragma unroll
-                for (int u = 0; u < NB; ++u) {
-                    const int i = i0 + u * IG;
-                    if (i >= H) continue;                       // uniform within a 32-lane group
-                    // dV[i, quad] (+)= sum_r h[r][i] dz[r]
-                    const float* hrow = hs + i * NR;
-                    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-                    float p[NR];
-#pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        const float h = hrow[r];
-                        sum.x = fmaf(h, dz[r].x, sum.x);
-                        sum.y = fmaf(h, dz[r].y, sum.y);
-                        sum.z = fmaf(h, dz[r].z, sum.z);
-                        sum.w = fmaf(h, dz[r].w, sum.w);
-                        // this quad's share of G[r][i] = sum_c dz[r][c] V[i][c]
-                        p[r] = fmaf(dz[r].x, v[u].x, fmaf(dz[r].y, v[u].y, fmaf(dz[r].z, v[u].z, dz[r].w * v[u].w)));
-                    }
-                    if (kin) {
-                        float4* dst = reinterpret_cast<float4*>(a.dV + (size_t)i * O + k);
-                        if (ACC) {
-                            const float4 old = *dst;
-                            sum.x += old.x; sum.y += old.y; sum.z += old.z; sum.w += old.w;
-                        }
-                        *dst = sum;
-                    }
-                    const float g = quad_rows_reduce(p, lane);
-                    if ((lane & 1) == 0) gs[myrow * H + i] = g;
-                }
-            }
-        };
-        if (a.beta || n0 > 0) products(std::true_type{}); else products(std::false_type{});
-        __syncthreads();
-        for (int e = tid; e < NR * H; e += NTH) {
-            const int r = e / H;
-            if (n0 + r < N) a.gpart[((size_t)blockIdx.x * N + n0 + r) * H + (e - r * H)] = gs[e];
-        }
-    }
-    if (ig == 0 && kin) {
-        float4* dst = reinterpret_cast<float4*>(a.dc + k);
-        if (a.beta) { const float4 o = *dst; dc.x += o.x; dc.y += o.y; dc.z += o.z; dc.w += o.w; }
-        *dst = dc;
-    }
-
-    // zero fill of the token-gradient matrix, an even share per workgroup (overwrite mode)
-    if (a.dWx_zero) {
-        const size_t total4 = ((size_t)a.NV * H) / 4;  // dWx is 16-byte aligned
-        const size_t per = (total4 + gridDim.x - 1) / gridDim.x;
-        const size_t b0 = (size_t)blockIdx.x * per;
-        const size_t b1 = b0 + per < total4 ? b0 + per : total4;
-        float4* z4 = reinterpret_cast<float4*>(a.dWx_zero);
-        for (size_t e = b0 + tid; e < b1; e += NTH) z4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (blockIdx.x == 0)
-            for (size_t e = total4 * 4 + tid; e < (size_t)a.NV * H; e += NTH) a.dWx_zero[e] = 0.f;
-    }
-}
-
-static_assert(IG == NR, "one group per register row");
-size_t logits_smem(int H) { return ((size_t)H * NR + (size_t)NWV * NR * CW) * 4; }
-size_t back_smem(int H) { return ((size_t)H * NR + (size_t)NR * CW + (size_t)NR * H) * 4; }
+size_t logits_smem(int H) { return ((size_t)H * NR + (size_t)NWV * NR * CW + (size_t)(NR + IG * NB) * ES) * 4; }
 
 }  // namespace
 
@@ -370,7 +272,7 @@ size_t skinny_stat_box_bytes(int N, int O) { return ((size_t)2 * N * skinny_stri
 bool skinny_supported(int N, int H, int O) {
     if (N > 32 || N < 1 || O % 4 != 0) return false;
     if (2 * skinny_strips(O) > NWV * NR * CW) return false;   // one row of strip statistics fits the LDS stage
-    return back_smem(H) <= 64 * 1024 && logits_smem(H) <= 140 * 1024;
+    return back_smem(H) <= 64 * 1024 && logits_smem(H) <= 156 * 1024;
 }
 
 hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s) {
@@ -384,12 +286,6 @@ hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s) {
     }
     ProfileScope ps(K_SKINNY_LOGITS, s);
     hipLaunchKernelGGL(skinny_logits_kernel, dim3(skinny_strips(a.O)), dim3(NTH), logits_smem(a.H), s, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_skinny_back(const SkinnyArgs& a, hipStream_t s) {
-    ProfileScope ps(K_SKINNY_BACK, s);
-    hipLaunchKernelGGL(skinny_back_kernel, dim3(skinny_strips(a.O)), dim3(NTH), back_smem(a.H), s, a);
     return hipGetLastError();
 }
 
