@@ -27,7 +27,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     // byte offsets into the workspace
-    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gpart, vy, seen,
+    size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gbox, gpart, vy, seen,
         total;
 };
 
@@ -131,6 +131,7 @@ Plan make_plan(const rnn_dims* d) {
     const size_t strips = (size_t)skinny_strips(s.O);
     const bool small = N <= 32;
     p.statbox = take(small ? skinny_stat_box_bytes((int)N, s.O) : 0);
+    p.gbox = take(small ? N * H * 8 : 0);
     p.gpart = take(small ? strips * N * H * 4 : 0);
     p.vy = take(small ? N * H * 4 : 0);
     p.seen = take(s.tokens && N >= 2048 ? (size_t)32 * s.NVin * 4 : 0);
@@ -287,7 +288,9 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         k.dWx_zero = beta ? nullptr : Gr->dWx;
         k.xids = static_cast<const int32_t*>(x);
         r.gpart = k.gpart; r.gstrips = skinny_strips(O); r.Gw = G;
-        r.stat_box = k.stat_box; r.lse = k.lse; r.vy = k.vy;
+        k.epoch = next_epoch();
+        k.g_box = at<unsigned long long>(ws, pl.gbox);
+        r.g_box = k.g_box; r.epoch = k.epoch;
         r.fuse_post = 1; r.x = static_cast<const int32_t*>(x);
         r.dWh = Gr->dWh; r.db = Gr->db; r.dWx = Gr->dWx; r.beta = beta;
         return launch_rec_bwd_with_strips(r, v.bwd, k, s);
@@ -497,6 +500,7 @@ int rnn_workspace_init(const rnn_dims* dims, void* workspace, size_t workspace_b
     if (z.N <= 32) {
         const size_t words = skinny_stat_box_bytes((int)z.N, z.O) / 4;
         if (launch_zero_words(at<int32_t>(workspace, pl.statbox), (int)words, s) != hipSuccess) return RNN_EHIP;
+        if (launch_zero_words(at<int32_t>(workspace, pl.gbox), (int)(z.N * z.H * 2), s) != hipSuccess) return RNN_EHIP;
     }
     return RNN_OK;
 }

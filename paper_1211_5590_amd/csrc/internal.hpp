@@ -67,11 +67,10 @@ struct RecResArgs {
     const float* G; const float* h_all; const float* dh_last; float* Delta; float* dh0;
     // fused weight gradients of a short single sequence (reverse, P == 1, B == 1)
     int fuse_post; float* dWh; float* db; float* dWx; int beta;
-    // Short single sequence (fuse_post): the strips' shares of G [strips][T][H], relative to
-    // each strip's maximum, with the strip statistics, lse and the target columns of V that
-    // turn them into G before the loop (gpart nullable = G is given)
+    // Short single sequence (fuse_post): G is produced by the other workgroups of the launch
+    // (gpart non-NULL marks this mode; otherwise G is given)
     const float* gpart; int gstrips; float* Gw;
-    const unsigned long long* stat_box; const float* lse; const float* vy;
+    const unsigned long long* g_box; uint32_t epoch;   // G arrives as tagged words [T][H]
 };
 struct RecResPlan { int P, R, L, ldw, w_floats, nq4, hpad; size_t smem; };
 // strips: column strips of the short-sequence output layer (fuse_post only, else 0)
@@ -135,6 +134,7 @@ struct SkinnyArgs {
     const int32_t* y;     // [N]
     float* Z;             // [N,O] logits (workspace)
     unsigned long long* stat_box;  // tagged words: [N][strips][2] strip max / sum exp, then [N] target logits
+    unsigned long long* g_box;     // tagged words: [N][H] G, from the backward strips to the reverse loop
     uint32_t epoch;       // tag of this call's words (never 0)
     int32_t* status;      // device status word: set to 1 when a bounded wait expires
     float* loss;          // device scalar written by the merging workgroup (logits kernel)

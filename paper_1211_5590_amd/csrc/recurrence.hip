@@ -88,7 +88,6 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
     float* Gl = stash + 2 * TC * 2 * R;       // fused tail only: [T][H] G, delta, h_{t-1}
     float* Dl = Gl + T * H;
     float* Hl = Dl + T * H;
-    float* wl = Hl + T * H;                   // fused tail only: [T][strips] weights of the strips' G shares
 
     // thread roles
     const int q = tid % L;                               // which share of the k range
@@ -237,70 +236,31 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
         }
     }
     if (BWD && a.gpart) {
-        // G = (sum over strips of w * share - V[:, y]) / N with w = exp(strip max - lse): the
-        // output-layer kernel left every strip's share of the softmax part relative to the
-        // strip's own maximum.  The order is fixed (a strip range per lane, then a shuffle
-        // tree), so results repeat bit for bit.  Only used with the fused tail (B == 1).
-        const int n = T * H, S = a.gstrips;
-        const float invN = 1.0f / (float)T;
-        for (int i = tid; i < T * S; i += kThreads) {
-            const int t = i / S;
-            wl[i] = __expf(tagged_value(a.stat_box[(size_t)i * 2]) - a.lse[t]);
-        }
-        __syncthreads();
-        if ((H & 3) == 0) {
-            const int n4 = n / 4, H4 = H / 4;
-            int parts = 1;
-            while (parts < 8 && parts * 2 * n4 <= kThreads) parts *= 2;
-            const int part_id = tid % parts;
-            const int per = (S + parts - 1) / parts;
-            const int sb = part_id * per, se = min(S, sb + per);
-            for (int e = tid / parts; e < n4; e += kThreads / parts) {
-                const float* w = wl + (e / H4) * S;
-                float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-                for (int s0 = sb; s0 < se; s0 += 20) {
-                    float4 t[20];
+        // G comes from the backward-strip workgroups of this launch as tagged words: all of a
+        // thread's words are requested before the first one is examined.  Only used with the
+        // fused tail (B == 1).
+        const int n = T * H;
+        for (int e0 = tid; e0 < n; e0 += 4 * kThreads) {
+            unsigned long long w[4];
 #pragma unroll
-                    for (int u = 0; u < 20; ++u)
-                        t[u] = (s0 + u < se)
-                                   ? reinterpret_cast<const float4*>(a.gpart + (size_t)(s0 + u) * n)[e]
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int u = 0; u < 4; ++u) w[u] = tagged_load(a.g_box + min(e0 + u * kThreads, n - 1));
 #pragma unroll
-                    for (int u = 0; u < 20; ++u) {
-                        const float wu = (s0 + u < se) ? w[s0 + u] : 0.f;
-                        g.x = fmaf(wu, t[u].x, g.x); g.y = fmaf(wu, t[u].y, g.y);
-                        g.z = fmaf(wu, t[u].z, g.z); g.w = fmaf(wu, t[u].w, g.w);
-                    }
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kThreads;
+                if (e >= n) continue;
+                for (int spins = 0; !tagged_ok(w[u], a.epoch); ++spins) {
+                    if (spins > a.spin_limit) { s_abort = 1; break; }
+                    w[u] = tagged_load(a.g_box + e);
                 }
-                for (int off = 1; off < parts; off <<= 1) {
-                    g.x += __shfl_xor(g.x, off, kWave);
-                    g.y += __shfl_xor(g.y, off, kWave);
-                    g.z += __shfl_xor(g.z, off, kWave);
-                    g.w += __shfl_xor(g.w, off, kWave);
-                }
-                if (part_id == 0) {
-                    const float4 vy = reinterpret_cast<const float4*>(a.vy)[e];
-                    reinterpret_cast<float4*>(Gl)[e] = make_float4((g.x - vy.x) * invN, (g.y - vy.y) * invN,
-                                                                   (g.z - vy.z) * invN, (g.w - vy.w) * invN);
-                }
-            }
-        } else {
-            for (int e = tid; e < n; e += kThreads) {
-                const float* w = wl + (e / H) * S;
-                float g = 0.f;
-                for (int s0 = 0; s0 < S; s0 += 8) {
-                    float t[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        t[u] = (s0 + u < S) ? a.gpart[(size_t)(s0 + u) * n + e] : 0.f;
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) g = fmaf((s0 + u < S) ? w[s0 + u] : 0.f, t[u], g);
-                }
-                Gl[e] = (g - a.vy[e]) * invN;
+                Gl[e] = tagged_value(w[u]);
             }
         }
     }
     __syncthreads();
+    if (BWD && a.gpart && s_abort) {   // uniform: a bounded wait expired
+        if (tid == 0) atomicExch(a.status, 1);
+        return;
+    }
 
     // ---- initial vector ------------------------------------------------------------------
     // forward: h_{-1} = h0 (or zeros), also stored as slot 0 of the history.
@@ -628,7 +588,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips
         pl.ldw = ldw;
         size_t w_floats = pl.nq4 <= 8 ? 0 : (size_t)R * ldw;   // small slices live in registers
         size_t floats = w_floats + 2 * (size_t)pl.hpad + (size_t)2 * TC * 2 * R;
-        if (fuse_post) floats += (size_t)3 * T * H + (size_t)T * strips;
+        if (fuse_post) floats += (size_t)3 * T * H;
         if (floats * 4 <= kLdsBudget) {
             pl.w_floats = (int)w_floats; pl.smem = floats * 4;
             *out = pl;

@@ -69,6 +69,41 @@ __device__ __forceinline__ float quad_rows_reduce(float (&p)[NR], int lane) {
 }
 
 
+// This workgroup's slice of G = (sum over strips of w * share - V[:, y]) / N, w = exp(strip max
+// - lse): up to 32 lanes per output walk the strips (fixed order: lane-strided partial sums, then a
+// shuffle tree), and the result is published to the reverse loop's workgroup as a tagged word.
+__device__ __forceinline__ void reduce_g_slice(const SkinnyArgs& a, int part, int nparts) {
+    const int N = a.N, H = a.H, n = N * H, S = (a.O + CW - 1) / CW;
+    const int per = (n + nparts - 1) / nparts;
+    const int o_lo = part * per, o_hi = min(n, o_lo + per);
+    int lpo = 1;                                       // lanes per output: power of two, <= 32
+    while (lpo < 32 && lpo < S) lpo *= 2;
+    const int tid = threadIdx.x, j = tid % lpo, slot = tid / lpo;
+    const float invN = 1.0f / (float)N;
+    for (int o0 = o_lo; o0 < o_hi; o0 += NTH / lpo) {
+        const int o = o0 + slot;
+        const bool live = o < o_hi;
+        const int oc = live ? o : o_hi - 1;
+        const int t = oc / H;
+        const float l = a.lse[t];
+        float sum = 0.f;
+        for (int g0 = j; g0 < S; g0 += lpo * 4) {     // up to four strips in flight per lane
+            float sh[4], m[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = min(g0 + lpo * u, S - 1);
+                sh[u] = a.gpart[(size_t)g * n + oc];
+                m[u] = tagged_value(a.stat_box[((size_t)t * S + g) * 2]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (g0 + lpo * u < S) sum = fmaf(__expf(m[u] - l), sh[u], sum);
+        }
+        for (int off = lpo / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+        if (live && j == 0) tagged_store(a.g_box + o, a.epoch, (sum - a.vy[o]) * invN);
+    }
+}
+
 // Backward pass of one strip of 128 vocabulary columns: dZ strip from Z and lse (never written
 // back), dc, dV strip = Hs^T dZ, and this workgroup's share of the zero fill of dWx.  It needs
 // neither V nor the reverse loop's results, so it runs beside the reverse loop in one launch.
@@ -81,6 +116,8 @@ __device__ __forceinline__ void back_body(const SkinnyArgs& a, int strip, int ns
     const int k0 = strip * CW, k = k0 + 4 * kq;
     const bool kin = k < O;
     const float invN = 1.0f / (float)N;
+
+    reduce_g_slice(a, strip, nstrips);   // first: the reverse loop waits for it
 
     float4 dc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int n0 = 0; n0 < N; n0 += NR) {
