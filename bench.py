@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--windows", type=int, default=None, help="override the number of C2 windows")
     ap.add_argument("--others", default="C3,C4,C5",
-                    help="comma list of further configurations reported under 'per_config' ('' = none)")
+                    help="comma list of further configurations reported under 'per_config' ('none' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
@@ -126,6 +126,7 @@ class Workload:
         for _ in range(steps):
             self.step(stream)
         prof = self.rnn.rnn_profile_end()
+        self.case["_skinny"] = "skinny_logits" in prof   # short-sequence output layer in use
         # An event pair with nothing between it does not read zero: measure that bracket cost
         # on the same stream and take it off every kernel's average (raw value kept).
         torch = self.torch
@@ -168,9 +169,9 @@ def algorithmic_work(kernel, c):
         "dwx_tokens": (f * (N * H + I * H), 1.0 * N * H),
         # time loops: the recurrent matrix once per launch, one state row in and out per step
         "rec_fwd": None, "rec_bwd": None,
-        # short-sequence output layer (column strips)
-        "skinny_logits": (f * (H * O + N * O + N * H), 2.0 * N * H * O),
-        "skinny_back": (f * (H * O + H * O + N * O + I * H), 4.0 * N * H * O),   # V in, dV out, Z in, dWx zero fill
+        # short-sequence output layer (column strips): V in, Z out, and the strips' shares of the
+        # softmax part of G (a second contraction with the same strip of V)
+        "skinny_logits": (f * (H * O + N * O + N * H), 4.0 * N * H * O),
     }
     variant = c.get("_variant", "")
     if variant == "step_mfma":      # one launch = one step: matrix + state in, state out
@@ -179,6 +180,9 @@ def algorithmic_work(kernel, c):
     else:                           # one launch = all T steps
         table["rec_fwd"] = (f * (H * H + 2 * N * H + (0 if tokens else N * H)), 2.0 * N * H * H)
         table["rec_bwd"] = (f * (H * H + 3 * N * H), 2.0 * N * H * H)
+        if c.get("_skinny"):        # the same launch runs the backward strips and the small
+            nb, nf = table["rec_bwd"]   # weight gradients: Z in, dV out, dWx zero fill, dWh out
+            table["rec_bwd"] = (nb + f * (N * O + H * O + I * H + H * H), nf + 2.0 * N * H * O + 2.0 * N * H * H)
     return table.get(kernel)
 
 
@@ -360,7 +364,7 @@ def main():
     torch.cuda.empty_cache()
 
     per = {}
-    for name in [s for s in a.others.split(",") if s and s != a.workload]:
+    for name in [s for s in a.others.split(",") if s and s != "none" and s != a.workload]:
         w = Workload(name, flags)
         wall_o, _ = w.time_steps(default_steps[name], default_warm[name])
         pr = w.profile(1)
