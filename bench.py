@@ -233,9 +233,11 @@ def _roofline_entry(name, prof, case):
                     traffic=None, avg_us=us)
     nbytes, flops = work
     sec = us * 1e-6
-    if flops / nbytes >= RIDGE:   # dense contraction above the ridge point: matrix-core bound
+    if flops / nbytes >= RIDGE:   # above the ridge point: arithmetic bound
         ach = flops / sec / 1e12
-        return dict(kernel=name, bound="mfma", achieved=ach, peak=FP32_MFMA_PEAK_TFLOPS,
+        # the batch-1..4 loops multiply on the vector ALUs (same fp32 peak as the matrix cores)
+        valu = name in ("rec_fwd", "rec_bwd") and case.get("_variant") in ("wg_resident", "grid_resident")
+        return dict(kernel=name, bound="alu" if valu else "mfma", achieved=ach, peak=FP32_MFMA_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=ach / FP32_MFMA_PEAK_TFLOPS, traffic=None, avg_us=us,
                     algorithmic_flops=flops)
     ach = nbytes / sec / 1e9
