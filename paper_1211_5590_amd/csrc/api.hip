@@ -134,7 +134,7 @@ Plan make_plan(const rnn_dims* d) {
     p.gbox = take(small ? N * H * 8 : 0);
     p.gpart = take(small ? strips * N * H * 4 : 0);
     p.vy = take(small ? N * H * 4 : 0);
-    p.seen = take(s.tokens && N >= 2048 ? (size_t)32 * s.NVin * 4 : 0);
+    p.seen = take(s.tokens && N > 32 ? dwx_table_ints((int)N, s.NVin) * 4 : 0);
     p.total = off;
     return p;
 }
@@ -358,10 +358,8 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
     // dWx
     if (z.tokens) {
         // the logits buffer is dead by now and serves as scratch for per-range partial rows
-        const bool chunked = N >= 2048;
         RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta,
-                                  chunked ? Z : nullptr, (size_t)N * O,
-                                  chunked ? at<int32_t>(ws, pl.seen) : nullptr, s));
+                                  Z, (size_t)N * O, N > 32 ? at<int32_t>(ws, pl.seen) : nullptr, s));
     } else {
         GemmArgs g{};
         g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;

@@ -153,7 +153,8 @@ hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);   // logits
 
 // ---------------------------------------------------------------------------------------
 // Token-keyed gradient of the input matrix and id validation
-// scratch (>= scratch_floats floats) and seen_flags (>= 32*NV ints) enable the chunked form
+// scratch (>= scratch_floats floats) and slot_table (>= dwx_table_ints(N, NV) ints) enable the grouped form
+size_t dwx_table_ints(int N, int NV);
 hipError_t launch_dwx_tokens(const int32_t* x, const float* Delta, float* dWx, int N, int NV,
                              int H, int beta, float* scratch, size_t scratch_floats,
                              int32_t* seen_flags, hipStream_t s);
