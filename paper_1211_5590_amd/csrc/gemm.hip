@@ -15,6 +15,8 @@
 #include "internal.hpp"
 #include "prof.hpp"
 
+#include <math.h>
+
 namespace rnn {
 namespace {
 
@@ -293,6 +295,19 @@ SplitPlan plan_split(int M, int N, int K) {
         const int by_fill = (1024 + tiles - 1) / tiles;  // aim at ~4 workgroups per CU
         splits = by_k < by_fill ? by_k : by_fill;
         if (splits < 1) splits = 1;
+    } else if (K >= 2048) {
+        // Enough tiles to fill the chip, but a whole number of tiles rarely fills whole rounds
+        // of the 256 x 3 resident workgroups: 632 tiles leave 18 % of the slots idle, 1024
+        // tiles run a second round at a third of the occupancy.  Cutting K evens the rounds
+        // out; the price is the partial-sum traffic.  Pick the cut with the least estimated time.
+        const double slots = 768.0, flops = 2.0 * M * N * (double)K, out_bytes = 4.0 * M * (double)N;
+        const double t_full = flops / 100e12;                      // at a typical achieved rate
+        double best = 1e30;
+        for (int sp = 1; sp <= 8; ++sp) {
+            const double rounds = ceil(tiles * sp / slots) / sp;    // in units of one full-K round
+            const double t = t_full * rounds * slots / tiles + (sp > 1 ? 2.0 * sp * out_bytes / 3e12 : 0.0);
+            if (t < best * 0.97) { best = t; splits = sp; }         // a cut has to pay for itself
+        }
     }
     int kchunk = (K + splits - 1) / splits;
     kchunk = (kchunk + BK - 1) / BK * BK;
