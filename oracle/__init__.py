@@ -154,3 +154,26 @@ def fwd_bptt(p, h0=None, dh_last=None):
     g = bptt(p, h_all, dh_last)
     g.update(loss=L, lse=lse, h_all=h_all)
     return g
+
+
+def train_stream(p, ids, n_windows, lr, h0=None):
+    """Plain SGD over n_windows consecutive windows of a token stream (token input, softmax-CE).
+
+    ids int32[n_windows*T + 1, B].  Returns dict: Wx, Wh, b, V, c (after the last update),
+    h_last [B,H] and losses [n_windows]; p's arrays are not modified.
+    """
+    lib = _load()
+    T, B, H = p["seq_len"], p["batch"], p["hidden"]
+    ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1, B)
+    assert ids.shape[0] >= n_windows * T + 1
+    out = {k: np.array(p[k], dtype=np.float64, order="C", copy=True) for k in ("Wx", "Wh", "b", "V", "c")}
+    h = np.zeros((B, H)) if h0 is None else np.array(h0, dtype=np.float64, order="C", copy=True).reshape(B, H)
+    losses = np.empty(n_windows, dtype=np.float64)
+    d = _dims(p)
+    rc = lib.orc_train_stream(ctypes.byref(d), _ptr(out["Wx"]), _ptr(out["Wh"]), _ptr(out["b"]),
+                              _ptr(out["V"]), _ptr(out["c"]), _ptr(ids), ctypes.c_long(n_windows),
+                              ctypes.c_double(lr), _ptr(h), _ptr(losses))
+    if rc != 0:
+        raise ValueError("orc_train_stream: bad argument")
+    out.update(h_last=h, losses=losses)
+    return out

@@ -308,3 +308,57 @@ int orc_bptt(const orc_dims *d, const double *Wx, const double *Wh, const double
     if (!delta_out) free(delta);
     return 0;
 }
+
+/* ---- many windows of a token stream with plain stochastic gradient descent --------
+ * The paper's function objects can repeat a compiled training function a given number
+ * of times without returning to the interpreter (its section on repeated calls of one
+ * function); its recurrent benchmark trains a language model that way, one truncated
+ * window after the other.  The paper gives no update rule; the plain one is used:
+ *
+ *   for w = 0 .. n_windows-1:
+ *       x = ids[w*T : w*T+T],  y = ids[w*T+1 : w*T+T+1]        (next-token targets)
+ *       h_all  = forward(params, x, h)            h = state carried from window w-1
+ *       loss_w = loss(params, h_all, y)
+ *       grads  = bptt(params, x, y, h_all)        no gradient arrives from later windows
+ *       params = params - lr * grads              all five tensors
+ *       h      = h_all[T]                         computed with the weights before the update
+ *
+ * ids: int32 [(n_windows*T + 1), B]; params are updated in place; h [B,H] holds the
+ * initial state on entry and the final state on return; losses [n_windows].
+ * Token input and softmax cross-entropy only.  Each window simply calls the three
+ * functions above.
+ */
+int orc_train_stream(const orc_dims *d, double *Wx, double *Wh, double *b, double *V, double *c,
+                     const int32_t *ids, long n_windows, double lr, double *h, double *losses)
+{
+    if (!dims_ok(d) || d->input_kind != 0 || d->loss_kind != 0 || !Wx || !Wh || !b || !V || !c ||
+        !ids || n_windows < 0 || !h || !losses)
+        return -1;
+    const int H = d->hidden, O = d->out_dim, T = d->seq_len, B = d->batch, NV = d->in_dim;
+    const size_t nWx = (size_t)NV * H, nWh = (size_t)H * H, nV = (size_t)H * O;
+    double *h_all = (double *)malloc(sizeof(double) * (size_t)(T + 1) * B * H);
+    double *dWx = (double *)malloc(sizeof(double) * nWx);
+    double *dWh = (double *)malloc(sizeof(double) * nWh);
+    double *db = (double *)malloc(sizeof(double) * H);
+    double *dV = (double *)malloc(sizeof(double) * nV);
+    double *dc = (double *)malloc(sizeof(double) * O);
+    int rc = (h_all && dWx && dWh && db && dV && dc) ? 0 : -1;
+    for (long w = 0; w < n_windows && rc == 0; ++w) {
+        const int32_t *x = ids + (size_t)w * T * B;
+        const int32_t *y = x + B; /* the same stream one step later */
+        rc = orc_forward(d, Wx, Wh, b, x, h, h_all);
+        if (rc == 0) rc = orc_loss(d, V, c, h_all, y, &losses[w], NULL, NULL);
+        if (rc == 0)
+            rc = orc_bptt(d, Wx, Wh, V, c, x, y, h_all, NULL, dWx, dWh, db, dV, dc, NULL, NULL,
+                          NULL, NULL);
+        if (rc != 0) break;
+        for (size_t e = 0; e < nWx; ++e) Wx[e] -= lr * dWx[e];
+        for (size_t e = 0; e < nWh; ++e) Wh[e] -= lr * dWh[e];
+        for (int j = 0; j < H; ++j) b[j] -= lr * db[j];
+        for (size_t e = 0; e < nV; ++e) V[e] -= lr * dV[e];
+        for (int k = 0; k < O; ++k) c[k] -= lr * dc[k];
+        for (size_t e = 0; e < (size_t)B * H; ++e) h[e] = h_all[(size_t)T * B * H + e];
+    }
+    free(h_all); free(dWx); free(dWh); free(db); free(dV); free(dc);
+    return rc;
+}

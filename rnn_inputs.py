@@ -164,3 +164,9 @@ def window(case: dict, w: int) -> dict:
         if k in case and case[k] is not None:
             out[k] = np.ascontiguousarray(case[k][w * T:(w + 1) * T])
     return out
+
+
+def stream_ids(case: dict) -> np.ndarray:
+    """The token stream of a multi-window token case as one array int32[windows*T + 1, B]:
+    x followed by the last target (y is the same stream shifted by one step)."""
+    return np.ascontiguousarray(np.concatenate([case["x"], case["y"][-1:]], axis=0), dtype=np.int32)
