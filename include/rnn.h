@@ -154,6 +154,42 @@ int rnn_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_b
 int rnn_workspace_status(const rnn_dims *dims, const void *workspace, size_t workspace_bytes,
                          void *hip_stream, int32_t *status_host);
 
+/*
+ * Many consecutive truncated-BPTT windows of ONE token stream with a plain SGD update after
+ * every window, in a single call and a single persistent launch (callers: training loops that
+ * would otherwise pay three launches per window; the paper's function objects offer the same
+ * shortcut as a repeat count on the call, returning only the last result).  The paper names
+ * no update rule; the plain one is used.  For w = 0 .. n_windows-1:
+ *
+ *     x = ids[w*T .. w*T+T-1],  y = ids[w*T+1 .. w*T+T]            (next-token targets)
+ *     h_all = forward(params, x, h);  losses[w] = loss(params, h_all, y)
+ *     params <- params - lr * gradient of that loss (all five tensors; no gradient arrives
+ *               from later windows, none is sent to earlier ones)
+ *     h <- h_{T-1} of this window (computed with the parameters before the update)
+ *
+ *   dims     token input, softmax-CE, batch 1, in_dim == out_dim, hidden <= 128, seq_len <= 32,
+ *            out_dim <= 32640 (else RNN_EUNSUPPORTED); flags: RNN_FLAG_SYNC only
+ *   params   device pointers, 16-byte aligned, UPDATED IN PLACE; while the call runs the
+ *            buffers are in an intermediate state (the model lives in on-chip memory and is
+ *            written back when the last window is done)
+ *   ids      device int32[n_windows*T + 1], values in [0, in_dim) (not checked)
+ *   h0       [H] initial state, NULL = zeros;  h_last [H] final state, NULL = not wanted
+ *   losses   device float32[n_windows], NULL = not wanted
+ *   workspace  rnn_train_stream_workspace_bytes() bytes, 16-byte aligned; needs no set-up (the
+ *            call clears what it uses) and may be shared with the other calls of this library
+ *            on the same stream
+ * Asynchronous like the other calls.  The launch is cooperative (1 + ceil(out_dim/128)
+ * workgroups that wait for each other with bounded spins); rnn_train_stream_status copies the
+ * workspace's status word to *status_host after synchronising the stream: 0 = every wait was
+ * met, 1 = a wait expired and the results of that call are invalid.
+ */
+typedef struct { float *Wx, *Wh, *b, *V, *c; } rnn_params_inout; /* device pointers */
+int rnn_train_stream_workspace_bytes(const rnn_dims *dims, size_t *bytes);
+int rnn_train_stream(const rnn_dims *dims, const rnn_params_inout *params, const int32_t *ids,
+                     int64_t n_windows, float lr, const float *h0, float *h_last, float *losses,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+int rnn_train_stream_status(const void *workspace, void *hip_stream, int32_t *status_host);
+
 /* Static description of an error code (host string, never NULL). */
 const char *rnn_strerror(int code);
 

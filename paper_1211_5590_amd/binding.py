@@ -20,7 +20,8 @@ FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
            "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
-           "rnn_workspace_status")
+           "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
+           "rnn_train_stream_status")
 
 
 class RnnError(RuntimeError):
@@ -85,6 +86,12 @@ def lib():
         L.rnn_profile_kernel_name.argtypes = [ctypes.c_int]
         L.rnn_profile_kernel_name.restype = ctypes.c_char_p
         for name in ("rnn_profile_begin", "rnn_profile_end", "rnn_profile_kernel_count"):
+            getattr(L, name).restype = ctypes.c_int
+        L.rnn_train_stream_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
+        L.rnn_train_stream.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Grads), vp, ctypes.c_int64,
+                                       ctypes.c_float, vp, vp, vp, vp, sz, vp]
+        L.rnn_train_stream_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        for name in ("rnn_train_stream_workspace_bytes", "rnn_train_stream", "rnn_train_stream_status"):
             getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens"):
             getattr(L, name).restype = ctypes.c_int
@@ -220,4 +227,28 @@ def rnn_workspace_status(dims, workspace, stream=None) -> int:
     wp, wb = _ws(workspace)
     out = ctypes.c_int32(-1)
     _check(lib().rnn_workspace_status(ctypes.byref(dims), wp, wb, _stream(stream), ctypes.byref(out)))
+    return int(out.value)
+
+
+def rnn_train_stream_workspace_bytes(dims: Dims) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().rnn_train_stream_workspace_bytes(ctypes.byref(dims), ctypes.byref(out)))
+    return int(out.value)
+
+
+def rnn_train_stream(dims, params, ids, n_windows, lr, h0, h_last, losses, workspace, stream=None,
+                     check=True):
+    """params: dict of the five parameter tensors (updated in place) or a 5-pointer struct."""
+    wp, wb = _ws(workspace)
+    pr = params if isinstance(params, Grads) else Grads(*[_p(params[k]) for k in ("Wx", "Wh", "b", "V", "c")])
+    rc = lib().rnn_train_stream(ctypes.byref(dims), ctypes.byref(pr), _p(ids), int(n_windows),
+                                float(lr), _p(h0), _p(h_last), _p(losses), wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_train_stream_status(workspace, stream=None) -> int:
+    out = ctypes.c_int32(-1)
+    _check(lib().rnn_train_stream_status(_p(workspace), _stream(stream), ctypes.byref(out)))
     return int(out.value)
