@@ -43,9 +43,9 @@ constexpr int NT = 512;          // threads per workgroup (both roles)
 constexpr int MAXH = NT / 4;     // four lanes share one hidden unit in the loop workgroup
 constexpr int MAXT = 32;         // longest window
 constexpr int CW = 128;          // vocabulary columns per strip
-constexpr int ES = CW + 16;      // LDS row stride of the strip of V: 16-byte reads by column quads
-                                 // (z) and by row groups (P) are both free of bank conflicts
-constexpr int HS = 128;          // LDS row stride of the hidden rows kept by a strip
+constexpr int ES = CW + 4;       // LDS row stride of the strip of V: the 16 rows of a 16-byte operand read
+                                 // fall into distinct banks
+constexpr int HT = 36;           // LDS row stride of the transposed hidden rows kept by a strip (>= MAXT + 4)
 constexpr int MAX_TS = 2048;     // T * strips the strip statistics stage in LDS holds
 
 struct StreamArgs {
@@ -61,6 +61,19 @@ struct StreamArgs {
     int32_t* status;
     int spin_limit;
 };
+
+// Optional phase timing for tuning (-DRNN_STREAM_TRACE): every workgroup sums the time between
+// consecutive marks over all windows (100 MHz clock) and leaves the sums in g_trace.
+#ifdef RNN_STREAM_TRACE
+__device__ long long g_trace[257 * 16];
+#define TS_DECL long long ts_prev = wall_clock64(); const long long ts_c0 = clock64(), ts_w0 = ts_prev; long long ts_acc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define TS(k) do { const long long ts_n = wall_clock64(); ts_acc[k] += ts_n - ts_prev; ts_prev = ts_n; } while (0)
+#define TS_FLUSH do { ts_acc[14] = clock64() - ts_c0; ts_acc[15] = wall_clock64() - ts_w0; if (threadIdx.x == 0) for (int k_ = 0; k_ < 16; ++k_) g_trace[blockIdx.x * 16 + k_] = ts_acc[k_]; } while (0)
+#else
+#define TS_DECL
+#define TS(k)
+#define TS_FLUSH
+#endif
 
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -113,6 +126,13 @@ __device__ __forceinline__ void lse_merge64(float& m, float& s) {
     }
 }
 
+// Every requested word is "used" here, also the clamped duplicates a batch requests past the end
+// of its range: a load whose result is never read stays pending in the compiler's bookkeeping,
+// and the wait it later inserts before reusing the register (in some unrelated loop) would also
+// wait for every store issued since.
+__device__ __forceinline__ void consume(unsigned long long v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void consume(float v) { asm volatile("" ::"v"(v)); }
+
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ float dot4(float4 a, float4 b, float acc) {
@@ -137,18 +157,30 @@ __device__ __forceinline__ void dev_store(float* p, float v) {
 }
 
 size_t loop_lds_floats(int T, int NQ) { return (size_t)(2 * (T + 1) + 5 * T) * 16 * NQ; }
-size_t strip_lds_floats(int H, int T, int S) {
-    const int HR = (H + 15) / 16 * 16;
-    return (size_t)HR * ES + CW + (size_t)T * HS + (size_t)T * CW + CW + 8 * CW + (size_t)3 * T * S;
+size_t strip_lds_floats(int NQ, int T, int S) {
+    const int HR = 16 * NQ;
+    return (size_t)HR * ES + CW + (size_t)32 * (HR + 4) + (size_t)HR * HT + (size_t)16 * (CW + 4) + (size_t)3 * T * S;
 }
 
 // ---------------------------------------------------------------------------------------
 // Workgroup 0: time loops and the recurrent-layer updates.  NQ = float4 per lane of a row of Wh.
+//
+// Nothing but the two loops is on the critical path of a window:
+//  * the rank-1 terms of the Wh update ride along with the steps (see the file header);
+//  * the rows of Wx for window w+1 are requested while the strips work on window w, i.e. before
+//    window w's update exists; the forward loop of w+1 subtracts, from the row of a token that
+//    also occurred in window w, lr * delta of those steps (their numbers come from a table built
+//    with the request); window w's own rows go to memory in the idle time of window w+1;
+//  * the per-window step tables are built in the same idle time, one window ahead.
 template <int ACT, int NQ>
 __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
     constexpr int HP = 16 * NQ;      // padded vector length
-    __shared__ int s_ids[MAXT + 1];
-    __shared__ int s_first[MAXT];
+    __shared__ int s_ids[2][MAXT + 1];   // by window parity: token of each step
+    __shared__ int s_first[2][MAXT];     // first step of the window with the same token
+    __shared__ int4 s_ch[2][MAXT];       // the next four steps of the window with the same token (-1: none)
+    __shared__ int4 s_pm[2][MAXT];       // the first four steps of the window whose token is the token of the
+                                         // same-numbered step of the FOLLOWING window (-1: none)
+    __shared__ int s_idf[MAXT + 1];      // tokens of the following window (scratch for the tables)
     __shared__ int s_abort;
     const int H = a.H, T = a.T, tid = threadIdx.x;
     const int own = tid >> 2, q = tid & 3;
@@ -157,9 +189,8 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
     float* Hl = smem;                        // [2][T+1][HP]  h_{-1} .. h_{T-1}, by window parity
     float* Dl = Hl + 2 * (T + 1) * HP;       // [T][HP] delta_t
     float* Sl = Dl + T * HP;                 // [T][HP] lr * delta_t
-    float* Fl = Sl + T * HP;                 // [T][HP] lr * delta summed per distinct token
-    float* Ul = Fl + T * HP;                 // [T][HP] rows of Wx of the window's tokens
-    float* Gl = Ul + T * HP;                 // [T][HP] G_t
+    float* Ul = Sl + T * HP;                 // [2][T][HP] rows of Wx of the window's tokens, by window parity
+    float* Gl = Ul + 2 * T * HP;             // [T][HP] G_t
     const int lds_floats = (2 * (T + 1) + 5 * T) * HP;
     for (int i = tid; i < lds_floats; i += NT) smem[i] = 0.f;   // padding must read as zero
 
@@ -178,55 +209,113 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
         wb[u] = make_float4(g[0], g[1], g[2], g[3]);
     }
     float bj = lead ? a.b[own] : 0.f;
-    int nid = tid <= T ? a.ids[tid] : 0;     // ids of window 0; later: prefetched a window ahead
+    // ids of the windows w+1 and w+2 travel in registers of the threads tid <= T
+    const int r0 = tid <= T ? a.ids[tid] : 0;
+    int r1 = (tid <= T && a.n_windows > 1) ? a.ids[(size_t)T + tid] : 0;
+    int r2 = (tid <= T && a.n_windows > 2) ? a.ids[(size_t)2 * T + tid] : 0;
     if (tid == 0) s_abort = 0;
-    __syncthreads();
-    if (lead) Hl[own] = a.h0 ? a.h0[own] : 0.f;
 
+    // step tables of the window whose tokens are in s_ids[p]; s_idf: tokens of the window after it
+    auto make_tables = [&](int p, bool has_fol) {
+        if (tid < T) {
+            const int mine = s_ids[p][tid], theirs = has_fol ? s_idf[tid] : -1;
+            int f = tid, nc = 0, np = 0;
+            int4 ch = make_int4(-1, -1, -1, -1), pm = make_int4(-1, -1, -1, -1);
+            for (int u0 = 0; u0 < T; u0 += 8) {
+                int iv[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) iv[k] = s_ids[p][min(u0 + k, T - 1)];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int idx = u0 + k;
+                    if (idx < T && iv[k] == mine) {
+                        if (idx < f) f = idx;
+                        if (idx > tid) {
+                            if (nc == 0) ch.x = idx; else if (nc == 1) ch.y = idx;
+                            else if (nc == 2) ch.z = idx; else if (nc == 3) ch.w = idx;
+                            ++nc;
+                        }
+                    }
+                    if (idx < T && iv[k] == theirs) {
+                        if (np == 0) pm.x = idx; else if (np == 1) pm.y = idx;
+                        else if (np == 2) pm.z = idx; else if (np == 3) pm.w = idx;
+                        ++np;
+                    }
+                }
+            }
+            s_first[p][tid] = f;
+            s_ch[p][tid] = ch;
+            s_pm[p][tid] = pm;
+        }
+    };
+    // sum over a token's steps of lr * delta for hidden unit `col`, steps given four at a time
+    // (wave-uniform control flow: the tables do not depend on the lane)
+    auto class_sum = [&](int4 c, int p, int col) -> float {
+        float sum = 0.f;
+        while (c.x >= 0) {
+            const float v0 = Sl[c.x * HP + col], v1 = Sl[max(c.y, 0) * HP + col];
+            const float v2 = Sl[max(c.z, 0) * HP + col], v3 = Sl[max(c.w, 0) * HP + col];
+            const int4 more = s_ch[p][max(c.w, 0)];
+            sum += v0;
+            if (c.y >= 0) sum += v1;
+            if (c.z >= 0) sum += v2;
+            if (c.w >= 0) sum += v3;
+            c = c.w >= 0 ? more : make_int4(-1, -1, -1, -1);
+        }
+        return sum;
+    };
+
+    __syncthreads();
+    if (tid <= T) { s_ids[0][tid] = r0; s_idf[tid] = r1; }
+    if (lead) Hl[own] = a.h0 ? a.h0[own] : 0.f;
+    __syncthreads();
+    make_tables(0, a.n_windows > 1);
+    if (lead) {              // rows of Wx for window 0, eight requests in flight
+        for (int t0 = 0; t0 < T; t0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = dev_load(a.Wx + (size_t)s_ids[0][min(t0 + u, T - 1)] * H + own);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (t0 + u < T) Ul[(t0 + u) * HP + own] = v[u];
+        }
+    }
+    __syncthreads();
+
+    TS_DECL;
     for (long long w = 0; w < a.n_windows; ++w) {
-        const int pw = (int)(w & 1);
+        TS(0);
+        const int pw = (int)(w & 1), pn = pw ^ 1;
         const unsigned tag = (unsigned)(w + 1);
         float* Hc = Hl + pw * (T + 1) * HP;           // this window's states
-        const float* Ho = Hl + (pw ^ 1) * (T + 1) * HP;   // the previous window's
-        if (tid <= T) {
-            s_ids[tid] = nid;
-            if (w + 1 < a.n_windows) nid = a.ids[(size_t)(w + 1) * T + tid];
-        }
-        __syncthreads();
-        if (tid < T) {       // first step at which each step's token occurs
-            int f = tid;
-            for (int u = tid - 1; u >= 0; --u)
-                if (s_ids[u] == s_ids[tid]) f = u;
-            s_first[tid] = f;
-        }
-        if (lead) {          // input vectors of the window's tokens, eight requests in flight
-            for (int t0 = 0; t0 < T; t0 += 8) {
-                float v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v[u] = dev_load(a.Wx + (size_t)s_ids[min(t0 + u, T - 1)] * H + own);
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (t0 + u < T) Ul[(t0 + u) * HP + own] = v[u];
-            }
-        }
-        __syncthreads();
+        const float* Ho = Hl + pn * (T + 1) * HP;     // the previous window's
+        float* Uc = Ul + pw * T * HP;                  // this window's rows of Wx
+        float* Uo = Ul + pn * T * HP;                  // the previous window's, then the next window's
+        const bool prev = w > 0, have_next = w + 1 < a.n_windows;
 
         // ---- forward steps; the column copy of Wh receives the previous window's update ----
+        int4 pm_cur = prev ? s_pm[pn][0] : make_int4(-1, -1, -1, -1);
         for (int s = 0; s < T; ++s) {
             const float4* v4 = reinterpret_cast<const float4*>(Hc + s * HP) + q;
             float4 x[NQ];
 #pragma unroll
             for (int u = 0; u < NQ; ++u) x[u] = v4[4 * u];
-            const float uin = lead ? Ul[s * HP + own] : 0.f;
+            float uin = Uc[s * HP + ownc];
             const int tt = T - 1 - s;                      // term of the previous update
             float4 sd[NQ];
             float ho = 0.f;
-            if (w > 0) {
+            int4 pm_nx = make_int4(-1, -1, -1, -1);
+            if (prev) {
                 const float4* s4 = reinterpret_cast<const float4*>(Sl + tt * HP) + q;
 #pragma unroll
                 for (int u = 0; u < NQ; ++u) sd[u] = s4[4 * u];
                 ho = Ho[tt * HP + ownc];
+                pm_nx = s_pm[pn][min(s + 1, T - 1)];
+                if (pm_cur.x >= 0) {   // this step's token occurred in the previous window
+                    uin -= class_sum(pm_cur, pn, ownc);
+                    if (lead) Uc[s * HP + own] = uin;
+                }
             }
             float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
@@ -239,13 +328,49 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
                 Hc[(s + 1) * HP + own] = hv;
                 tagged_store(a.hbox + (size_t)s * H + own, tag, hv);
             }
-            if (w > 0) {
+            if (prev) {
 #pragma unroll
                 for (int u = 0; u < NQ; ++u) rank1v(wb[u], sd[u], ho);
             }
+            pm_cur = pm_nx;
             lds_barrier();
         }
 
+        TS(1);
+        // ---- while the strips work: the previous window's rows of Wx go to memory, then the
+        //      tables and the rows of Wx for the next window are fetched ----
+        if (prev && lead) {
+            for (int t = 0; t < T; ++t) {
+                if (s_first[pn][t] != t) continue;
+                const int4 c = s_ch[pn][t];
+                const float sum = Sl[t * HP + own] + class_sum(c, pn, own);
+                dev_store(a.Wx + (size_t)s_ids[pn][t] * H + own, Uo[t * HP + own] - sum);
+            }
+        }
+        lds_barrier();
+        if (have_next) {
+            if (tid <= T) { s_ids[pn][tid] = r1; s_idf[tid] = r2; }
+            lds_barrier();
+            make_tables(pn, w + 2 < a.n_windows);
+            if (lead) {
+                for (int t0 = 0; t0 < T; t0 += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        v[u] = dev_load(a.Wx + (size_t)s_ids[pn][min(t0 + u, T - 1)] * H + own);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        consume(v[u]);
+                        if (t0 + u < T) Uo[(t0 + u) * HP + own] = v[u];
+                    }
+                }
+            }
+            if (tid <= T) {
+                r1 = r2;
+                if (w + 3 < a.n_windows) r2 = a.ids[(size_t)(w + 3) * T + tid];
+            }
+        }
+        TS(2);
         // ---- G from the strips -------------------------------------------------------------
         {
             const int n = T * H;
@@ -256,6 +381,7 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int e = e0 + u * NT;
+                    consume(wd[u]);
                     if (e >= n) continue;
                     for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
                         if (spins > a.spin_limit) { s_abort = 1; break; }
@@ -272,13 +398,15 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
             return;
         }
 
+        TS(3);
         // ---- reverse steps; the row copy of Wh receives this window's update ------------------
         float bsum = 0.f;
         if (lead) {
             const float h = Hc[T * HP + own];
             const float d = Gl[(T - 1) * HP + own] * act_grad<ACT>(h);
+            const float sl = a.lr * d;
             Dl[(T - 1) * HP + own] = d;
-            Sl[(T - 1) * HP + own] = a.lr * d;
+            Sl[(T - 1) * HP + own] = sl;
             bsum = d;
         }
         lds_barrier();
@@ -289,8 +417,7 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
 #pragma unroll
             for (int u = 0; u < NQ; ++u) { x[u] = d4[4 * u]; hh[u] = h4[4 * u]; }
             const float sj = Sl[(t + 1) * HP + ownc];
-            float g = 0.f, h = 0.f;
-            if (lead) { g = Gl[t * HP + own]; h = Hc[(t + 1) * HP + own]; }
+            const float g = Gl[t * HP + ownc], h = Hc[(t + 1) * HP + ownc];
             float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
             for (int u = 0; u < NQ; ++u) {
@@ -299,8 +426,9 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
             const float acc = sum4(acc0 + acc1);
             if (lead) {
                 const float d = (g + acc) * act_grad<ACT>(h);
+                const float sl = a.lr * d;
                 Dl[t * HP + own] = d;
-                Sl[t * HP + own] = a.lr * d;
+                Sl[t * HP + own] = sl;
                 bsum += d;
             }
 #pragma unroll
@@ -309,29 +437,33 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
         }
         {   // term 0: delta_0 (x) h_{-1}
             const float4* h4 = reinterpret_cast<const float4*>(Hc) + q;
+            float4 hh[NQ];
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) hh[u] = h4[4 * u];
             const float sj = Sl[ownc];
 #pragma unroll
-            for (int u = 0; u < NQ; ++u) rank1(wf[u], sj, h4[4 * u]);
+            for (int u = 0; u < NQ; ++u) rank1(wf[u], sj, hh[u]);
         }
-
-        // ---- bias, touched rows of Wx, carried state ----------------------------------------
+        TS(4);
         if (lead) {
             bj = fmaf(-a.lr, bsum, bj);
-            for (int t = 0; t < T; ++t) Fl[t * HP + own] = Sl[t * HP + own];
-            for (int u = 1; u < T; ++u) {
-                const int f = s_first[u];
-                if (f != u) Fl[f * HP + own] += Fl[u * HP + own];
-            }
-            for (int t = 0; t < T; ++t)
-                if (s_first[t] == t)
-                    dev_store(a.Wx + (size_t)s_ids[t] * H + own, Ul[t * HP + own] - Fl[t * HP + own]);
-            Hl[(pw ^ 1) * (T + 1) * HP + own] = Hc[T * HP + own];
+            Hl[pn * (T + 1) * HP + own] = Hc[T * HP + own];   // carried state
         }
-        __syncthreads();
+        lds_barrier();
+        TS(5);
     }
+    TS_FLUSH;
 
-    // ---- write the recurrent layer back --------------------------------------------------------
-    const int plast = (int)((a.n_windows - 1) & 1);
+    // ---- write the recurrent layer back: rows of Wx of the last window, Wh, b, the state --------
+    const int pl = (int)((a.n_windows - 1) & 1);
+    if (lead) {
+        const float* Uc = Ul + pl * T * HP;
+        for (int t = 0; t < T; ++t) {
+            if (s_first[pl][t] != t) continue;
+            const float sum = Sl[t * HP + own] + class_sum(s_ch[pl][t], pl, own);
+            dev_store(a.Wx + (size_t)s_ids[pl][t] * H + own, Uc[t * HP + own] - sum);
+        }
+    }
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
         const int k = 4 * (q + 4 * u);
@@ -342,136 +474,215 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
     }
     if (lead) {
         a.b[own] = bj;
-        if (a.h_last) a.h_last[own] = Hl[plast * (T + 1) * HP + T * HP + own];
+        if (a.h_last) a.h_last[own] = Hl[pl * (T + 1) * HP + T * HP + own];
     }
 }
 
+
 // ---------------------------------------------------------------------------------------
-// Workgroups 1..S: one strip of CW vocabulary columns each.
+// Workgroups 1..S: one strip of CW = 128 vocabulary columns each; wavefront w owns the 16 columns
+// 16w.. of the strip.  All three products with the strip of V run on the matrix cores
+// (v_mfma_f32_16x16x4: lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives
+// D[4(l/16)+r][l%16], r = 0..3), on up to 16 rows of the window per pass:
+//   logits   Z[n][c]  = sum_i h[n][i] V[i][c]      M = rows, N = own 16 columns, K = hidden
+//   share    P[n][i]  = sum_c e[n][c] V[i][c]      M = rows, N = 16 hidden rows per wavefront, K = columns
+//   update   D[i][c]  = sum_n h[n][i] dZ[n][c]     M = hidden, N = own 16 columns, K = rows
+// The logits of a wavefront's columns stay in its registers from the first product to the update
+// (D's layout of Z is exactly the B operand the update wants).  NQ: the hidden dimension is padded
+// to HR = 16*NQ rows of zeros; lane group kg = l/16 walks the hidden rows kg*4NQ.. in the first
+// product.  Every phase issues all its LDS reads before it computes.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int ESE = CW + 4;      // LDS row stride of the exponentials
+
+template <int NQ>
 __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, float* smem) {
+    constexpr int HR = 16 * NQ, HPP = HR + 4, KC = 4 * NQ;
     __shared__ int s_y[MAXT];
     __shared__ float lse_s[MAXT];
     __shared__ float zy_s[MAXT];
+    __shared__ float tmax[8 * 16], tsum[8 * 16];
     __shared__ int s_abort;
     const int H = a.H, T = a.T, S = a.S, NV = a.NV, tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int c4 = tid & 31, ig = tid >> 5;          // column quad, group of hidden rows
-    const int NU = (H + 15) / 16, HR = 16 * NU;
+    const int lane = tid & 63, wave = tid >> 6, m = lane & 15, kg = lane >> 4;
     const int k0 = g * CW, ncols = min(CW, NV - k0);
+    const int cown = 16 * wave + m;                  // this lane's column of the strip
     const float invN = 1.0f / (float)T;
+    const int npass = (T + 15) / 16;
     float* Vs = smem;                     // [HR][ES]
     float* cs = Vs + HR * ES;             // [CW]
-    float* hs = cs + CW;                  // [T][HS]
-    float* Zs = hs + T * HS;              // [T][CW]
-    float* es = Zs + T * CW;              // [CW]
-    float* red = es + CW;                 // [8][CW]
-    float* stage = red + 8 * CW;          // [T][S][2]
+    float* hs = cs + CW;                  // [32][HPP] hidden rows of the window (rows past T: zeros)
+    float* hsT = hs + 32 * HPP;           // [HR][HT]  the same, transposed
+    float* es = hsT + HR * HT;            // [16][ESE] exp(z - strip max) of the current pass
+    float* stage = es + 16 * ESE;         // [T][S][2]
     float* wts = stage + 2 * T * S;       // [T][S]
 
-    for (int e = tid; e < HR * CW; e += NT) {
-        const int i = e / CW, cc = e - i * CW;
-        Vs[i * ES + cc] = (i < H && cc < ncols) ? a.V[(size_t)i * NV + k0 + cc] : 0.f;
-    }
-    for (int e = tid; e < HR * (ES - CW); e += NT) {
-        const int i = e / (ES - CW), cc = e - i * (ES - CW);
-        Vs[i * ES + CW + cc] = 0.f;
+    for (int e = tid; e < HR * ES; e += NT) {
+        const int i = e / ES, cc = e - i * ES;
+        Vs[e] = (i < H && cc < ncols) ? a.V[(size_t)i * NV + k0 + cc] : 0.f;
     }
     if (tid < CW) cs[tid] = tid < ncols ? a.c[k0 + tid] : 0.f;
-    for (int e = tid; e < T * HS; e += NT) hs[e] = 0.f;
+    for (int e = tid; e < 32 * HPP; e += NT) hs[e] = 0.f;
+    for (int e = tid; e < HR * HT; e += NT) hsT[e] = 0.f;
     int ny = tid < T ? a.ids[tid + 1] : 0;           // targets of window 0
     if (tid == 0) s_abort = 0;
     __syncthreads();
 
+    TS_DECL;
     for (long long w = 0; w < a.n_windows; ++w) {
+        TS(0);
         const unsigned tag = (unsigned)(w + 1);
         if (tid < T) {
             s_y[tid] = ny;
             if (w + 1 < a.n_windows) ny = a.ids[(size_t)(w + 1) * T + tid + 1];
         }
-        // ---- rows, as the hidden states arrive ---------------------------------------------
-        for (int t = 0; t < T; ++t) {
-            // The last wavefront polls (two words per lane): it publishes nothing in this loop
-            // (for H <= 112), so its loads never queue behind stores that await their
-            // acknowledgement.
-            if (wave == NT / 64 - 1) {
+        // ---- all hidden rows of the window ---------------------------------------------------
+        {
+            const int n = T * H;
+            for (int e0 = tid; e0 < n; e0 += 4 * NT) {
+                unsigned long long wd[4];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int i = lane + 64 * u;
-                    if (i < H) {
-                        float v = 0.f;
-                        if (!tagged_wait(a.hbox + (size_t)t * H + i, tag, a.spin_limit, v)) s_abort = 1;
-                        hs[t * HS + i] = v;
-                    }
-                }
-            }
-            lds_barrier();
-            if (s_abort) {
-                if (tid == 0) atomicExch(a.status, 1);
-                return;
-            }
-            // partial logits of a column quad over this thread's hidden rows
-            {
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int u = 0; u < 4; ++u) wd[u] = tagged_load(a.hbox + min(e0 + u * NT, n - 1));
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (u < NU) {
-                        const int i = ig + 16 * u;
-                        const float h = hs[t * HS + i];
-                        const float4 v = ld4(Vs + i * ES + 4 * c4);
-                        acc.x = fmaf(h, v.x, acc.x); acc.y = fmaf(h, v.y, acc.y);
-                        acc.z = fmaf(h, v.z, acc.z); acc.w = fmaf(h, v.w, acc.w);
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * NT;
+                    consume(wd[u]);
+                    if (e >= n) continue;
+                    for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
+                        if (spins > a.spin_limit) { s_abort = 1; break; }
+                        wd[u] = tagged_load(a.hbox + e);
                     }
-                }
-                acc.x = swap32_sum(acc.x); acc.y = swap32_sum(acc.y);
-                acc.z = swap32_sum(acc.z); acc.w = swap32_sum(acc.w);
-                if (lane < 32) st4(red + wave * CW + 4 * c4, acc);
-            }
-            lds_barrier();
-            if (wave == 0) {   // logits of the strip, its maximum and sum of exponentials
-                float z0 = cs[lane], z1 = cs[64 + lane];
-#pragma unroll
-                for (int wv = 0; wv < 8; ++wv) { z0 += red[wv * CW + lane]; z1 += red[wv * CW + 64 + lane]; }
-                if (lane >= ncols) z0 = -INFINITY;
-                if (64 + lane >= ncols) z1 = -INFINITY;
-                Zs[t * CW + lane] = z0;
-                Zs[t * CW + 64 + lane] = z1;
-                const float m = max64(fmaxf(z0, z1));
-                const float e0 = __expf(z0 - m), e1 = __expf(z1 - m);
-                const float sm = sum64(e0 + e1);
-                es[lane] = e0;
-                es[64 + lane] = e1;
-                if (lane == 0) {
-                    unsigned long long* st = a.statbox + ((size_t)t * S + g) * 2;
-                    tagged_store(st, tag, m);
-                    tagged_store(st + 1, tag, sm);
-                }
-                const int yl = s_y[t] - k0;
-                if (yl >= 0 && yl < CW && lane == (yl & 63))
-                    tagged_store(a.zybox + t, tag, yl < 64 ? z0 : z1);
-            }
-            lds_barrier();
-            // share of the softmax part of G, relative to the strip maximum:
-            // P[i] = sum_c exp(z_c - m) V[i][c]; four lanes per hidden row
-            {
-                const int i = tid >> 2, q = tid & 3;
-                if (i < HR) {
-                    float p0 = 0.f, p1 = 0.f;
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const float4 e4 = ld4(es + 4 * (q + 4 * u));
-                        const float4 v4 = ld4(Vs + i * ES + 4 * (q + 4 * u));
-                        if (u & 1) p1 = dot4(e4, v4, p1); else p0 = dot4(e4, v4, p0);
-                    }
-                    const float p = sum4(p0 + p1);
-                    if (q == 0 && i < H) {
-                        tagged_store(a.pbox + ((size_t)g * T + t) * H + i, tag, p);
-                        const int yl = s_y[t] - k0;
-                        if (yl >= 0 && yl < CW) tagged_store(a.vybox + (size_t)t * H + i, tag, Vs[i * ES + yl]);
-                    }
+                    const int r = e / H, i = e - r * H;
+                    const float v = tagged_value(wd[u]);
+                    hs[r * HPP + i] = v;
+                    hsT[i * HT + r] = v;
                 }
             }
         }
+        __syncthreads();
+        if (s_abort) {
+            if (tid == 0) atomicExch(a.status, 1);
+            return;
+        }
+        TS(1);
 
+        f32x4 zreg[2];                    // logits of this lane's column, rows 4kg.. of each pass
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            zreg[ps] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (ps >= npass) continue;
+            const int n0 = 16 * ps;
+            // ---- logits of the wavefront's 16 columns for 16 rows ---------------------------
+            {
+                float4 ha[NQ];
+                float vb[KC];
+#pragma unroll
+                for (int u = 0; u < NQ; ++u) ha[u] = ld4(hs + (n0 + m) * HPP + kg * KC + 4 * u);
+#pragma unroll
+                for (int j = 0; j < KC; ++j) vb[j] = Vs[(kg * KC + j) * ES + cown];
+                const float cb = cs[cown];
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < NQ; ++u) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ha[u].x, vb[4 * u], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ha[u].y, vb[4 * u + 1], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ha[u].z, vb[4 * u + 2], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ha[u].w, vb[4 * u + 3], acc, 0, 0, 0);
+                }
+                const bool cin = cown < ncols;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = cin ? acc[r] + cb : -INFINITY;
+                zreg[ps] = acc;
+            }
+            // ---- maximum per row over the strip: 16 columns in the wavefront, 8 wavefronts via LDS ----
+            {
+                float4 tm;
+                float* tp = &tm.x;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = zreg[ps][r];
+                    v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
+                    v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
+                    tp[r] = v;
+                }
+                if (m == 0) st4(tmax + wave * 16 + 4 * kg, tm);
+            }
+            lds_barrier();
+            TS(9);
+            float mx[4];
+            {
+                float4 t8[8];
+                int yv[4];
+#pragma unroll
+                for (int wv = 0; wv < 8; ++wv) t8[wv] = ld4(tmax + wv * 16 + 4 * kg);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) yv[r] = s_y[min(n0 + 4 * kg + r, T - 1)];
+                float4 mm = t8[0];
+#pragma unroll
+                for (int wv = 1; wv < 8; ++wv) {
+                    mm.x = fmaxf(mm.x, t8[wv].x); mm.y = fmaxf(mm.y, t8[wv].y);
+                    mm.z = fmaxf(mm.z, t8[wv].z); mm.w = fmaxf(mm.w, t8[wv].w);
+                }
+                mx[0] = mm.x; mx[1] = mm.y; mx[2] = mm.z; mx[3] = mm.w;
+                float4 sm;
+                float* sp = &sm.x;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float e = __expf(zreg[ps][r] - mx[r]);
+                    es[(4 * kg + r) * ESE + cown] = e;
+                    sp[r] = sum16(e);
+                    const int n = n0 + 4 * kg + r;
+                    if (n < T && yv[r] - k0 == cown) tagged_store(a.zybox + n, tag, zreg[ps][r]);
+                }
+                if (m == 0) st4(tsum + wave * 16 + 4 * kg, sm);
+            }
+            lds_barrier();
+            TS(10);
+            if (tid < 16 && n0 + tid < T) {   // strip statistics of row n0 + tid
+                float tm8[8], ts8[8];
+#pragma unroll
+                for (int wv = 0; wv < 8; ++wv) { tm8[wv] = tmax[wv * 16 + tid]; ts8[wv] = tsum[wv * 16 + tid]; }
+                float mmx = tm8[0], ss = ts8[0];
+#pragma unroll
+                for (int wv = 1; wv < 8; ++wv) { mmx = fmaxf(mmx, tm8[wv]); ss += ts8[wv]; }
+                unsigned long long* st = a.statbox + ((size_t)(n0 + tid) * S + g) * 2;
+                tagged_store(st, tag, mmx);
+                tagged_store(st + 1, tag, ss);
+            }
+            // ---- share of the softmax part of G relative to the strip maximum -------------------
+            if (wave < NQ) {
+                float4 ea[8], vb4[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    ea[u] = ld4(es + m * ESE + 32 * kg + 4 * u);
+                    vb4[u] = ld4(Vs + (16 * wave + m) * ES + 32 * kg + 4 * u);
+                }
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[u].x, vb4[u].x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[u].y, vb4[u].y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[u].z, vb4[u].z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ea[u].w, vb4[u].w, acc, 0, 0, 0);
+                }
+                const int i = 16 * wave + m;
+                if (i < H) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int n = n0 + 4 * kg + r;
+                        if (n < T) tagged_store(a.pbox + ((size_t)g * T + n) * H + i, tag, acc[r]);
+                    }
+                }
+            }
+            if (ps + 1 < npass) lds_barrier();   // the next pass overwrites tmax, tsum and es
+        }
+        // column y_n of V for the rows whose target lies in this strip
+        for (int e = tid; e < T * H; e += NT) {
+            const int n = e / H, i = e - n * H;
+            const int yl = s_y[n] - k0;
+            if (yl >= 0 && yl < CW) tagged_store(a.vybox + e, tag, Vs[i * ES + yl]);
+        }
+
+        TS(4);
         // ---- statistics of all strips -> lse per row and the strips' weights -----------------
         {
             const int cnt = T * S * 2;
@@ -482,6 +693,7 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int idx = w0 + u * NT;
+                    consume(wd[u]);
                     if (idx >= cnt) continue;
                     for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
                         if (spins > a.spin_limit) { s_abort = 1; break; }
@@ -501,52 +713,99 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
             if (tid == 0) atomicExch(a.status, 1);
             return;
         }
-        for (int t = wave; t < T; t += NT / 64) {
-            float m = -INFINITY, sm = 0.f;
-            for (int g2 = lane; g2 < S; g2 += 64)
-                lse_merge(m, sm, stage[(t * S + g2) * 2], stage[(t * S + g2) * 2 + 1]);
-            lse_merge64(m, sm);
-            const float l = m + __logf(sm);
-            if (lane == 0) lse_s[t] = l;
-            for (int g2 = lane; g2 < S; g2 += 64) wts[t * S + g2] = __expf(stage[(t * S + g2) * 2] - l);
+        TS(5);
+        // The first batch of this strip's slice of G is requested before the row statistics are
+        // merged (the shares were published a moment ago; the merge hides the round trip).
+        const int gn = T * H, gper = (gn + S - 1) / S;
+        const int o_lo = min(gn, g * gper), o_hi = min(gn, o_lo + gper);
+        const int gj = tid & 31, gslot = tid >> 5;
+        unsigned long long pw4[4] = {0ull, 0ull, 0ull, 0ull}, vy0 = 0ull;
+        if (o_lo < o_hi) {
+            const int oc = min(o_lo + gslot, o_hi - 1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pw4[u] = tagged_load(a.pbox + (size_t)min(gj + 32 * u, S - 1) * gn + oc);
+            vy0 = tagged_load(a.vybox + oc);
+        }
+        // lse_t = M + log(sum_g s_g exp(m_g - M)), M = max_g m_g; weight of strip g:
+        // exp(m_g - lse_t) = exp(m_g - M) / sum.  32 lanes per row, strips in lane-strided order.
+        for (int t = tid >> 5; t < T; t += NT / 32) {
+            const int j = tid & 31;
+            float mg[8], sg[8];                           // S <= 256 strips: 8 per lane
+            float M = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int g2 = j + 32 * u;
+                mg[u] = g2 < S ? stage[(t * S + g2) * 2] : -INFINITY;
+                sg[u] = g2 < S ? stage[(t * S + g2) * 2 + 1] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) M = fmaxf(M, mg[u]);
+            M = fmaxf(M, dpp<0xB1>(M)); M = fmaxf(M, dpp<0x4E>(M));
+            M = fmaxf(M, dpp<0x141>(M)); M = fmaxf(M, dpp<0x140>(M));
+            {
+                const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(M), __float_as_uint(M), false, false);
+                M = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { mg[u] = __expf(mg[u] - M); sum = fmaf(sg[u], mg[u], sum); }
+            sum = sum32(sum);
+            const float rs = fast_rcp(sum);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int g2 = j + 32 * u;
+                if (g2 < S) wts[t * S + g2] = mg[u] * rs;
+            }
+            if (j == 0) lse_s[t] = M + __logf(sum);
         }
         lds_barrier();
 
+        TS(6);
         // ---- this strip's slice of G: 32 lanes per output walk the strips in a fixed order ------
+#pragma unroll
+        for (int u = 0; u < 4; ++u) consume(pw4[u]);
+        consume(vy0);
         {
-            const int n = T * H, per = (n + S - 1) / S;
-            const int o_lo = min(n, g * per), o_hi = min(n, o_lo + per);
-            const int j = tid & 31, slot = tid >> 5;
+            const int n = gn, j = gj, slot = gslot;
             for (int o0 = o_lo; o0 < o_hi; o0 += NT / 32) {
                 const int o = o0 + slot;
                 const bool have = o < o_hi;
                 const int oc = have ? o : o_hi - 1;
                 const int t = oc / H;
                 float sum = 0.f;
+                unsigned long long vyw = o0 == o_lo ? vy0 : tagged_load(a.vybox + oc);
                 for (int g0 = j; g0 < S; g0 += 32 * 4) {
                     unsigned long long wd[4];
+                    float wt[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        wd[u] = tagged_load(a.pbox + (size_t)min(g0 + 32 * u, S - 1) * n + oc);
+                    for (int u = 0; u < 4; ++u) {
+                        const int g2 = min(g0 + 32 * u, S - 1);
+                        wd[u] = (o0 == o_lo && g0 == j) ? pw4[u] : tagged_load(a.pbox + (size_t)g2 * n + oc);
+                        wt[u] = wts[t * S + g2];
+                    }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int g2 = g0 + 32 * u;
+                        consume(wd[u]);
                         if (g2 >= S) continue;
                         for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
                             if (spins > a.spin_limit) { s_abort = 1; break; }
                             wd[u] = tagged_load(a.pbox + (size_t)g2 * n + oc);
                         }
-                        sum = fmaf(wts[t * S + g2], tagged_value(wd[u]), sum);
+                        sum = fmaf(wt[u], tagged_value(wd[u]), sum);
                     }
                 }
                 sum = sum32(sum);
                 if (have && j == 0) {
-                    float vy = 0.f;
-                    if (!tagged_wait(a.vybox + oc, tag, a.spin_limit, vy)) s_abort = 1;
-                    tagged_store(a.gbox + oc, tag, (sum - vy) * invN);
+                    for (int spins = 0; !tagged_ok(vyw, tag); ++spins) {
+                        if (spins > a.spin_limit) { s_abort = 1; break; }
+                        vyw = tagged_load(a.vybox + oc);
+                    }
+                    tagged_store(a.gbox + oc, tag, (sum - tagged_value(vyw)) * invN);
                 }
             }
         }
+        TS(7);
         if (g == S - 1 && wave == 0) {
             float v = lane < T ? lse_s[lane] - zy_s[lane] : 0.f;
             v = sum64(v);
@@ -555,63 +814,64 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
 
         // ---- update of the resident columns: V -= lr Hs^T dZ, c -= lr colsum(dZ) --------------
         {
-            float4 accv[8];
+            f32x4 dz[2];
+            float dcs = 0.f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) accv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            float4 dcs = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int n0 = 0; n0 < T; n0 += 8) {
-                float4 dz[8];
+            for (int ps = 0; ps < 2; ++ps) {
+                float l[4];
+                int yv[4];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const int n = min(n0 + r, T - 1);
-                    const float4 z = ld4(Zs + n * CW + 4 * c4);
-                    const float l = lse_s[n];
-                    const int yl = s_y[n] - k0 - 4 * c4;
-                    float4 d;
-                    d.x = (__expf(z.x - l) - (yl == 0 ? 1.f : 0.f)) * invN;
-                    d.y = (__expf(z.y - l) - (yl == 1 ? 1.f : 0.f)) * invN;
-                    d.z = (__expf(z.z - l) - (yl == 2 ? 1.f : 0.f)) * invN;
-                    d.w = (__expf(z.w - l) - (yl == 3 ? 1.f : 0.f)) * invN;
-                    if (n0 + r >= T) d = make_float4(0.f, 0.f, 0.f, 0.f);
-                    dz[r] = d;
-                    dcs.x += d.x; dcs.y += d.y; dcs.z += d.z; dcs.w += d.w;
+                for (int r = 0; r < 4; ++r) {
+                    const int n = min(16 * ps + 4 * kg + r, T - 1);
+                    l[r] = lse_s[n];
+                    yv[r] = s_y[n];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (u < NU) {
-                        const int i = ig + 16 * u;
-#pragma unroll
-                        for (int r = 0; r < 8; ++r) {
-                            const float h = hs[min(n0 + r, T - 1) * HS + i];
-                            accv[u].x = fmaf(h, dz[r].x, accv[u].x); accv[u].y = fmaf(h, dz[r].y, accv[u].y);
-                            accv[u].z = fmaf(h, dz[r].z, accv[u].z); accv[u].w = fmaf(h, dz[r].w, accv[u].w);
-                        }
-                    }
+                for (int r = 0; r < 4; ++r) {
+                    const bool on = 16 * ps + 4 * kg + r < T;
+                    const float d = (__expf(zreg[ps][r] - l[r]) - (yv[r] - k0 == cown ? 1.f : 0.f)) * invN;
+                    dz[ps][r] = on ? d : 0.f;
+                    dcs += dz[ps][r];
                 }
             }
+            dcs = swap32_sum(swap16_sum(dcs));          // over the four lane groups
+            float4 ht[NQ][2];
+            float vold[NQ][4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (u < NU) {
-                    float* p = Vs + (ig + 16 * u) * ES + 4 * c4;
-                    float4 v = ld4(p);
-                    v.x = fmaf(-a.lr, accv[u].x, v.x); v.y = fmaf(-a.lr, accv[u].y, v.y);
-                    v.z = fmaf(-a.lr, accv[u].z, v.z); v.w = fmaf(-a.lr, accv[u].w, v.w);
-                    st4(p, v);
+            for (int it = 0; it < NQ; ++it) {
+                ht[it][0] = ld4(hsT + (16 * it + m) * HT + 4 * kg);
+                ht[it][1] = ld4(hsT + (16 * it + m) * HT + 16 + 4 * kg);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vold[it][r] = Vs[(16 * it + 4 * kg + r) * ES + cown];
+            }
+            const float cold = cs[cown];
+#pragma unroll
+            for (int it = 0; it < NQ; ++it) {
+                f32x4 d = {0.f, 0.f, 0.f, 0.f};
+                d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][0].x, dz[0][0], d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][0].y, dz[0][1], d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][0].z, dz[0][2], d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][0].w, dz[0][3], d, 0, 0, 0);
+                if (npass > 1) {
+                    d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][1].x, dz[1][0], d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][1].y, dz[1][1], d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][1].z, dz[1][2], d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][1].w, dz[1][3], d, 0, 0, 0);
                 }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    Vs[(16 * it + 4 * kg + r) * ES + cown] = fmaf(-a.lr, d[r], vold[it][r]);
             }
-            if (ig == 0) {
-                float4 v = ld4(cs + 4 * c4);
-                v.x = fmaf(-a.lr, dcs.x, v.x); v.y = fmaf(-a.lr, dcs.y, v.y);
-                v.z = fmaf(-a.lr, dcs.z, v.z); v.w = fmaf(-a.lr, dcs.w, v.w);
-                st4(cs + 4 * c4, v);
-            }
+            if (kg == 0) cs[cown] = fmaf(-a.lr, dcs, cold);
         }
         __syncthreads();
         if (s_abort) {   // a wait in the G slice expired
             if (tid == 0) atomicExch(a.status, 1);
             return;
         }
+        TS(8);
     }
+    TS_FLUSH;
 
     // ---- write the columns back --------------------------------------------------------------
     for (int e = tid; e < H * CW; e += NT) {
@@ -625,7 +885,7 @@ template <int ACT, int NQ>
 __global__ __launch_bounds__(NT) void train_stream_kernel(StreamArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     if (blockIdx.x == 0) loop_body<ACT, NQ>(a, smem);
-    else strip_body(a, (int)blockIdx.x - 1, smem);
+    else strip_body<NQ>(a, (int)blockIdx.x - 1, smem);
 }
 
 template <int ACT>
@@ -674,7 +934,7 @@ int stream_supported(const rnn_dims* d) {
     if (d->hidden > MAXH || d->seq_len > MAXT) return RNN_EUNSUPPORTED;
     const int S = (d->out_dim + CW - 1) / CW;
     if (S + 1 > 256 || d->seq_len * S > MAX_TS) return RNN_EUNSUPPORTED;
-    if (strip_lds_floats(d->hidden, d->seq_len, S) * 4 > 158 * 1024) return RNN_EUNSUPPORTED;
+    if (strip_lds_floats(pick_nq(d->hidden), d->seq_len, S) * 4 > 158 * 1024) return RNN_EUNSUPPORTED;
     if (loop_lds_floats(d->seq_len, pick_nq(d->hidden)) * 4 > 158 * 1024) return RNN_EUNSUPPORTED;
     return RNN_OK;
 }
@@ -737,7 +997,7 @@ int rnn_train_stream(const rnn_dims* dims, const rnn_params_inout* params, const
     const int nq = pick_nq(a.H);
     const void* fn = dims->act == RNN_ACT_SIGMOID ? pick_kernel<0>(nq) : pick_kernel<1>(nq);
     size_t lds = loop_lds_floats(a.T, nq);
-    if (strip_lds_floats(a.H, a.T, a.S) > lds) lds = strip_lds_floats(a.H, a.T, a.S);
+    if (strip_lds_floats(nq, a.T, a.S) > lds) lds = strip_lds_floats(nq, a.T, a.S);
     lds *= 4;
     if (lds > 64 * 1024)
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -753,6 +1013,12 @@ int rnn_train_stream(const rnn_dims* dims, const rnn_params_inout* params, const
         if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
     return RNN_OK;
 }
+
+#ifdef RNN_STREAM_TRACE
+int rnn_train_stream_trace(long long* host_out, int n) {
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(rnn::g_trace), (size_t)n * 8) == hipSuccess ? RNN_OK : RNN_EHIP;
+}
+#endif
 
 int rnn_train_stream_status(const void* workspace, void* hip_stream, int32_t* status_host) {
     if (!workspace || !status_host) return RNN_EINVAL;
