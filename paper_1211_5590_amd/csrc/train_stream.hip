@@ -22,9 +22,9 @@
 //
 // dV and dWx are never materialised: V <- V - lr Hs^T dZ is applied to the resident columns, and
 // only the rows of Wx whose tokens occur in the window are rewritten.  The rank-T update of Wh is
-// folded into the time loops one rank-1 term per step (row form during the reverse loop, column
-// form during the next window's forward loop, same order and same operands, so both copies stay
-// bit-identical), where it fills issue slots the latency-bound steps leave idle.
+// applied one rank-1 term at a time: to the row copy during the reverse loop, where it fills issue
+// slots the latency-bound steps leave idle, and to the column copy while the loop workgroup waits
+// for the next window's G (same order and same operands, so both copies stay bit-identical).
 //
 // Every wait is bounded; a wait that expires sets the status word and makes its workgroup leave,
 // after which the others run into their own limits, so the grid always drains.
@@ -132,6 +132,39 @@ __device__ __forceinline__ void lse_merge64(float& m, float& s) {
 // wait for every store issued since.
 __device__ __forceinline__ void consume(unsigned long long v) { asm volatile("" ::"v"(v)); }
 __device__ __forceinline__ void consume(float v) { asm volatile("" ::"v"(v)); }
+
+// Waits for N tagged words at once (act[u] false marks an unused slot).  All stale words are
+// requested again together, so words that arrive while the batch is being polled cost one more
+// round trip in total, not one each.  Returns false when the bounded wait expires.
+template <int N>
+__device__ __forceinline__ bool wait_n(const unsigned long long* const (&ptr)[N], const bool (&act)[N],
+                                       unsigned tag, int spin_limit, unsigned long long (&w)[N]) {
+#pragma unroll
+    for (int u = 0; u < N; ++u) w[u] = tagged_load(ptr[u]);
+    bool ok = true;
+    for (int spins = 0;; ++spins) {
+        bool stale = false;
+#pragma unroll
+        for (int u = 0; u < N; ++u) stale = stale || (act[u] && !tagged_ok(w[u], tag));
+        if (!stale) break;
+        if (spins > spin_limit) { ok = false; break; }
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            if (act[u] && !tagged_ok(w[u], tag)) w[u] = tagged_load(ptr[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < N; ++u) consume(w[u]);
+    return ok;
+}
+// four words base[idx[u]]; idx[u] < 0 marks an unused slot
+__device__ __forceinline__ bool wait4(const unsigned long long* base, const long long (&idx)[4], unsigned tag,
+                                      int spin_limit, unsigned long long (&w)[4]) {
+    const unsigned long long* ptr[4];
+    bool act[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { act[u] = idx[u] >= 0; ptr[u] = base + (act[u] ? idx[u] : 0); }
+    return wait_n<4>(ptr, act, tag, spin_limit, w);
+}
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
@@ -294,7 +327,7 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
         float* Uo = Ul + pn * T * HP;                  // the previous window's, then the next window's
         const bool prev = w > 0, have_next = w + 1 < a.n_windows;
 
-        // ---- forward steps; the column copy of Wh receives the previous window's update ----
+        // ---- forward steps ----
         int4 pm_cur = prev ? s_pm[pn][0] : make_int4(-1, -1, -1, -1);
         for (int s = 0; s < T; ++s) {
             const float4* v4 = reinterpret_cast<const float4*>(Hc + s * HP) + q;
@@ -302,15 +335,8 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
 #pragma unroll
             for (int u = 0; u < NQ; ++u) x[u] = v4[4 * u];
             float uin = Uc[s * HP + ownc];
-            const int tt = T - 1 - s;                      // term of the previous update
-            float4 sd[NQ];
-            float ho = 0.f;
             int4 pm_nx = make_int4(-1, -1, -1, -1);
             if (prev) {
-                const float4* s4 = reinterpret_cast<const float4*>(Sl + tt * HP) + q;
-#pragma unroll
-                for (int u = 0; u < NQ; ++u) sd[u] = s4[4 * u];
-                ho = Ho[tt * HP + ownc];
                 pm_nx = s_pm[pn][min(s + 1, T - 1)];
                 if (pm_cur.x >= 0) {   // this step's token occurred in the previous window
                     uin -= class_sum(pm_cur, pn, ownc);
@@ -328,10 +354,6 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
                 Hc[(s + 1) * HP + own] = hv;
                 tagged_store(a.hbox + (size_t)s * H + own, tag, hv);
             }
-            if (prev) {
-#pragma unroll
-                for (int u = 0; u < NQ; ++u) rank1v(wb[u], sd[u], ho);
-            }
             pm_cur = pm_nx;
             lds_barrier();
         }
@@ -339,6 +361,17 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
         TS(1);
         // ---- while the strips work: the previous window's rows of Wx go to memory, then the
         //      tables and the rows of Wx for the next window are fetched ----
+        if (prev) {   // column copy of Wh: the previous window's update, same terms in the same order
+            for (int tt = T - 1; tt >= 0; --tt) {
+                const float4* s4 = reinterpret_cast<const float4*>(Sl + tt * HP) + q;
+                float4 sd[NQ];
+#pragma unroll
+                for (int u = 0; u < NQ; ++u) sd[u] = s4[4 * u];
+                const float ho = Ho[tt * HP + ownc];
+#pragma unroll
+                for (int u = 0; u < NQ; ++u) rank1v(wb[u], sd[u], ho);
+            }
+        }
         if (prev && lead) {
             for (int t = 0; t < T; ++t) {
                 if (s_first[pn][t] != t) continue;
@@ -376,17 +409,14 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
             const int n = T * H;
             for (int e0 = tid; e0 < n; e0 += 4 * NT) {
                 unsigned long long wd[4];
+                long long idx[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) wd[u] = tagged_load(a.gbox + min(e0 + u * NT, n - 1));
+                for (int u = 0; u < 4; ++u) idx[u] = e0 + u * NT < n ? e0 + u * NT : -1;
+                if (!wait4(a.gbox, idx, tag, a.spin_limit, wd)) s_abort = 1;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int e = e0 + u * NT;
-                    consume(wd[u]);
                     if (e >= n) continue;
-                    for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
-                        if (spins > a.spin_limit) { s_abort = 1; break; }
-                        wd[u] = tagged_load(a.gbox + e);
-                    }
                     const int t = e / H;
                     Gl[t * HP + (e - t * H)] = tagged_value(wd[u]);
                 }
@@ -540,17 +570,14 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
             const int n = T * H;
             for (int e0 = tid; e0 < n; e0 += 4 * NT) {
                 unsigned long long wd[4];
+                long long idx[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) wd[u] = tagged_load(a.hbox + min(e0 + u * NT, n - 1));
+                for (int u = 0; u < 4; ++u) idx[u] = e0 + u * NT < n ? e0 + u * NT : -1;
+                if (!wait4(a.hbox, idx, tag, a.spin_limit, wd)) s_abort = 1;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int e = e0 + u * NT;
-                    consume(wd[u]);
                     if (e >= n) continue;
-                    for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
-                        if (spins > a.spin_limit) { s_abort = 1; break; }
-                        wd[u] = tagged_load(a.hbox + e);
-                    }
                     const int r = e / H, i = e - r * H;
                     const float v = tagged_value(wd[u]);
                     hs[r * HPP + i] = v;
@@ -688,19 +715,13 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
             const int cnt = T * S * 2;
             for (int w0 = tid; w0 < cnt; w0 += 4 * NT) {
                 unsigned long long wd[4];
+                long long idx[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) wd[u] = tagged_load(a.statbox + min(w0 + u * NT, cnt - 1));
+                for (int u = 0; u < 4; ++u) idx[u] = w0 + u * NT < cnt ? w0 + u * NT : -1;
+                if (!wait4(a.statbox, idx, tag, a.spin_limit, wd)) s_abort = 1;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = w0 + u * NT;
-                    consume(wd[u]);
-                    if (idx >= cnt) continue;
-                    for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
-                        if (spins > a.spin_limit) { s_abort = 1; break; }
-                        wd[u] = tagged_load(a.statbox + idx);
-                    }
-                    stage[idx] = tagged_value(wd[u]);
-                }
+                for (int u = 0; u < 4; ++u)
+                    if (w0 + u * NT < cnt) stage[w0 + u * NT] = tagged_value(wd[u]);
             }
             if (g == S - 1 && tid < T) {   // target logits, for the loss (read before G is published)
                 float v = 0.f;
@@ -777,23 +798,27 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
                 for (int g0 = j; g0 < S; g0 += 32 * 4) {
                     unsigned long long wd[4];
                     float wt[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int g2 = min(g0 + 32 * u, S - 1);
-                        wd[u] = (o0 == o_lo && g0 == j) ? pw4[u] : tagged_load(a.pbox + (size_t)g2 * n + oc);
-                        wt[u] = wts[t * S + g2];
-                    }
+                    long long idx[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int g2 = g0 + 32 * u;
-                        consume(wd[u]);
-                        if (g2 >= S) continue;
-                        for (int spins = 0; !tagged_ok(wd[u], tag); ++spins) {
-                            if (spins > a.spin_limit) { s_abort = 1; break; }
-                            wd[u] = tagged_load(a.pbox + (size_t)g2 * n + oc);
-                        }
-                        sum = fmaf(wt[u], tagged_value(wd[u]), sum);
+                        idx[u] = g2 < S ? (long long)g2 * n + oc : -1;
+                        wt[u] = wts[t * S + min(g2, S - 1)];
                     }
+                    if (o0 == o_lo && g0 == j) {   // requested before the merge of the statistics
+                        bool stale = false;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            wd[u] = pw4[u];
+                            stale = stale || (idx[u] >= 0 && !tagged_ok(wd[u], tag));
+                        }
+                        if (stale && !wait4(a.pbox, idx, tag, a.spin_limit, wd)) s_abort = 1;
+                    } else if (!wait4(a.pbox, idx, tag, a.spin_limit, wd)) {
+                        s_abort = 1;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (idx[u] >= 0) sum = fmaf(wt[u], tagged_value(wd[u]), sum);
                 }
                 sum = sum32(sum);
                 if (have && j == 0) {
