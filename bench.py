@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--others", default="C3,C4,C5",
                     help="comma list of further configurations reported under 'per_config' ('none' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-train-stream", action="store_true",
+                    help="skip the single-launch SGD driver leg of the headline workload")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -307,6 +309,56 @@ def cpu_baseline(name, budget_s):
                 seconds=dt)
 
 
+def train_stream_leg(windows, reps=3, lr=0.1):
+    """The whole C2 stream in ONE call of rnn_train_stream (persistent launch, SGD after every
+    window): time of the launch from HIP events on its stream, tokens/s, and what the launch does
+    per window against the matrix-core rate of the compute units it occupies."""
+    import numpy as np
+    import torch
+    import paper_1211_5590_amd as rnn
+    import rnn_inputs as ri
+    case = ri.make_config("C2", **({"windows": windows} if windows else {}))
+    W, T, H, NV = case["windows"], case["seq_len"], case["hidden"], case["out_dim"]
+    dims = rnn.Dims.of(case)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    p0 = {k: dev(case[k]) for k in ("Wx", "Wh", "b", "V", "c")}
+    ids = dev(ri.stream_ids(case).reshape(-1))
+    losses = torch.zeros(W, device="cuda")
+    h_last = torch.zeros(H, device="cuda")
+    ws = torch.empty(rnn.rnn_train_stream_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
+    times = []
+    for rep in range(reps + 1):                      # first repetition is the warm-up
+        p = {k: v.clone() for k, v in p0.items()}
+        torch.cuda.synchronize()
+        rnn.rnn_profile_begin(16)
+        rnn.rnn_train_stream(dims, p, ids, W, lr, None, h_last, losses, ws)
+        prof = rnn.rnn_profile_end()
+        assert rnn.rnn_train_stream_status(ws) == 0, "a bounded wait expired"
+        if rep:
+            times.append(prof["train_stream"][1] / 1e3)
+    sec = sorted(times)[len(times) // 2]
+    strips = (NV + 127) // 128
+    n_cu = 1 + strips
+    # per window: logits, shares of G and the update of V (2 N H NV each), both time loops and both
+    # copies of Wh (2 T H^2 each)
+    flops = W * (6.0 * T * H * NV + 8.0 * T * H * H)
+    peak = n_cu * 256 * 2.4e9 / 1e12                # fp32 matrix rate of the occupied units, TFLOP/s
+    lo = losses.cpu().numpy()
+    return {
+        "entry_point": "rnn_train_stream", "windows": W, "lr": lr, "workgroups": n_cu,
+        "tokens_per_s": W * T / sec, "us_per_window": 1e6 * sec / W, "ms_per_stream": 1e3 * sec,
+        "loss_first_window": float(lo[0]), "loss_mean_last_100_windows": float(lo[-100:].mean()),
+        "roofline": {"kernel": "train_stream", "bound": "mfma", "achieved": flops / sec / 1e12,
+                     "peak": peak, "unit": "TFLOP/s", "frac": flops / sec / 1e12 / peak,
+                     "traffic": None, "n_cu": n_cu, "avg_us": 1e6 * sec,
+                     "algorithmic_flops": flops,
+                     "note": "one launch per stream; the model stays on chip (HBM sees the ids, the "
+                             "touched rows of Wx and the losses), so the ceiling stated is the matrix "
+                             "rate of the occupied compute units; the launch is bound by the latency "
+                             "of its dependent steps and exchanges"},
+    }
+
+
 def describe(c):
     return dict(in_dim=c["in_dim"], hidden=c["hidden"], out_dim=c["out_dim"], seq_len=c["seq_len"],
                 batch=c["batch"], windows=c["windows"],
@@ -381,6 +433,9 @@ def main():
         torch.cuda.empty_cache()
     if per:
         out["per_config"] = per
+
+    if a.workload == "C2" and not a.reference_kernels and not a.no_train_stream:
+        out["train_stream"] = train_stream_leg(a.windows)
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)

@@ -148,6 +148,7 @@ __device__ __forceinline__ bool wait_n(const unsigned long long* const (&ptr)[N]
         for (int u = 0; u < N; ++u) stale = stale || (act[u] && !tagged_ok(w[u], tag));
         if (!stale) break;
         if (spins > spin_limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);   // a short pause keeps the pollers from crowding the memory pipeline
 #pragma unroll
         for (int u = 0; u < N; ++u)
             if (act[u] && !tagged_ok(w[u], tag)) w[u] = tagged_load(ptr[u]);

@@ -81,3 +81,29 @@ def test_strerror_and_variant_names():
     assert rnn.rnn_recurrence_variant(good_dims()) in ("wg_resident", "grid_resident", "batch_mfma", "step_mfma", "reference")
     assert rnn.rnn_recurrence_workgroups(good_dims()) >= 1
     assert rnn.rnn_recurrence_workgroups(good_dims(hidden=256, batch=128)) == 32   # 4 rows each
+
+
+def test_train_stream_rejects_what_it_cannot_run_without_a_gpu():
+    ok = good_dims(seq_len=10, hidden=100, in_dim=10000, out_dim=10000)
+    assert rnn.rnn_train_stream_workspace_bytes(ok) > 0
+    for bad, code in ((dict(batch=2), -3), (dict(hidden=129), -3), (dict(seq_len=33), -3),
+                      (dict(out_dim=128), -3), (dict(input_kind=1), -3), (dict(loss_kind=1), -3),
+                      (dict(in_dim=40000, out_dim=40000), -3), (dict(hidden=0), -1), (dict(act=7), -1),
+                      (dict(flags=1), -1)):
+        with pytest.raises(rnn.RnnError) as e:
+            rnn.rnn_train_stream_workspace_bytes(good_dims(**bad))
+        assert e.value.code == code, bad
+    L = rnn.lib()
+    fake = 0x1000
+    P = rnn.Grads(fake, fake, fake, fake, fake)
+    need = rnn.rnn_train_stream_workspace_bytes(ok)
+    call = lambda params, ids, n, ws, nbytes: L.rnn_train_stream(
+        ctypes.byref(ok), ctypes.byref(params) if params else None, ids, n, 0.1, None, None, None, ws, nbytes, None)
+    assert call(None, fake, 1, fake, need) == -1
+    assert call(rnn.Grads(fake, None, fake, fake, fake), fake, 1, fake, need) == -1
+    assert call(P, None, 1, fake, need) == -1
+    assert call(P, fake + 2, 1, fake, need) == -1
+    assert call(P, fake, -1, fake, need) == -1
+    assert call(P, fake, 1, None, need) == -2
+    assert call(P, fake, 1, fake, need - 1) == -2
+    assert call(P, fake, 0, fake, need) == 0          # nothing to do: nothing is launched

@@ -75,3 +75,67 @@ def test_rnnlm_shape_300_windows():
     # rows of Wx whose token never occurs are untouched, bit for bit
     unseen = np.setdiff1d(np.arange(case["in_dim"]), ids[:W * case["seq_len"]].reshape(-1))
     np.testing.assert_array_equal(got["Wx"][unseen], case["Wx"][unseen])
+
+
+def test_rnnlm_shape_2000_windows_and_run_to_run_identical():
+    # long enough for rounding differences of the float32 trajectory to show if they grew
+    W, lr = 2000, 0.1
+    print("case C2 x 2000 windows", flush=True)
+    case = ri.make_config("C2", windows=W)
+    ids = ri.stream_ids(case)
+    ref = oracle.train_stream(case, ids, W, lr)
+    got = run_gpu_stream(case, ids, W, lr)
+    compare_stream(got, ref, W)
+    assert got["losses"][-200:].mean() < got["losses"][:20].mean() - 1.0     # it learns the unigram statistics
+    again = run_gpu_stream(case, ids, W, lr)
+    for k in PNAMES + ("losses", "h_last"):
+        np.testing.assert_array_equal(got[k], again[k])
+
+
+def test_windows_can_be_split_over_calls():
+    # two calls of 3 windows with the state carried equal one call of 6 windows, bit for bit
+    case = ri.make_case(batch=1, wdist=("normal", 0.3), bias_std=0.1, seed=99, in_dim=500, hidden=64,
+                        out_dim=500, seq_len=7, windows=6)
+    ids = ri.stream_ids(case)
+    T, lr = case["seq_len"], 0.2
+    one = run_gpu_stream(case, ids, 6, lr)
+    first = run_gpu_stream(case, ids[:3 * T + 1], 3, lr)
+    mid = dict(case)
+    mid.update({k: first[k] for k in PNAMES})
+    second = run_gpu_stream(mid, ids[3 * T:], 3, lr, h0=first["h_last"])
+    for k in PNAMES + ("h_last",):
+        np.testing.assert_array_equal(one[k], second[k])
+    np.testing.assert_array_equal(one["losses"], np.concatenate([first["losses"], second["losses"]]))
+
+
+def test_zero_windows_and_unsupported_shapes():
+    case = ri.make_config("C1", seq_len=8, windows=2)
+    dims = rnn.Dims.of(case)
+    params = {k: dev(case[k]) for k in PNAMES}
+    before = {k: v.clone() for k, v in params.items()}
+    ws = torch.zeros(rnn.rnn_train_stream_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
+    rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 0, 0.1, None, None, None, ws)
+    torch.cuda.synchronize()
+    for k in PNAMES:
+        assert torch.equal(params[k], before[k])
+
+
+def test_expired_wait_sets_the_status_word_and_the_grid_drains(monkeypatch):
+    # failure handling forced from the host: with a spin limit of one poll the waits between the
+    # workgroups expire at once; every workgroup must leave, and the status word must say so
+    monkeypatch.setenv("RNN_STREAM_SPIN_LIMIT", "1")
+    case = ri.make_config("C2", windows=4)
+    dims = rnn.Dims.of(case)
+    params = {k: dev(case[k]) for k in PNAMES}
+    ws = torch.zeros(rnn.rnn_train_stream_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
+    rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 4, 0.1, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert rnn.rnn_train_stream_status(ws) == 1
+    monkeypatch.delenv("RNN_STREAM_SPIN_LIMIT")
+    params = {k: dev(case[k]) for k in PNAMES}     # and the next call on the same workspace is fine
+    losses = torch.zeros(4, device="cuda")
+    rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 4, 0.1, None, None, losses, ws)
+    torch.cuda.synchronize()
+    assert rnn.rnn_train_stream_status(ws) == 0
+    ref = oracle.train_stream(case, ri.stream_ids(case), 4, 0.1)
+    np.testing.assert_allclose(losses.cpu().numpy(), ref["losses"], rtol=1e-4)
