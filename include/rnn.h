@@ -190,6 +190,30 @@ int rnn_train_stream(const rnn_dims *dims, const rnn_params_inout *params, const
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 int rnn_train_stream_status(const void *workspace, void *hip_stream, int32_t *status_host);
 
+/*
+ * One truncated-BPTT window in ONE launch: what rnn_forward -> rnn_loss -> rnn_bptt compute
+ * together (same equations, same outputs), for callers that step through a stream window by
+ * window and would otherwise pay three launches per window.  Serves the paper's benchmark shape
+ * (its recurrent-network benchmark section: batch 1, vocabulary-sized output layer, short
+ * windows): token input, softmax-CE, batch 1, hidden <= 128, seq_len <= 32, out_dim <= 32640;
+ * anything else returns RNN_EUNSUPPORTED and the three calls above serve it.
+ *   x, targets  device int32[T] (4-byte aligned; a window may start anywhere in a stream)
+ *   h0, dh_last [H], NULL = zeros;  h_all [T+1][H], h_last [H], dh0 [H]: NULL = not wanted
+ *   loss        device float32[1];  grads as in rnn_bptt (RNN_FLAG_ACCUMULATE adds)
+ *   workspace   rnn_window_workspace_bytes() bytes, 16-byte aligned, cleared ONCE with
+ *               rnn_window_workspace_init before its first use (the workgroups of the launch
+ *               exchange words that carry a per-call tag; cleared memory is "not written yet")
+ * The launch is cooperative (1 + ceil(out_dim/128) workgroups with bounded waits);
+ * rnn_train_stream_status reads the status word of this workspace as well.
+ */
+int rnn_window_workspace_bytes(const rnn_dims *dims, size_t *bytes);
+int rnn_window_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+int rnn_window(const rnn_dims *dims, const rnn_params *params, const int32_t *x,
+               const int32_t *targets, const float *h0, const float *dh_last, float *h_all,
+               float *h_last, float *loss, const rnn_grads *grads, float *dh0,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static description of an error code (host string, never NULL). */
 const char *rnn_strerror(int code);
 

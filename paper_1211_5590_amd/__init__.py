@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     rnn_profile_begin, rnn_profile_end, rnn_recurrence_variant, rnn_recurrence_workgroups, rnn_strerror,
     rnn_workspace_bytes, rnn_workspace_init, rnn_workspace_status,
     rnn_train_stream, rnn_train_stream_status, rnn_train_stream_workspace_bytes,
+    rnn_window, rnn_window_workspace_bytes, rnn_window_workspace_init,
 )

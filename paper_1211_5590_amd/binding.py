@@ -21,7 +21,8 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
-           "rnn_train_stream_status")
+           "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
+           "rnn_window")
 
 
 class RnnError(RuntimeError):
@@ -91,7 +92,12 @@ def lib():
         L.rnn_train_stream.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Grads), vp, ctypes.c_int64,
                                        ctypes.c_float, vp, vp, vp, vp, sz, vp]
         L.rnn_train_stream_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
-        for name in ("rnn_train_stream_workspace_bytes", "rnn_train_stream", "rnn_train_stream_status"):
+        L.rnn_window_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
+        L.rnn_window_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
+        L.rnn_window.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp,
+                                 ctypes.POINTER(Grads), vp, vp, sz, vp]
+        for name in ("rnn_train_stream_workspace_bytes", "rnn_train_stream", "rnn_train_stream_status",
+                     "rnn_window_workspace_bytes", "rnn_window_workspace_init", "rnn_window"):
             getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens"):
             getattr(L, name).restype = ctypes.c_int
@@ -252,3 +258,26 @@ def rnn_train_stream_status(workspace, stream=None) -> int:
     out = ctypes.c_int32(-1)
     _check(lib().rnn_train_stream_status(_p(workspace), _stream(stream), ctypes.byref(out)))
     return int(out.value)
+
+
+def rnn_window_workspace_bytes(dims: Dims) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().rnn_window_workspace_bytes(ctypes.byref(dims), ctypes.byref(out)))
+    return int(out.value)
+
+
+def rnn_window_workspace_init(dims, workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(lib().rnn_window_workspace_init(ctypes.byref(dims), wp, wb, _stream(stream)))
+
+
+def rnn_window(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0, workspace,
+               stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr, gr = _params(params), _grads(grads)
+    rc = lib().rnn_window(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(targets), _p(h0), _p(dh_last),
+                          _p(h_all), _p(h_last), _p(loss), ctypes.byref(gr), _p(dh0), wp, wb,
+                          _stream(stream))
+    if check:
+        _check(rc)
+    return rc

@@ -32,6 +32,8 @@
 
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -49,9 +51,16 @@ constexpr int HT = 36;           // LDS row stride of the transposed hidden rows
 constexpr int MAX_TS = 2048;     // T * strips the strip statistics stage in LDS holds
 
 struct StreamArgs {
-    float *Wx, *Wh, *b, *V, *c;          // parameters, updated in place
-    const int32_t* ids;                   // [n_windows*T + 1]
+    float *Wx, *Wh, *b, *V, *c;          // parameters (stream mode: updated in place)
+    const int32_t* ids;                   // inputs: [n_windows*T (+ 1)]
+    const int32_t* ys;                    // targets, same stride (stream mode: ids + 1)
     long long n_windows;
+    unsigned tag0;                        // tag of the first window's words (never 0)
+    // gradient mode (one window, parameters untouched)
+    float *dWx, *dWh, *db, *dV, *dc;
+    int beta, NVin;                       // beta: add to the gradient buffers; NVin: rows of Wx
+    const float* dh_last;                 // nullable [H]
+    float *dh0, *h_all;                   // nullable [H], [T+1][H]
     float lr;
     const float* h0;                      // nullable [H]
     float* h_last;                        // nullable [H]
@@ -321,7 +330,7 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
     for (long long w = 0; w < a.n_windows; ++w) {
         TS(0);
         const int pw = (int)(w & 1), pn = pw ^ 1;
-        const unsigned tag = (unsigned)(w + 1);
+        const unsigned tag = a.tag0 + (unsigned)w;
         float* Hc = Hl + pw * (T + 1) * HP;           // this window's states
         const float* Ho = Hl + pn * (T + 1) * HP;     // the previous window's
         float* Uc = Ul + pw * T * HP;                  // this window's rows of Wx
@@ -525,7 +534,7 @@ __device__ __forceinline__ void loop_body(const StreamArgs& a, float* smem) {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int ESE = CW + 4;      // LDS row stride of the exponentials
 
-template <int NQ>
+template <int NQ, int MODE>   // MODE 0: SGD over a stream, 1: gradients of one window
 __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, float* smem) {
     constexpr int HR = 16 * NQ, HPP = HR + 4, KC = 4 * NQ;
     __shared__ int s_y[MAXT];
@@ -539,6 +548,7 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
     const int cown = 16 * wave + m;                  // this lane's column of the strip
     const float invN = 1.0f / (float)T;
     const int npass = (T + 15) / 16;
+    TS_DECL;
     float* Vs = smem;                     // [HR][ES]
     float* cs = Vs + HR * ES;             // [CW]
     float* hs = cs + CW;                  // [32][HPP] hidden rows of the window (rows past T: zeros)
@@ -547,24 +557,73 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
     float* stage = es + 16 * ESE;         // [T][S][2]
     float* wts = stage + 2 * T * S;       // [T][S]
 
-    for (int e = tid; e < HR * ES; e += NT) {
-        const int i = e / ES, cc = e - i * ES;
-        Vs[e] = (i < H && cc < ncols) ? a.V[(size_t)i * NV + k0 + cc] : 0.f;
+    // The strip of V: every element of the HR x 128 block is written (zeros outside the matrix);
+    // 16-byte loads, all of a thread's requests in flight, when the rows allow it.
+    if ((NV & 3) == 0) {
+        const int c4 = tid & 31, ig = tid >> 5;
+        float4 v[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+            const int i = ig + 16 * u;
+            v[u] = (i < H && 4 * c4 < ncols) ? ld4(a.V + (size_t)i * NV + k0 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) st4(Vs + (ig + 16 * u) * ES + 4 * c4, v[u]);
+    } else {
+        for (int e = tid; e < HR * CW; e += NT) {
+            const int i = e / CW, cc = e - i * CW;
+            Vs[i * ES + cc] = (i < H && cc < ncols) ? a.V[(size_t)i * NV + k0 + cc] : 0.f;
+        }
     }
     if (tid < CW) cs[tid] = tid < ncols ? a.c[k0 + tid] : 0.f;
     for (int e = tid; e < 32 * HPP; e += NT) hs[e] = 0.f;
     for (int e = tid; e < HR * HT; e += NT) hsT[e] = 0.f;
-    int ny = tid < T ? a.ids[tid + 1] : 0;           // targets of window 0
+    if (MODE == 1 && !a.beta) {
+        // Gradient mode: zero fill of the token-gradient matrix, an even share of its rows per
+        // strip, done now, while the forward loop runs.  The rows of the tokens that occur in the
+        // window are left alone: the loop workgroup writes those in full, and nothing orders the
+        // two workgroups.
+        __shared__ int s_x[MAXT];
+        __shared__ unsigned char s_skip[512];
+        const int per = (a.NVin + S - 1) / S;
+        const int r_lo = min(a.NVin, g * per), r_hi = min(a.NVin, r_lo + per);
+        if (tid < T) s_x[tid] = a.ids[tid];
+        for (int r0 = r_lo; r0 < r_hi; r0 += 512) {      // 512 rows at a time
+            __syncthreads();
+            {
+                bool hit = false;
+                for (int u = 0; u < T; ++u) hit = hit || s_x[u] == r0 + tid;
+                s_skip[tid] = hit ? 1 : 0;
+            }
+            __syncthreads();
+            const int rows = min(512, r_hi - r0);
+            if ((H & 3) == 0) {
+                const int H4 = H / 4, total = rows * H4;
+                const float invH4 = 1.0f / (float)H4;
+                for (int e = tid; e < total; e += NT) {
+                    int row = (int)((float)e * invH4);
+                    if (row * H4 > e) --row; else if ((row + 1) * H4 <= e) ++row;
+                    if (!s_skip[row])
+                        reinterpret_cast<float4*>(a.dWx + (size_t)r0 * H)[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            } else {
+                const int total = rows * H;
+                for (int e = tid; e < total; e += NT)
+                    if (!s_skip[e / H]) a.dWx[(size_t)r0 * H + e] = 0.f;
+            }
+        }
+    }
+    int ny = tid < T ? a.ys[tid] : 0;               // targets of window 0
     if (tid == 0) s_abort = 0;
     __syncthreads();
+    TS(11);
 
-    TS_DECL;
     for (long long w = 0; w < a.n_windows; ++w) {
         TS(0);
-        const unsigned tag = (unsigned)(w + 1);
+        const unsigned tag = a.tag0 + (unsigned)w;
         if (tid < T) {
             s_y[tid] = ny;
-            if (w + 1 < a.n_windows) ny = a.ids[(size_t)(w + 1) * T + tid + 1];
+            if (w + 1 < a.n_windows) ny = a.ys[(size_t)(w + 1) * T + tid];
         }
         // ---- all hidden rows of the window ---------------------------------------------------
         {
@@ -868,9 +927,16 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
                 ht[it][0] = ld4(hsT + (16 * it + m) * HT + 4 * kg);
                 ht[it][1] = ld4(hsT + (16 * it + m) * HT + 16 + 4 * kg);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) vold[it][r] = Vs[(16 * it + 4 * kg + r) * ES + cown];
+                for (int r = 0; r < 4; ++r) {
+                    if (MODE == 0) {
+                        vold[it][r] = Vs[(16 * it + 4 * kg + r) * ES + cown];
+                    } else {        // gradient mode: the old gradient when accumulating, else nothing
+                        const int i = 16 * it + 4 * kg + r;
+                        vold[it][r] = (a.beta && i < H && cown < ncols) ? a.dV[(size_t)i * NV + k0 + cown] : 0.f;
+                    }
+                }
             }
-            const float cold = cs[cown];
+            const float cold = MODE == 0 ? cs[cown] : ((a.beta && kg == 0 && cown < ncols) ? a.dc[k0 + cown] : 0.f);
 #pragma unroll
             for (int it = 0; it < NQ; ++it) {
                 f32x4 d = {0.f, 0.f, 0.f, 0.f};
@@ -885,10 +951,20 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
                     d = __builtin_amdgcn_mfma_f32_16x16x4f32(ht[it][1].w, dz[1][3], d, 0, 0, 0);
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    Vs[(16 * it + 4 * kg + r) * ES + cown] = fmaf(-a.lr, d[r], vold[it][r]);
+                for (int r = 0; r < 4; ++r) {
+                    if (MODE == 0) {
+                        Vs[(16 * it + 4 * kg + r) * ES + cown] = fmaf(-a.lr, d[r], vold[it][r]);
+                    } else {
+                        const int i = 16 * it + 4 * kg + r;
+                        if (i < H && cown < ncols) a.dV[(size_t)i * NV + k0 + cown] = vold[it][r] + d[r];
+                    }
+                }
             }
-            if (kg == 0) cs[cown] = fmaf(-a.lr, dcs, cold);
+            if (MODE == 0) {
+                if (kg == 0) cs[cown] = fmaf(-a.lr, dcs, cold);
+            } else if (kg == 0 && cown < ncols) {
+                a.dc[k0 + cown] = cold + dcs;
+            }
         }
         __syncthreads();
         if (s_abort) {   // a wait in the G slice expired
@@ -899,6 +975,7 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
     }
     TS_FLUSH;
 
+    if (MODE == 1) return;
     // ---- write the columns back --------------------------------------------------------------
     for (int e = tid; e < H * CW; e += NT) {
         const int i = e / CW, cc = e - i * CW;
@@ -907,11 +984,280 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
     if (tid < ncols) a.c[k0 + tid] = cs[tid];
 }
 
+// ---------------------------------------------------------------------------------------
+// Workgroup 0 in gradient mode: one window, parameters untouched; dWh is accumulated in registers
+// (row layout of Wh) one rank-1 term per reverse step, db in a register, the touched rows of dWx
+// from the deltas in LDS.
+template <int ACT, int NQ>
+__device__ __forceinline__ void loop_body_grad(const StreamArgs& a, float* smem) {
+    constexpr int HP = 16 * NQ;
+    __shared__ int s_ids[MAXT];
+    __shared__ int s_first[MAXT];
+    __shared__ int4 s_ch[MAXT];
+    __shared__ int s_abort;
+    const int H = a.H, T = a.T, tid = threadIdx.x;
+    const int own = tid >> 2, q = tid & 3;
+    const int ownc = min(own, HP - 1);
+    const bool live = own < H, lead = live && q == 0;
+    const unsigned tag = a.tag0;
+    float* Hc = smem;                        // [T+1][HP]  h_{-1} .. h_{T-1}
+    float* Dl = Hc + (T + 1) * HP;           // [T][HP] delta_t
+    float* Ul = Dl + T * HP;                 // [T][HP] rows of Wx of the window's tokens
+    float* Gl = Ul + T * HP;                 // [T][HP] G_t
+    const int lds_floats = ((T + 1) + 3 * T) * HP;
+    TS_DECL;
+    for (int i = tid; i < lds_floats; i += NT) smem[i] = 0.f;
+
+    float4 wf[NQ], wb[NQ], ga[NQ];           // Wh by rows, by columns; dWh by rows
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int k = 4 * (q + 4 * u);
+        if ((H & 3) == 0) {
+            wf[u] = (live && k < H) ? ld4(a.Wh + (size_t)own * H + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            float f[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (live && k + e < H) f[e] = a.Wh[(size_t)own * H + k + e];
+            wf[u] = make_float4(f[0], f[1], f[2], f[3]);
+        }
+        ga[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    const float bj = lead ? a.b[own] : 0.f;
+    const int myid = tid < T ? a.ids[tid] : 0;
+    if (tid == 0) s_abort = 0;
+    __syncthreads();
+    if (tid < T) s_ids[tid] = myid;
+    if (lead) Hc[own] = a.h0 ? a.h0[own] : 0.f;
+    __syncthreads();
+    if (tid < T) {       // first step with the same token, and the next four
+        int f = tid, nc = 0;
+        int4 ch = make_int4(-1, -1, -1, -1);
+        for (int u0 = 0; u0 < T; u0 += 8) {
+            int iv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) iv[k] = s_ids[min(u0 + k, T - 1)];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int idx = u0 + k;
+                if (idx < T && iv[k] == myid) {
+                    if (idx < f) f = idx;
+                    if (idx > tid) {
+                        if (nc == 0) ch.x = idx; else if (nc == 1) ch.y = idx;
+                        else if (nc == 2) ch.z = idx; else if (nc == 3) ch.w = idx;
+                        ++nc;
+                    }
+                }
+            }
+        }
+        s_first[tid] = f;
+        s_ch[tid] = ch;
+    }
+    if (lead) {
+        for (int t0 = 0; t0 < T; t0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = a.Wx[(size_t)s_ids[min(t0 + u, T - 1)] * H + own];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                consume(v[u]);
+                if (t0 + u < T) Ul[(t0 + u) * HP + own] = v[u];
+            }
+        }
+    }
+    __syncthreads();
+    TS(0);
+
+    for (int s = 0; s < T; ++s) {
+        const float4* v4 = reinterpret_cast<const float4*>(Hc + s * HP) + q;
+        float4 x[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) x[u] = v4[4 * u];
+        const float uin = Ul[s * HP + ownc];
+        float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+            if (u & 1) acc1 = dot4(wf[u], x[u], acc1); else acc0 = dot4(wf[u], x[u], acc0);
+        }
+        const float acc = sum4(acc0 + acc1);
+        if (lead) {
+            const float hv = activate<ACT>(acc + uin + bj);
+            Hc[(s + 1) * HP + own] = hv;
+            tagged_store(a.hbox + (size_t)s * H + own, tag, hv);
+        }
+        lds_barrier();
+    }
+    TS(1);
+    // while the strips work: the column copy of Wh for the reverse loop (strided reads, off the
+    // critical path here) and the states the caller asked for
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int k = 4 * (q + 4 * u);
+        float g[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (live && k + e < H) g[e] = a.Wh[(size_t)(k + e) * H + own];
+        wb[u] = make_float4(g[0], g[1], g[2], g[3]);
+    }
+    if (lead) {
+        if (a.h_all)
+            for (int t = 0; t <= T; ++t) a.h_all[(size_t)t * H + own] = Hc[t * HP + own];
+        if (a.h_last) a.h_last[own] = Hc[T * HP + own];
+    }
+    const float dhl = (lead && a.dh_last) ? a.dh_last[own] : 0.f;
+    {
+        const int n = T * H;
+        for (int e0 = tid; e0 < n; e0 += 4 * NT) {
+            unsigned long long wd[4];
+            long long idx[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) idx[u] = e0 + u * NT < n ? e0 + u * NT : -1;
+            if (!wait4(a.gbox, idx, tag, a.spin_limit, wd)) s_abort = 1;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * NT;
+                if (e >= n) continue;
+                const int t = e / H;
+                Gl[t * HP + (e - t * H)] = tagged_value(wd[u]);
+            }
+        }
+    }
+    __syncthreads();
+    if (s_abort) {
+        if (tid == 0) atomicExch(a.status, 1);
+        return;
+    }
+    TS(3);
+    float bsum = 0.f;
+    if (lead) {
+        const float h = Hc[T * HP + own];
+        const float d = (Gl[(T - 1) * HP + own] + dhl) * act_grad<ACT>(h);
+        Dl[(T - 1) * HP + own] = d;
+        bsum = d;
+    }
+    lds_barrier();
+    for (int t = T - 2; t >= 0; --t) {
+        const float4* d4 = reinterpret_cast<const float4*>(Dl + (t + 1) * HP) + q;
+        const float4* h4 = reinterpret_cast<const float4*>(Hc + (t + 1) * HP) + q;
+        float4 x[NQ], hh[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) { x[u] = d4[4 * u]; hh[u] = h4[4 * u]; }
+        const float dj = Dl[(t + 1) * HP + ownc];
+        const float g = Gl[t * HP + ownc], h = Hc[(t + 1) * HP + ownc];
+        float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+            if (u & 1) acc1 = dot4(wb[u], x[u], acc1); else acc0 = dot4(wb[u], x[u], acc0);
+        }
+        const float acc = sum4(acc0 + acc1);
+        if (lead) {
+            const float d = (g + acc) * act_grad<ACT>(h);
+            Dl[t * HP + own] = d;
+            bsum += d;
+        }
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) rank1(ga[u], -dj, hh[u]);   // dWh += delta_{t+1} (x) h_t
+        lds_barrier();
+    }
+    {   // delta_0 (x) h_{-1}, and dh0 = Wh^T delta_0
+        const float4* h4 = reinterpret_cast<const float4*>(Hc) + q;
+        const float4* d4 = reinterpret_cast<const float4*>(Dl) + q;
+        float4 hh[NQ], x[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) { hh[u] = h4[4 * u]; x[u] = d4[4 * u]; }
+        const float dj = Dl[ownc];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) rank1(ga[u], -dj, hh[u]);
+        float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+            if (u & 1) acc1 = dot4(wb[u], x[u], acc1); else acc0 = dot4(wb[u], x[u], acc0);
+        }
+        const float acc = sum4(acc0 + acc1);
+        if (lead && a.dh0) a.dh0[own] = acc;
+    }
+    TS(4);
+    // gradients of the recurrent layer; overwrite and accumulate as separate loops (a load in a
+    // storing loop would wait for the previous store's acknowledgement)
+    if (live) {
+        if ((H & 3) == 0) {
+            float4 old[NQ];
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) {
+                const int k = 4 * (q + 4 * u);
+                old[u] = (a.beta && k < H) ? ld4(a.dWh + (size_t)own * H + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) {
+                const int k = 4 * (q + 4 * u);
+                if (k < H)
+                    st4(a.dWh + (size_t)own * H + k, make_float4(old[u].x + ga[u].x, old[u].y + ga[u].y,
+                                                                 old[u].z + ga[u].z, old[u].w + ga[u].w));
+            }
+        } else {
+            float old[NQ][4];
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) {
+                const int k = 4 * (q + 4 * u);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) old[u][e] = (a.beta && k + e < H) ? a.dWh[(size_t)own * H + k + e] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) {
+                const int k = 4 * (q + 4 * u);
+                const float f[4] = {ga[u].x, ga[u].y, ga[u].z, ga[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (k + e < H) a.dWh[(size_t)own * H + k + e] = old[u][e] + f[e];
+            }
+        }
+    }
+    if (lead) a.db[own] = (a.beta ? a.db[own] : 0.f) + bsum;
+    if (live) {          // rows of dWx: the four lanes of a hidden unit share the steps
+        for (int t = q; t < T; t += 4) {
+            if (s_first[t] != t) continue;
+            float sum = Dl[t * HP + own];
+            int4 c = s_ch[t];
+            while (c.x >= 0) {
+                const float v0 = Dl[c.x * HP + own], v1 = Dl[max(c.y, 0) * HP + own];
+                const float v2 = Dl[max(c.z, 0) * HP + own], v3 = Dl[max(c.w, 0) * HP + own];
+                const int4 more = s_ch[max(c.w, 0)];
+                sum += v0;
+                if (c.y >= 0) sum += v1;
+                if (c.z >= 0) sum += v2;
+                if (c.w >= 0) sum += v3;
+                c = c.w >= 0 ? more : make_int4(-1, -1, -1, -1);
+            }
+            float* dst = a.dWx + (size_t)s_ids[t] * H + own;
+            *dst = (a.beta ? *dst : 0.f) + sum;
+        }
+    }
+    TS(5);
+    TS_FLUSH;
+}
+
 template <int ACT, int NQ>
 __global__ __launch_bounds__(NT) void train_stream_kernel(StreamArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     if (blockIdx.x == 0) loop_body<ACT, NQ>(a, smem);
-    else strip_body<NQ>(a, (int)blockIdx.x - 1, smem);
+    else strip_body<NQ, 0>(a, (int)blockIdx.x - 1, smem);
+}
+
+template <int ACT, int NQ>
+__global__ __launch_bounds__(NT) void window_kernel(StreamArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    if (blockIdx.x == 0) loop_body_grad<ACT, NQ>(a, smem);
+    else strip_body<NQ, 1>(a, (int)blockIdx.x - 1, smem);
+}
+
+template <int ACT>
+const void* pick_window_kernel(int nq) {
+    switch (nq) {
+        case 2: return (const void*)window_kernel<ACT, 2>;
+        case 4: return (const void*)window_kernel<ACT, 4>;
+        case 7: return (const void*)window_kernel<ACT, 7>;
+        default: return (const void*)window_kernel<ACT, 8>;
+    }
 }
 
 template <int ACT>
@@ -965,10 +1311,130 @@ int stream_supported(const rnn_dims* d) {
     return RNN_OK;
 }
 
+// the fused one-window call accepts what the stream driver accepts, plus different vocabulary
+// sizes on the two sides and the accumulate flag
+int window_supported(const rnn_dims* d) {
+    if (!d) return RNN_EINVAL;
+    rnn_dims t = *d;
+    if (t.flags & ~(RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE)) return RNN_EINVAL;
+    t.flags &= RNN_FLAG_SYNC;
+    if (t.in_dim <= 0) return RNN_EINVAL;
+    t.in_dim = t.out_dim;
+    return stream_supported(&t);
+}
+
+void bind_boxes(StreamArgs& a, void* workspace, const StreamPlan& pl) {
+    char* ws = static_cast<char*>(workspace);
+    a.S = pl.S;
+    a.status = reinterpret_cast<int32_t*>(ws + pl.status);
+    a.hbox = reinterpret_cast<unsigned long long*>(ws + pl.hbox);
+    a.gbox = reinterpret_cast<unsigned long long*>(ws + pl.gbox);
+    a.vybox = reinterpret_cast<unsigned long long*>(ws + pl.vybox);
+    a.zybox = reinterpret_cast<unsigned long long*>(ws + pl.zybox);
+    a.statbox = reinterpret_cast<unsigned long long*>(ws + pl.statbox);
+    a.pbox = reinterpret_cast<unsigned long long*>(ws + pl.pbox);
+    a.spin_limit = 1 << 22;
+    if (const char* env = getenv("RNN_STREAM_SPIN_LIMIT")) {   // failure-path tests: make waits expire
+        const long v = strtol(env, nullptr, 10);
+        if (v > 0 && v < (1L << 30)) a.spin_limit = (int)v;
+    }
+}
+
+// dynamic LDS above 64 KB has to be allowed once per kernel
+hipError_t allow_lds(const void* fn, size_t bytes) {
+    static const void* seen[32];
+    static size_t seen_bytes[32];
+    static int n_seen = 0;
+    if (bytes <= 64 * 1024) return hipSuccess;
+    for (int i = 0; i < n_seen; ++i)
+        if (seen[i] == fn && seen_bytes[i] >= bytes) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && n_seen < 32) { seen[n_seen] = fn; seen_bytes[n_seen] = bytes; ++n_seen; }
+    return e;
+}
+
+uint32_t next_window_tag() {
+    static std::atomic<uint32_t> counter{0};
+    uint32_t e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (e == 0) e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
+    return e;
+}
+
 }  // namespace
 }  // namespace rnn
 
 extern "C" {
+
+int rnn_window_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
+    using namespace rnn;
+    if (!bytes) return RNN_EINVAL;
+    const int rc = window_supported(dims);
+    if (rc != RNN_OK) return rc;
+    *bytes = stream_plan(dims).total;
+    return RNN_OK;
+}
+
+int rnn_window_workspace_init(const rnn_dims* dims, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    using namespace rnn;
+    const int rc = window_supported(dims);
+    if (rc != RNN_OK) return rc;
+    const StreamPlan pl = stream_plan(dims);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
+        return RNN_EWORKSPACE;
+    return launch_zero_words(static_cast<int32_t*>(workspace), (int)(pl.total / 4),
+                             static_cast<hipStream_t>(hip_stream)) == hipSuccess ? RNN_OK : RNN_EHIP;
+}
+
+int rnn_window(const rnn_dims* dims, const rnn_params* params, const int32_t* x, const int32_t* targets,
+               const float* h0, const float* dh_last, float* h_all, float* h_last, float* loss,
+               const rnn_grads* grads, float* dh0, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+    using namespace rnn;
+    const int rc = window_supported(dims);
+    if (rc != RNN_OK) return rc;
+    if (!params || !params->Wx || !params->Wh || !params->b || !params->V || !params->c || !x ||
+        !targets || !loss || !grads || !grads->dWx || !grads->dWh || !grads->db || !grads->dV || !grads->dc)
+        return RNN_EINVAL;
+    auto bad16 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); };
+    auto bad4 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 3u); };
+    if (bad16(params->Wx) || bad16(params->Wh) || bad16(params->b) || bad16(params->V) || bad16(params->c) ||
+        bad16(grads->dWx) || bad16(grads->dWh) || bad16(grads->db) || bad16(grads->dV) || bad16(grads->dc) ||
+        bad4(x) || bad4(targets) || bad4(h0) || bad4(dh_last) || bad4(h_all) || bad4(h_last) || bad4(loss) ||
+        bad4(dh0))
+        return RNN_EINVAL;
+    const StreamPlan pl = stream_plan(dims);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
+        return RNN_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    StreamArgs a{};
+    a.Wx = const_cast<float*>(params->Wx); a.Wh = const_cast<float*>(params->Wh);
+    a.b = const_cast<float*>(params->b); a.V = const_cast<float*>(params->V); a.c = const_cast<float*>(params->c);
+    a.ids = x; a.ys = targets; a.n_windows = 1; a.lr = 1.0f; a.tag0 = next_window_tag();
+    a.h0 = h0; a.h_last = h_last; a.losses = loss; a.h_all = h_all; a.dh_last = dh_last; a.dh0 = dh0;
+    a.dWx = grads->dWx; a.dWh = grads->dWh; a.db = grads->db; a.dV = grads->dV; a.dc = grads->dc;
+    a.beta = (dims->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
+    a.H = dims->hidden; a.NV = dims->out_dim; a.NVin = dims->in_dim; a.T = dims->seq_len;
+    bind_boxes(a, workspace, pl);
+
+    const int nq = pick_nq(a.H);
+    const void* fn = dims->act == RNN_ACT_SIGMOID ? pick_window_kernel<0>(nq) : pick_window_kernel<1>(nq);
+    size_t lds = loop_lds_floats(a.T, nq);
+    if (strip_lds_floats(nq, a.T, a.S) > lds) lds = strip_lds_floats(nq, a.T, a.S);
+    lds *= 4;
+    if (allow_lds(fn, lds) != hipSuccess) return RNN_EHIP;
+    hipError_t e;
+    {
+        ProfileScope ps(K_WINDOW, s);
+        void* args[] = {&a};
+        e = getenv("RNN_WINDOW_COOP") ? hipLaunchCooperativeKernel(fn, dim3(1 + a.S), dim3(NT), args, (unsigned)lds, s)
+                                      : hipLaunchKernel(fn, dim3(1 + a.S), dim3(NT), args, lds, s);
+    }
+    if (e != hipSuccess) return RNN_EHIP;
+    if (dims->flags & RNN_FLAG_SYNC)
+        if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
+    return RNN_OK;
+}
 
 int rnn_train_stream_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
     using namespace rnn;
@@ -1002,20 +1468,10 @@ int rnn_train_stream(const rnn_dims* dims, const rnn_params_inout* params, const
     char* ws = static_cast<char*>(workspace);
     StreamArgs a{};
     a.Wx = params->Wx; a.Wh = params->Wh; a.b = params->b; a.V = params->V; a.c = params->c;
-    a.ids = ids; a.n_windows = n_windows; a.lr = lr; a.h0 = h0; a.h_last = h_last; a.losses = losses;
-    a.H = dims->hidden; a.NV = dims->out_dim; a.T = dims->seq_len; a.S = pl.S;
-    a.status = reinterpret_cast<int32_t*>(ws + pl.status);
-    a.hbox = reinterpret_cast<unsigned long long*>(ws + pl.hbox);
-    a.gbox = reinterpret_cast<unsigned long long*>(ws + pl.gbox);
-    a.vybox = reinterpret_cast<unsigned long long*>(ws + pl.vybox);
-    a.zybox = reinterpret_cast<unsigned long long*>(ws + pl.zybox);
-    a.statbox = reinterpret_cast<unsigned long long*>(ws + pl.statbox);
-    a.pbox = reinterpret_cast<unsigned long long*>(ws + pl.pbox);
-    a.spin_limit = 1 << 22;
-    if (const char* env = getenv("RNN_STREAM_SPIN_LIMIT")) {   // failure-path tests: make waits expire
-        const long v = strtol(env, nullptr, 10);
-        if (v > 0 && v < (1L << 30)) a.spin_limit = (int)v;
-    }
+    a.ids = ids; a.ys = ids + 1; a.n_windows = n_windows; a.lr = lr; a.tag0 = 1u;
+    a.h0 = h0; a.h_last = h_last; a.losses = losses;
+    a.H = dims->hidden; a.NV = dims->out_dim; a.NVin = dims->in_dim; a.T = dims->seq_len;
+    bind_boxes(a, workspace, pl);
 
     // tags start at 1 in every call, so the boxes (and the status word) start cleared
     if (launch_zero_words(reinterpret_cast<int32_t*>(ws), (int)(pl.total / 4), s) != hipSuccess) return RNN_EHIP;
@@ -1025,9 +1481,7 @@ int rnn_train_stream(const rnn_dims* dims, const rnn_params_inout* params, const
     size_t lds = loop_lds_floats(a.T, nq);
     if (strip_lds_floats(nq, a.T, a.S) > lds) lds = strip_lds_floats(nq, a.T, a.S);
     lds *= 4;
-    if (lds > 64 * 1024)
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return RNN_EHIP;
+    if (allow_lds(fn, lds) != hipSuccess) return RNN_EHIP;
     hipError_t e;
     {
         ProfileScope ps(K_TRAIN_STREAM, s);
