@@ -4,8 +4,9 @@
 One "step" is one pass of the whole path over one batch of synthetic input:
   C2 (headline, the paper's benchmark shape: batch 1, vocabulary-sized input and output layers):
      the 100000-token Zipf stream as 10000 dependent truncated-BPTT windows of 10 steps; every
-     window runs rnn_forward -> rnn_loss -> rnn_bptt with the hidden state carried, in stream
-     order, exactly as if an optimiser step sat between windows.
+     window is one rnn_window call (forward, loss and BPTT of the window in one launch; the same
+     outputs as rnn_forward -> rnn_loss -> rnn_bptt, whose timing is reported beside it) with the
+     hidden state carried, in stream order, exactly as if an optimiser step sat between windows.
   C1, C3, C4, C5: one window of the named configuration.
 Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
 """
@@ -37,6 +38,8 @@ def parse():
     ap.add_argument("--others", default="C3,C4,C5",
                     help="comma list of further configurations reported under 'per_config' ('none' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="time rnn_forward -> rnn_loss -> rnn_bptt even where rnn_window serves the shape")
     ap.add_argument("--no-train-stream", action="store_true",
                     help="skip the single-launch SGD driver leg of the headline workload")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
@@ -49,7 +52,7 @@ def parse():
 class Workload:
     """Device-resident buffers and pre-marshalled C calls of one configuration."""
 
-    def __init__(self, name, flags=0, windows=None):
+    def __init__(self, name, flags=0, windows=None, three_calls=False):
         import numpy as np
         import torch
         import paper_1211_5590_amd as rnn
@@ -73,6 +76,15 @@ class Workload:
         self.loss = torch.zeros((max(self.windows, 1),), device="cuda")
         self.ws = torch.empty(rnn.rnn_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
         rnn.rnn_workspace_init(self.dims, self.ws)
+        # one launch per window (rnn_window) where the library serves the shape, else the three calls
+        self.fused = False
+        if not three_calls and not flags:
+            try:
+                self.wws = torch.empty(rnn.rnn_window_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
+                rnn.rnn_window_workspace_init(self.dims, self.wws)
+                self.fused = True
+            except rnn.RnnError:
+                pass
         # pre-marshalled arguments: plain ints and ctypes structs, no per-call Python objects
         self.L = rnn.lib()
         self.P = rnn.Params(*[self.p[k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])
@@ -93,6 +105,15 @@ class Workload:
         xb, yb, lb = self.x.data_ptr(), self.y.data_ptr(), self.loss.data_ptr()
         c0, c1 = self.carry[0].data_ptr(), self.carry[1].data_ptr()
         fwd, loss, bptt = L.rnn_forward, L.rnn_loss, L.rnn_bptt
+        if self.fused:
+            win, wws, wwb = L.rnn_window, self.wws.data_ptr(), self.wws.numel()
+            for w in range(self.windows):
+                h0 = None if w == 0 else (c1 if w & 1 else c0)
+                rc = win(d, P, xb + w * self.x_stride, yb + w * self.y_stride, h0, None, None,
+                         c0 if w & 1 else c1, lb + 4 * w, G, None, wws, wwb, stream)
+                if rc:
+                    raise RuntimeError(f"rnn_window failed in window {w}: {rc}")
+            return
         for w in range(self.windows):
             x, y = xb + w * self.x_stride, yb + w * self.y_stride
             h0 = None if w == 0 else (c1 if w & 1 else c0)
@@ -174,6 +195,10 @@ def algorithmic_work(kernel, c):
         # short-sequence output layer (column strips): V in, Z out, and the strips' shares of the
         # softmax part of G (a second contraction with the same strip of V)
         "skinny_logits": (f * (H * O + N * O + N * H), 4.0 * N * H * O),
+        # whole window in one launch: V and Wh in, dV, dWh and the dense dWx out (logits and dZ
+        # never leave the chip); logits, shares of G and dV are three contractions with V-sized
+        # operands, the loops and dWh three with Wh-sized ones
+        "window": (f * (2 * H * O + 2 * H * H + I * H + 3 * N * H + 2 * O), 6.0 * N * H * O + 6.0 * N * H * H),
     }
     variant = c.get("_variant", "")
     if variant == "step_mfma":      # one launch = one step: matrix + state in, state out
@@ -392,9 +417,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    wl = Workload(a.workload, flags, a.windows)
+    wl = Workload(a.workload, flags, a.windows, a.three_calls)
     wall, gpu_s = wl.time_steps(steps, warm)
     prof = wl.profile(1)
+    if wl.fused and wl.rnn.rnn_train_stream_status(wl.wws) != 0:
+        print("bench.py: a bounded wait of rnn_window expired; results invalid", file=sys.stderr)
+        sys.exit(4)
     out = {
         "metric": "fwd+BPTT tokens/sec",
         "value": wl.tokens_per_step * steps / wall,
@@ -404,6 +432,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": dict(workload=a.workload, **describe(wl.case),
+                       entry_points="rnn_window" if wl.fused else "rnn_forward,rnn_loss,rnn_bptt",
                        recurrence_variant=rnn.rnn_recurrence_variant(wl.dims)),
         "timesteps_per_s": wl.timesteps_per_step * steps / wall,
         "gpu_event_ms_per_step": 1e3 * gpu_s / steps,
@@ -414,8 +443,24 @@ def main():
                             total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
         "event_bracket_us": round(wl.bracket_us, 3),
     }
+    fused_headline = wl.fused
     del wl
     torch.cuda.empty_cache()
+
+    if fused_headline:
+        # the same workload through the three separate calls, for comparison
+        w3 = Workload(a.workload, flags, a.windows, three_calls=True)
+        wall3, _ = w3.time_steps(max(1, steps // 3), 1)
+        n3 = max(1, steps // 3)
+        pr3 = w3.profile(1)
+        out["three_call_path"] = dict(entry_points="rnn_forward,rnn_loss,rnn_bptt",
+                                      tokens_per_s=w3.tokens_per_step * n3 / wall3,
+                                      ms_per_step=1e3 * wall3 / n3,
+                                      roofline=roofline_of(pr3, w3.case),
+                                      kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
+                                               for k, v in sorted(pr3.items())})
+        del w3
+        torch.cuda.empty_cache()
 
     per = {}
     for name in [s for s in a.others.split(",") if s and s != "none" and s != a.workload]:
