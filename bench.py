@@ -369,18 +369,27 @@ def train_stream_leg(windows, reps=3, lr=0.1):
     flops = W * (6.0 * T * H * NV + 8.0 * T * H * H)
     peak = n_cu * 256 * 2.4e9 / 1e12                # fp32 matrix rate of the occupied units, TFLOP/s
     lo = losses.cpu().numpy()
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            t = json.load(fh).get("C2", {}).get("train_stream")
+        if t and t.get("windows"):
+            traffic = t["bytes_per_launch"] / t["windows"] * W    # counters were taken on a shorter stream
+    except (OSError, ValueError):
+        pass
     return {
         "entry_point": "rnn_train_stream", "windows": W, "lr": lr, "workgroups": n_cu,
         "tokens_per_s": W * T / sec, "us_per_window": 1e6 * sec / W, "ms_per_stream": 1e3 * sec,
         "loss_first_window": float(lo[0]), "loss_mean_last_100_windows": float(lo[-100:].mean()),
         "roofline": {"kernel": "train_stream", "bound": "mfma", "achieved": flops / sec / 1e12,
                      "peak": peak, "unit": "TFLOP/s", "frac": flops / sec / 1e12 / peak,
-                     "traffic": None, "n_cu": n_cu, "avg_us": 1e6 * sec,
+                     "traffic": traffic, "n_cu": n_cu, "avg_us": 1e6 * sec,
                      "algorithmic_flops": flops,
-                     "note": "one launch per stream; the model stays on chip (HBM sees the ids, the "
-                             "touched rows of Wx and the losses), so the ceiling stated is the matrix "
-                             "rate of the occupied compute units; the launch is bound by the latency "
-                             "of its dependent steps and exchanges"},
+                     "note": "one launch per stream; the model stays on chip (memory sees the ids, "
+                             "the touched rows of Wx, the losses and the tagged words the workgroups "
+                             "exchange), so the ceiling stated is the matrix rate of the occupied "
+                             "compute units; the launch is bound by the latency of its dependent steps "
+                             "and exchanges"},
     }
 
 
