@@ -61,6 +61,9 @@ def lib():
     """Load librnn_mi355x.so (building it first only if it has never been built)."""
     global _lib
     if _lib is None:
+        # torch ships its own HIP runtime: it has to be in the process before this library is
+        # loaded, so that both use the same one whatever the import order of the caller
+        import torch  # noqa: F401
         if not os.path.exists(_LIB_PATH):
             from . import build as _build
             _build.build()
