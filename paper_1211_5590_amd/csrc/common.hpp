@@ -85,4 +85,47 @@ __device__ __forceinline__ bool tagged_wait(const unsigned long long* p, unsigne
     return true;
 }
 
+
+// Every requested word is "used" here, also the clamped duplicates a batch requests past the end
+// of its range: a load whose result is never read stays pending in the compiler's bookkeeping,
+// and the wait it later inserts before reusing the register (in some unrelated loop) would also
+// wait for every store issued since.
+__device__ __forceinline__ void consume(unsigned long long v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void consume(float v) { asm volatile("" ::"v"(v)); }
+
+// Waits for N tagged words at once (act[u] false marks an unused slot).  All stale words are
+// requested again together, so words that arrive while the batch is being polled cost one more
+// round trip in total, not one each.  Returns false when the bounded wait expires.
+template <int N>
+__device__ __forceinline__ bool wait_n(const unsigned long long* const (&ptr)[N], const bool (&act)[N],
+                                       unsigned tag, int spin_limit, unsigned long long (&w)[N]) {
+#pragma unroll
+    for (int u = 0; u < N; ++u) w[u] = tagged_load(ptr[u]);
+    bool ok = true;
+    for (int spins = 0;; ++spins) {
+        bool stale = false;
+#pragma unroll
+        for (int u = 0; u < N; ++u) stale = stale || (act[u] && !tagged_ok(w[u], tag));
+        if (!stale) break;
+        if (spins > spin_limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);   // a short pause keeps the pollers from crowding the memory pipeline
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            if (act[u] && !tagged_ok(w[u], tag)) w[u] = tagged_load(ptr[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < N; ++u) consume(w[u]);
+    return ok;
+}
+// four words base[idx[u]]; idx[u] < 0 marks an unused slot
+__device__ __forceinline__ bool wait4(const unsigned long long* base, const long long (&idx)[4], unsigned tag,
+                                      int spin_limit, unsigned long long (&w)[4]) {
+    const unsigned long long* ptr[4];
+    bool act[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { act[u] = idx[u] >= 0; ptr[u] = base + (act[u] ? idx[u] : 0); }
+    return wait_n<4>(ptr, act, tag, spin_limit, w);
+}
+
+
 }  // namespace rnn

@@ -242,18 +242,13 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
         const int n = T * H;
         for (int e0 = tid; e0 < n; e0 += 4 * kThreads) {
             unsigned long long w[4];
+            long long idx[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) w[u] = tagged_load(a.g_box + min(e0 + u * kThreads, n - 1));
+            for (int u = 0; u < 4; ++u) idx[u] = e0 + u * kThreads < n ? e0 + u * kThreads : -1;
+            if (!wait4(a.g_box, idx, a.epoch, a.spin_limit, w)) s_abort = 1;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int e = e0 + u * kThreads;
-                if (e >= n) continue;
-                for (int spins = 0; !tagged_ok(w[u], a.epoch); ++spins) {
-                    if (spins > a.spin_limit) { s_abort = 1; break; }
-                    w[u] = tagged_load(a.g_box + e);
-                }
-                Gl[e] = tagged_value(w[u]);
-            }
+            for (int u = 0; u < 4; ++u)
+                if (idx[u] >= 0) Gl[idx[u]] = tagged_value(w[u]);
         }
     }
     __syncthreads();

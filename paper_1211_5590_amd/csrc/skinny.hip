@@ -205,7 +205,7 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     float* stage = red;                  // NWV*NR*CW floats >= 2*strips (checked by the host)
     __shared__ float zys[32];
     const unsigned long long* zybox = a.stat_box + (size_t)N * strips * 2;
-    unsigned long long wz = tid < N ? tagged_load(zybox + tid) : 0ull;   // in flight with the rest
+    unsigned long long wz = tagged_load(zybox + min(tid, N - 1));   // in flight with the rest
     const int rows_per_pass = max(1, (NWV * NR * CW) / (2 * strips));
     for (int n_lo = 0; n_lo < N; n_lo += rows_per_pass) {
         const int n_hi = min(N, n_lo + rows_per_pass);
@@ -213,18 +213,13 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
         const unsigned long long* src = a.stat_box + (size_t)n_lo * strips * 2;
         for (int w0 = tid; w0 < cnt; w0 += 4 * NTH) {
             unsigned long long w[4];
+            long long idx[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) w[u] = tagged_load(src + min(w0 + u * NTH, cnt - 1));
+            for (int u = 0; u < 4; ++u) idx[u] = w0 + u * NTH < cnt ? w0 + u * NTH : -1;
+            if (!wait4(src, idx, epoch, spin_limit, w)) s_fail = 1;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int idx = w0 + u * NTH;
-                if (idx >= cnt) continue;
-                for (int spins = 0; !tagged_ok(w[u], epoch); ++spins) {
-                    if (spins > spin_limit) { s_fail = 1; break; }
-                    w[u] = tagged_load(src + idx);
-                }
-                stage[idx] = tagged_value(w[u]);
-            }
+            for (int u = 0; u < 4; ++u)
+                if (idx[u] >= 0) stage[idx[u]] = tagged_value(w[u]);
         }
         if (n_lo == 0 && tid < N) {
             for (int spins = 0; !tagged_ok(wz, epoch); ++spins) {
@@ -233,6 +228,7 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
             }
             zys[tid] = tagged_value(wz);
         }
+        consume(wz);
         __syncthreads();
         for (int n = n_lo + wave; n < n_hi; n += NWV) {
             float m = -INFINITY, sum = 0.f;

@@ -96,8 +96,11 @@ __device__ __forceinline__ void reduce_g_slice(const SkinnyArgs& a, int part, in
                 m[u] = tagged_value(a.stat_box[((size_t)t * S + g) * 2]);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 4; ++u) {
+                consume(sh[u]);
+                consume(m[u]);
                 if (g0 + lpo * u < S) sum = fmaf(__expf(m[u] - l), sh[u], sum);
+            }
         }
         for (int off = lpo / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
         if (live && j == 0) tagged_store(a.g_box + o, a.epoch, (sum - a.vy[o]) * invN);
