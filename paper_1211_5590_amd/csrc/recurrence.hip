@@ -391,23 +391,28 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
             const unsigned tag = (unsigned)(s + 1);
             unsigned long long* box = reinterpret_cast<unsigned long long*>(a.flags) +
                                       ((size_t)(s & 1) * B + bb) * H;
-            if (lead) {
-                const int j = r0 + own;
-                const unsigned long long w =
-                    ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(val);
-                __hip_atomic_store(box + j, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            for (int j = tid; j < H; j += kThreads) {
-                if (j >= r0 && j < r0 + rows) continue;   // own slice: already in LDS
-                int spins = 0;
-                unsigned long long w;
-                while ((unsigned)((w = __hip_atomic_load(box + j, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
-                    if (++spins > a.spin_limit) { s_abort = 1; break; }
+            // The last wavefront publishes the slice (and writes the history row); the others
+            // poll.  A wavefront that polls right after storing would first wait for its own
+            // stores to be acknowledged, once per step.
+            lds_barrier();                        // the slice's new values are in vnext
+            if (tid >= kThreads - kWave) {
+                for (int o = tid - (kThreads - kWave); o < rows; o += kWave) {
+                    const float v = vnext[r0 + o];
+                    tagged_store(box + r0 + o, tag, v);
+                    out_row[r0 + o] = v;
                 }
-                vnext[j] = __uint_as_float((unsigned)w);
+            } else {
+                for (int j = tid; j < H; j += kThreads - kWave) {
+                    if (j >= r0 && j < r0 + rows) continue;   // own slice: already in LDS
+                    int spins = 0;
+                    unsigned long long w;
+                    while ((unsigned)((w = __hip_atomic_load(box + j, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
+                        if (++spins > a.spin_limit) { s_abort = 1; break; }
+                    }
+                    vnext[j] = __uint_as_float((unsigned)w);
+                }
             }
-            if (lead) out_row[r0 + own] = val;
             lds_barrier();
             if (s_abort) {
                 if (tid == 0) atomicExch(a.status, 1);
