@@ -33,6 +33,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "common.hpp"
 #include "internal.hpp"
@@ -768,36 +769,44 @@ __device__ __forceinline__ void strip_body(const StreamArgs& a, const int g, flo
         }
         // lse_t = M + log(sum_g s_g exp(m_g - M)), M = max_g m_g; weight of strip g:
         // exp(m_g - lse_t) = exp(m_g - M) / sum.  32 lanes per row, strips in lane-strided order.
-        for (int t = tid >> 5; t < T; t += NT / 32) {
-            const int j = tid & 31;
-            float mg[8], sg[8];                           // S <= 256 strips: 8 per lane
-            float M = -INFINITY;
+        auto merge = [&](auto per_lane) {
+            constexpr int NP = decltype(per_lane)::value;     // strips per lane: S <= 32 * NP
+            for (int t = tid >> 5; t < T; t += NT / 32) {
+                const int j = tid & 31;
+                float2 ms[NP];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int g2 = j + 32 * u;
-                mg[u] = g2 < S ? stage[(t * S + g2) * 2] : -INFINITY;
-                sg[u] = g2 < S ? stage[(t * S + g2) * 2 + 1] : 0.f;
+                for (int u = 0; u < NP; ++u)
+                    ms[u] = *reinterpret_cast<const float2*>(stage + (t * S + min(j + 32 * u, S - 1)) * 2);
+                __builtin_amdgcn_sched_barrier(0);            // all reads in flight before the first use
+                float mg[NP], sg[NP];
+                float M = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < NP; ++u) {
+                    const bool in = j + 32 * u < S;
+                    mg[u] = in ? ms[u].x : -INFINITY;
+                    sg[u] = in ? ms[u].y : 0.f;
+                    M = fmaxf(M, mg[u]);
+                }
+                M = fmaxf(M, dpp<0xB1>(M)); M = fmaxf(M, dpp<0x4E>(M));
+                M = fmaxf(M, dpp<0x141>(M)); M = fmaxf(M, dpp<0x140>(M));
+                {
+                    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(M), __float_as_uint(M), false, false);
+                    M = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+                }
+                float sum = 0.f;
+#pragma unroll
+                for (int u = 0; u < NP; ++u) { mg[u] = __expf(mg[u] - M); sum = fmaf(sg[u], mg[u], sum); }
+                sum = sum32(sum);
+                const float rs = fast_rcp(sum);
+#pragma unroll
+                for (int u = 0; u < NP; ++u)
+                    if (j + 32 * u < S) wts[t * S + j + 32 * u] = mg[u] * rs;
+                if (j == 0) lse_s[t] = M + __logf(sum);
             }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) M = fmaxf(M, mg[u]);
-            M = fmaxf(M, dpp<0xB1>(M)); M = fmaxf(M, dpp<0x4E>(M));
-            M = fmaxf(M, dpp<0x141>(M)); M = fmaxf(M, dpp<0x140>(M));
-            {
-                const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(M), __float_as_uint(M), false, false);
-                M = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-            }
-            float sum = 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) { mg[u] = __expf(mg[u] - M); sum = fmaf(sg[u], mg[u], sum); }
-            sum = sum32(sum);
-            const float rs = fast_rcp(sum);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int g2 = j + 32 * u;
-                if (g2 < S) wts[t * S + g2] = mg[u] * rs;
-            }
-            if (j == 0) lse_s[t] = M + __logf(sum);
-        }
+        };
+        if (S <= 96) merge(std::integral_constant<int, 3>{});
+        else if (S <= 160) merge(std::integral_constant<int, 5>{});
+        else merge(std::integral_constant<int, 8>{});
         lds_barrier();
 
         TS(6);
