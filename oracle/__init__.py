@@ -177,3 +177,30 @@ def train_stream(p, ids, n_windows, lr, h0=None):
         raise ValueError("orc_train_stream: bad argument")
     out.update(h_last=h, losses=losses)
     return out
+
+
+def gauss_newton_vec(p, gamma, h_all=None, metric=0, want_Rz=False):
+    """G gamma = J^T M J gamma by one R-operator sweep and one reverse sweep.
+
+    gamma: dict with Wx, Wh, b, V, c (a direction of the parameters' shapes); metric 0 = the
+    loss Hessian w.r.t. the outputs, 1 = identity.  Returns dict GWx, GWh, Gb, GV, Gc (+ Rz).
+    """
+    lib = _load()
+    N, O = p["seq_len"] * p["batch"], p["out_dim"]
+    Wx, Wh, V, c = _f64(p["Wx"]), _f64(p["Wh"]), _f64(p["V"]), _f64(p["c"])
+    g = {k: _f64(gamma[k]) for k in ("Wx", "Wh", "b", "V", "c")}
+    x = _inputs(p)
+    h_all = _f64(h_all if h_all is not None else forward(p, p.get("h0")))
+    out = dict(GWx=np.empty_like(Wx), GWh=np.empty_like(Wh), Gb=np.empty(p["hidden"]),
+               GV=np.empty_like(V), Gc=np.empty(O))
+    Rz = np.empty((N, O)) if want_Rz else None
+    d = _dims(p)
+    rc = lib.orc_gauss_newton_vec(ctypes.byref(d), ctypes.c_int(metric), _ptr(Wx), _ptr(Wh), _ptr(V),
+                                  _ptr(c), _ptr(g["Wx"]), _ptr(g["Wh"]), _ptr(g["b"]), _ptr(g["V"]),
+                                  _ptr(g["c"]), _ptr(x), _ptr(h_all), _ptr(out["GWx"]), _ptr(out["GWh"]),
+                                  _ptr(out["Gb"]), _ptr(out["GV"]), _ptr(out["Gc"]), _ptr(Rz))
+    if rc != 0:
+        raise ValueError("orc_gauss_newton_vec: bad argument")
+    if want_Rz:
+        out["Rz"] = Rz
+    return out

@@ -362,3 +362,146 @@ int orc_train_stream(const orc_dims *d, double *Wx, double *Wh, double *b, doubl
     free(h_all); free(dWx); free(dWh); free(db); free(dV); free(dc);
     return rc;
 }
+
+/* ---- Gauss-Newton matrix times a vector, by the R-operator ---------------------------
+ * The paper's section on the R-operator: the forward-mode directional derivative
+ * R{f} = (df/dtheta) gamma, and, for a recurrent network, the Gauss-Newton
+ * approximation of the Hessian times a vector as Lop(f, theta, Rop(f, theta, gamma)),
+ * i.e. J^T (J gamma) with J the Jacobian of the network outputs, evaluated with one
+ * forward sweep that carries (h_t, R h_t) and one reverse sweep.  With a loss on top
+ * the Gauss-Newton matrix has the Hessian M of the loss with respect to the outputs in
+ * the middle, G = J^T M J (the reference the paper cites for the method); metric = 0
+ * uses M of this file's loss, metric = 1 uses M = I (the paper's literal expression).
+ *
+ *   f = z (all T*B rows of logits / linear outputs), theta = (Wx, Wh, b, V, c),
+ *   gamma = (gWx, gWh, gb, gV, gc) a direction of the same shapes.
+ *   forward:  R a_t = gin_t + gb + gWh h_{t-1} + Wh R h_{t-1},  gin_t = gWx[x_t,:] or gWx x_t
+ *             R h_t = act'(h_t) * R a_t,   R h_{-1} = 0   (the initial state is a constant)
+ *             R z_t = V^T R h_t + gV^T h_t + gc
+ *   metric:   softmax-CE  u_n = (p_n * Rz_n - p_n (p_n . Rz_n)) / N,  p_n = softmax(z_n)
+ *             linear-MSE  u_n = 2 Rz_n / (N O);      identity  u_n = Rz_n
+ *   reverse:  ordinary backpropagation of u in place of d loss / d z.
+ * h_all [T+1,B,H] as produced by orc_forward for the same parameters.  Rz_out (nullable,
+ * [T*B,O]) receives R z.  Outputs G* have the shapes of the parameters.
+ */
+int orc_gauss_newton_vec(const orc_dims *d, int metric, const double *Wx, const double *Wh,
+                         const double *V, const double *c, const double *gWx, const double *gWh,
+                         const double *gb, const double *gV, const double *gc, const void *x,
+                         const double *h_all, double *GWx, double *GWh, double *Gb, double *GV,
+                         double *Gc, double *Rz_out)
+{
+    if (!dims_ok(d) || (metric != 0 && metric != 1) || !Wx || !Wh || !V || !c || !gWx || !gWh ||
+        !gb || !gV || !gc || !x || !h_all || !GWx || !GWh || !Gb || !GV || !Gc)
+        return -1;
+    const int H = d->hidden, O = d->out_dim, T = d->seq_len, B = d->batch, D = d->in_dim;
+    const long N = (long)T * B;
+    const int32_t *ids = (const int32_t *)x;
+    const double *X = (const double *)x;
+    const size_t wx_elems = d->input_kind == 0 ? (size_t)D * H : (size_t)H * D;
+    double *Rh = (double *)calloc((size_t)(T + 1) * B * H, sizeof(double)); /* Rh[0] = R h_{-1} = 0 */
+    double *u = (double *)malloc(sizeof(double) * (size_t)N * O);
+    double *g = (double *)malloc(sizeof(double) * (size_t)N * H);
+    double *delta = (double *)malloc(sizeof(double) * (size_t)N * H);
+    double *z = (double *)malloc(sizeof(double) * O);
+    if (!Rh || !u || !g || !delta || !z) return -1;
+
+    /* forward sweep of the R-operator */
+    for (int t = 0; t < T; ++t)
+        for (int bb = 0; bb < B; ++bb) {
+            const double *hp = h_all + ((size_t)t * B + bb) * H;
+            const double *ht = h_all + ((size_t)(t + 1) * B + bb) * H;
+            const double *Rhp = Rh + ((size_t)t * B + bb) * H;
+            double *Rht = Rh + ((size_t)(t + 1) * B + bb) * H;
+            for (int j = 0; j < H; ++j) {
+                double Ra = gb[j];
+                if (d->input_kind == 0) {
+                    const int32_t v = ids[(size_t)t * B + bb];
+                    if (v < 0 || v >= D) return -1;
+                    Ra += gWx[(size_t)v * H + j];
+                } else {
+                    const double *xt = X + ((size_t)t * B + bb) * D;
+                    for (int k = 0; k < D; ++k) Ra += gWx[(size_t)j * D + k] * xt[k];
+                }
+                for (int i = 0; i < H; ++i)
+                    Ra += gWh[(size_t)j * H + i] * hp[i] + Wh[(size_t)j * H + i] * Rhp[i];
+                const double dact = d->act == 0 ? ht[j] * (1.0 - ht[j]) : 1.0 - ht[j] * ht[j];
+                Rht[j] = dact * Ra;
+            }
+        }
+
+    /* R z, then the loss metric, row by row */
+    for (long n = 0; n < N; ++n) {
+        const double *h = h_all + (size_t)(n + B) * H;
+        const double *Rhn = Rh + (size_t)(n + B) * H;
+        double *un = u + (size_t)n * O;
+        for (int k = 0; k < O; ++k) {
+            double s = gc[k];
+            for (int i = 0; i < H; ++i) s += V[(size_t)i * O + k] * Rhn[i] + gV[(size_t)i * O + k] * h[i];
+            un[k] = s;
+        }
+        if (Rz_out)
+            for (int k = 0; k < O; ++k) Rz_out[(size_t)n * O + k] = un[k];
+        if (metric == 1) continue;
+        if (d->loss_kind == 0) {
+            logits_row(h, V, c, H, O, z);
+            double m = z[0];
+            for (int k = 1; k < O; ++k) if (z[k] > m) m = z[k];
+            double s = 0.0;
+            for (int k = 0; k < O; ++k) s += exp(z[k] - m);
+            double dot = 0.0;
+            for (int k = 0; k < O; ++k) { z[k] = exp(z[k] - m) / s; dot += z[k] * un[k]; }
+            for (int k = 0; k < O; ++k) un[k] = z[k] * (un[k] - dot) / (double)N;
+        } else {
+            for (int k = 0; k < O; ++k) un[k] = 2.0 * un[k] / ((double)N * O);
+        }
+    }
+
+    /* reverse sweep: backpropagation of u */
+    for (int k = 0; k < O; ++k) Gc[k] = 0.0;
+    for (size_t e = 0; e < (size_t)H * O; ++e) GV[e] = 0.0;
+    for (long n = 0; n < N; ++n) {
+        const double *h = h_all + (size_t)(n + B) * H;
+        const double *un = u + (size_t)n * O;
+        for (int k = 0; k < O; ++k) Gc[k] += un[k];
+        for (int i = 0; i < H; ++i) {
+            double s = 0.0;
+            for (int k = 0; k < O; ++k) {
+                GV[(size_t)i * O + k] += h[i] * un[k];
+                s += V[(size_t)i * O + k] * un[k];
+            }
+            g[(size_t)n * H + i] = s;
+        }
+    }
+    for (int j = 0; j < H; ++j) Gb[j] = 0.0;
+    for (size_t e = 0; e < (size_t)H * H; ++e) GWh[e] = 0.0;
+    for (size_t e = 0; e < wx_elems; ++e) GWx[e] = 0.0;
+    for (int bb = 0; bb < B; ++bb) {
+        for (int t = T - 1; t >= 0; --t) {
+            const size_t n = (size_t)t * B + bb;
+            const double *ht = h_all + ((size_t)(t + 1) * B + bb) * H;
+            const double *hp = h_all + ((size_t)t * B + bb) * H;
+            double *dl = delta + n * H;
+            for (int j = 0; j < H; ++j) {
+                double dh = g[n * H + j];
+                if (t + 1 < T) {
+                    const double *dn = delta + ((size_t)(t + 1) * B + bb) * H;
+                    for (int i = 0; i < H; ++i) dh += Wh[(size_t)i * H + j] * dn[i];
+                }
+                const double dact = d->act == 0 ? ht[j] * (1.0 - ht[j]) : 1.0 - ht[j] * ht[j];
+                dl[j] = dh * dact;
+            }
+            for (int j = 0; j < H; ++j) {
+                Gb[j] += dl[j];
+                for (int i = 0; i < H; ++i) GWh[(size_t)j * H + i] += dl[j] * hp[i];
+                if (d->input_kind == 0) {
+                    GWx[(size_t)ids[n] * H + j] += dl[j];
+                } else {
+                    const double *xt = X + n * D;
+                    for (int k = 0; k < D; ++k) GWx[(size_t)j * D + k] += dl[j] * xt[k];
+                }
+            }
+        }
+    }
+    free(Rh); free(u); free(g); free(delta); free(z);
+    return 0;
+}

@@ -170,3 +170,10 @@ def stream_ids(case: dict) -> np.ndarray:
     """The token stream of a multi-window token case as one array int32[windows*T + 1, B]:
     x followed by the last target (y is the same stream shifted by one step)."""
     return np.ascontiguousarray(np.concatenate([case["x"], case["y"][-1:]], axis=0), dtype=np.int32)
+
+
+def make_direction(case: dict, seed: int, scale: float = 1.0) -> dict:
+    """A random direction gamma of the parameters' shapes (for Jacobian-vector products)."""
+    rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED, seed]))
+    return {k: (scale * rng.standard_normal(size=np.shape(case[k]))).astype(np.float32)
+            for k in ("Wx", "Wh", "b", "V", "c")}
