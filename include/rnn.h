@@ -214,6 +214,36 @@ int rnn_window(const rnn_dims *dims, const rnn_params *params, const int32_t *x,
                float *h_last, float *loss, const rnn_grads *grads, float *dh0,
                void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Gauss-Newton matrix times a vector by the R-operator (the paper's section on the R-operator:
+ * the forward-mode derivative R{f} = (df/dtheta) gamma carried through the loop next to the
+ * states, then a reverse pass, i.e. Lop(f, theta, Rop(f, theta, gamma)) -- two passes over the
+ * sequence instead of forming any Jacobian).  f is the matrix of all T*B output rows z; with
+ * J = df/dtheta the call returns  J^T M J gamma  for
+ *   RNN_GN_METRIC_LOSS      M = Hessian of this library's mean loss w.r.t. z
+ *                           (softmax-CE: (diag(p) - p p^T)/N per row; linear-MSE: 2/(N O) I)
+ *   RNN_GN_METRIC_IDENTITY  M = I, the paper's literal expression.
+ *     R a_t = gin_t + gamma.b + gamma.Wh h_{t-1} + Wh R h_{t-1}    gin_t = gamma.Wx[x_t,:] or gamma.Wx x_t
+ *     R h_t = act'(h_t) R a_t,  R h_{-1} = 0 (the initial state is a constant)
+ *     R z_t = V^T R h_t + gamma.V^T h_t + gamma.c;   u = M R z;   result = backpropagation of u
+ *   params, gamma  the parameters and a direction of the same shapes (device, 16-byte aligned)
+ *   x        as in rnn_forward;  h_all [T+1,B,H] from rnn_forward with these parameters
+ *   out      five device pointers of the parameters' shapes; overwritten, or added to with
+ *            RNN_FLAG_ACCUMULATE (token input: rows of out->dWx as in rnn_bptt)
+ *   Rz       [T*B,out_dim] receives R z (the R-operator's own result); NULL = not wanted
+ *   workspace  rnn_gauss_newton_workspace_bytes() bytes, 16-byte aligned; its first
+ *            rnn_workspace_bytes() bytes are an ordinary workspace and need rnn_workspace_init
+ *            once.  The logits rnn_loss left in a workspace do not survive this call.
+ * Needs no prior rnn_loss.  Asynchronous like the other calls.  RNN_FLAG_BPTT_RECOMPUTE is
+ * rejected (RNN_EINVAL).
+ */
+#define RNN_GN_METRIC_LOSS     0
+#define RNN_GN_METRIC_IDENTITY 1
+int rnn_gauss_newton_workspace_bytes(const rnn_dims *dims, size_t *bytes);
+int rnn_gauss_newton_vec(const rnn_dims *dims, const rnn_params *params, const rnn_params *gamma,
+                         const void *x, const float *h_all, int32_t metric, const rnn_grads *out,
+                         float *Rz, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static description of an error code (host string, never NULL). */
 const char *rnn_strerror(int code);
 

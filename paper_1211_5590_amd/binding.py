@@ -22,7 +22,8 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
            "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
-           "rnn_window")
+           "rnn_window", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec")
+GN_METRIC_LOSS, GN_METRIC_IDENTITY = 0, 1
 
 
 class RnnError(RuntimeError):
@@ -99,6 +100,11 @@ def lib():
         L.rnn_window_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
         L.rnn_window.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp,
                                  ctypes.POINTER(Grads), vp, vp, sz, vp]
+        L.rnn_gauss_newton_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
+        L.rnn_gauss_newton_vec.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), ctypes.POINTER(Params),
+                                           vp, vp, ctypes.c_int32, ctypes.POINTER(Grads), vp, vp, sz, vp]
+        for name in ("rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_train_stream_workspace_bytes", "rnn_train_stream", "rnn_train_stream_status",
                      "rnn_window_workspace_bytes", "rnn_window_workspace_init", "rnn_window"):
             getattr(L, name).restype = ctypes.c_int
@@ -200,6 +206,22 @@ def rnn_bptt(dims, params, x, targets, h_all, dh_last, grads, dh0, workspace, st
     pr, gr = _params(params), _grads(grads)
     rc = lib().rnn_bptt(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(targets), _p(h_all),
                         _p(dh_last), ctypes.byref(gr), _p(dh0), wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_gauss_newton_workspace_bytes(dims: Dims) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().rnn_gauss_newton_workspace_bytes(ctypes.byref(dims), ctypes.byref(n)))
+    return n.value
+
+
+def rnn_gauss_newton_vec(dims, params, gamma, x, h_all, metric, out, Rz, workspace, stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr, ga, gr = _params(params), _params(gamma), _grads(out)
+    rc = lib().rnn_gauss_newton_vec(ctypes.byref(dims), ctypes.byref(pr), ctypes.byref(ga), _p(x), _p(h_all),
+                                    int(metric), ctypes.byref(gr), _p(Rz), wp, wb, _stream(stream))
     if check:
         _check(rc)
     return rc

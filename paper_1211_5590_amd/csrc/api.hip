@@ -260,9 +260,56 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
     return launch_loss_reduce(rowloss, n_partial, (float)(1.0 / ((double)N * (double)z.O)), loss, s);
 }
 
-hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const void* targets,
-                    const float* h_all, const float* dh_last, const rnn_grads* Gr, float* dh0,
-                    void* ws, const Plan& pl, hipStream_t s) {
+// Reverse-time loop delta_t = (G_t + Wh^T delta_{t+1}) * act'(h_t) with the kernel family that
+// serves these sizes (never the fused short-sequence form).  Wh and its transposed copy are
+// passed explicitly: the R-operator's forward sweep is the same recurrence run on time-reversed
+// rows with the two exchanged.
+hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT_or_null, float* WhT_ws,
+                            const float* G, const float* h_all, const float* dh_last, float* Delta,
+                            float* dh0, void* ws, const Plan& pl, hipStream_t s) {
+    const Sizes z = sizes_of(d);
+    const int H = z.H;
+    Variant v = pick_variant(d);
+    if (v.skinny) {   // the plain plan of the resident loop
+        if (!rec_resident_plan(z.H, z.B, z.T, true, false, 0, &v.bwd)) v.resident = false;
+    }
+    if (v.resident) {
+        RecResArgs r{};
+        r.Wh = Wh; r.H = H; r.T = z.T; r.B = z.B; r.act = d->act;
+        r.flags = at<int32_t>(ws, pl.flags); r.status = at<int32_t>(ws, pl.scratch) + 1;
+        r.G = G; r.h_all = h_all; r.dh_last = dh_last; r.Delta = Delta; r.dh0 = dh0;
+        return launch_rec_resident(r, v.bwd, true, s);
+    }
+    if (v.batch_mfma) {
+        RecMfmaArgs m{};
+        m.Wh = Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
+        m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
+        return launch_rec_batch_mfma(m, true, s);
+    }
+    if (v.stepwise) {
+        RecBwdArgs a{};
+        a.Wh = Wh; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
+        a.Delta = Delta; a.dh0 = dh0; a.splitk_ws = at<float>(ws, pl.splitk);
+        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
+        return run_rec_bwd_stepwise(a, s);
+    }
+    const float* WhT = WhT_or_null;
+    if (!WhT) {
+        RNN_TRY(launch_transpose(Wh, WhT_ws, H, H, s));
+        WhT = WhT_ws;
+    }
+    RecBwdArgs a{};
+    a.Wh = Wh; a.WhT = WhT; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
+    a.Delta = Delta; a.dh0 = dh0;
+    a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
+    return launch_rec_bwd_reference(a, s);
+}
+
+// Everything of backpropagation that follows d loss / d z (held in the logits buffer of the
+// workspace): dV, G, the reverse loop, dWh, db, dWx.  dc is the caller's.
+hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const void* x, const float* h_all,
+                                const float* dh_last, const rnn_grads* Gr, float* dh0, void* ws,
+                                const Plan& pl, hipStream_t s) {
     const Sizes z = sizes_of(d);
     const int N = (int)z.N, H = z.H, O = z.O;
     const int beta = (d->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
@@ -272,6 +319,64 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
     float* G = at<float>(ws, pl.G);
     float* Delta = at<float>(ws, pl.Delta);
     const float* Hs = h_all + (size_t)z.B * H;  // h_t rows
+    const int chunks = colsum_chunks(N);
+    // dV = Hs^T dZ
+    {
+        GemmArgs g{};
+        g.A = Hs; g.B = Z; g.C = Gr->dV;
+        g.M = H; g.N = O; g.K = N;
+        g.lda = H; g.ldb = O; g.ldc = O;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DV;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    // G = dZ V^T
+    {
+        GemmArgs g{};
+        g.A = Z; g.B = P->V; g.C = G;
+        g.M = N; g.N = H; g.K = O;
+        g.lda = O; g.ldb = O; g.ldc = H;
+        g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk; g.prof_id = K_GEMM_G;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    RNN_TRY(run_reverse_loop(d, P->Wh, nullptr, at<float>(ws, pl.WhT), G, h_all, dh_last, Delta, dh0, ws, pl, s));
+    // dWh = Delta^T Hprev  (Hprev rows = h_all[0:T])
+    {
+        GemmArgs g{};
+        g.A = Delta; g.B = h_all; g.C = Gr->dWh;
+        g.M = H; g.N = H; g.K = N;
+        g.lda = H; g.ldb = H; g.ldc = H;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWH;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    // db = column sums of Delta
+    RNN_TRY(launch_colsum_partial(Delta, part, N, H, s));
+    RNN_TRY(launch_colsum_finish(part, Gr->db, chunks, H, beta, s));
+    // dWx
+    if (z.tokens) {
+        // the logits buffer is dead by now and serves as scratch for per-range partial rows
+        RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta,
+                                  Z, (size_t)N * O, N > 32 ? at<int32_t>(ws, pl.seen) : nullptr, s));
+    } else {
+        GemmArgs g{};
+        g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;
+        g.M = H; g.N = z.NVin; g.K = N;
+        g.lda = H; g.ldb = z.NVin; g.ldc = z.NVin;
+        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWX;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    return hipSuccess;
+}
+
+hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const void* targets,
+                    const float* h_all, const float* dh_last, const rnn_grads* Gr, float* dh0,
+                    void* ws, const Plan& pl, hipStream_t s) {
+    const Sizes z = sizes_of(d);
+    const int N = (int)z.N, H = z.H, O = z.O;
+    const int beta = (d->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
+    float* Z = at<float>(ws, pl.Z);
+    float* part = at<float>(ws, pl.part);
+    float* G = at<float>(ws, pl.G);
+    float* Delta = at<float>(ws, pl.Delta);
     const int chunks = colsum_chunks(N);
     const Variant v = pick_variant(d);
 
@@ -301,74 +406,109 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
                       z.ce ? nullptr : static_cast<const float*>(targets), part, N, O,
                       d->loss_kind, s));
     RNN_TRY(launch_colsum_finish(part, Gr->dc, chunks, O, beta, s));
+    return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, s);
+}
 
-    // dV = Hs^T dZ
-    {
+// Extra regions of the Gauss-Newton-vector product behind the ordinary plan.
+struct GnPlan {
+    Plan base;
+    size_t logits, Rh, hrev, splitk_c, total;
+};
+
+GnPlan make_gn_plan(const rnn_dims* d) {
+    const Sizes s = sizes_of(d);
+    const size_t N = (size_t)s.N, H = (size_t)s.H, O = (size_t)s.O, B = (size_t)s.B;
+    GnPlan p;
+    p.base = make_plan(d);
+    size_t off = p.base.total;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up(bytes); return o; };
+    p.logits = take(N * O * 4);
+    p.Rh = take(N * H * 4);
+    p.hrev = take((N + B) * H * 4);
+    p.splitk_c = take(gemm_splitk_floats((int)N, (int)H, (int)H) * 4);   // Hprev gWh^T
+    p.total = off;
+    return p;
+}
+
+// G gamma = J^T M J gamma (the paper's section on the R-operator).  Forward sweep of the
+// R-operator:  R a_t = gin_t + gb + gWh h_{t-1} + Wh R h_{t-1},  R h_t = act'(h_t) R a_t.  Its
+// non-recurrent part C_t = gin_t + gb + gWh h_{t-1} is one product over all steps (hoisted like
+// the input term); what stays in the loop has the form of the reverse loop of backpropagation
+// with time running the other way and Wh transposed, so it runs on that loop's kernels over
+// time-reversed rows.  R z = R h V + h gV + gc, the loss metric row by row, then ordinary
+// backpropagation of the result.
+hipError_t run_gauss_newton(const rnn_dims* d, const rnn_params* P, const rnn_params* Ga, const void* x,
+                            const float* h_all, int metric, const rnn_grads* Out, float* Rz_out,
+                            void* ws, const GnPlan& gp, hipStream_t s) {
+    const Plan& pl = gp.base;
+    const Sizes z = sizes_of(d);
+    const int N = (int)z.N, H = z.H, O = z.O;
+    const size_t BH = (size_t)z.B * H;
+    const int beta = (d->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
+    float* U = at<float>(ws, pl.Z);          // R z, then u = M R z (what backpropagation reads)
+    float* Zl = at<float>(ws, gp.logits);
+    float* C = at<float>(ws, pl.Delta);
+    float* Crev = at<float>(ws, pl.G);
+    float* Rhrev = at<float>(ws, pl.Delta);  // C is dead once Crev exists
+    float* Rh = at<float>(ws, gp.Rh);
+    float* hrev = at<float>(ws, gp.hrev);
+    float* WhT = at<float>(ws, pl.WhT);
+    float* splitk = at<float>(ws, pl.splitk);
+    const float* Hs = h_all + BH;
+    const bool ce_metric = metric == RNN_GN_METRIC_LOSS && z.ce;
+
+    if (ce_metric) {   // logits of the current parameters, for the softmax in the metric
         GemmArgs g{};
-        g.A = Hs; g.B = Z; g.C = Gr->dV;
-        g.M = H; g.N = O; g.K = N;
-        g.lda = H; g.ldb = O; g.ldc = O;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DV;
+        g.A = Hs; g.B = P->V; g.C = Zl;
+        g.M = N; g.N = O; g.K = H; g.lda = H; g.ldb = O; g.ldc = O;
+        g.a_t = false; g.b_t = false; g.bias_n = P->c; g.beta = 0; g.prof_id = K_GEMM_LOGITS;
+        g.splitk_ws = splitk;
         RNN_TRY(launch_gemm(g, s));
     }
-    // G = dZ V^T
-    {
+    {   // C = Hprev gWh^T + gb
         GemmArgs g{};
-        g.A = Z; g.B = P->V; g.C = G;
-        g.M = N; g.N = H; g.K = O;
-        g.lda = O; g.ldb = O; g.ldc = H;
-        g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk; g.prof_id = K_GEMM_G;
+        g.A = h_all; g.B = Ga->Wh; g.C = C;
+        g.M = N; g.N = H; g.K = H; g.lda = H; g.ldb = H; g.ldc = H;
+        g.a_t = false; g.b_t = true; g.bias_n = Ga->b; g.beta = 0; g.prof_id = K_GEMM_U;
+        g.splitk_ws = at<float>(ws, gp.splitk_c);
         RNN_TRY(launch_gemm(g, s));
     }
-    // reverse-time loop
-    if (v.resident) {
-        RNN_TRY(launch_rec_resident(r, v.bwd, true, s));
-    } else if (v.batch_mfma) {
-        RecMfmaArgs m{};
-        m.Wh = P->Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
-        m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
-        RNN_TRY(launch_rec_batch_mfma(m, true, s));
-    } else if (v.stepwise) {
-        RecBwdArgs a{};
-        a.Wh = P->Wh; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
-        a.Delta = Delta; a.dh0 = dh0; a.splitk_ws = splitk;
-        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
-        RNN_TRY(run_rec_bwd_stepwise(a, s));
-    } else {
-        float* WhT = at<float>(ws, pl.WhT);
-        RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
-        RecBwdArgs a{};
-        a.Wh = P->Wh; a.WhT = WhT; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
-        a.Delta = Delta; a.dh0 = dh0;
-        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
-        RNN_TRY(launch_rec_bwd_reference(a, s));
-    }
-    // dWh = Delta^T Hprev  (Hprev rows = h_all[0:T])
-    {
-        GemmArgs g{};
-        g.A = Delta; g.B = h_all; g.C = Gr->dWh;
-        g.M = H; g.N = H; g.K = N;
-        g.lda = H; g.ldb = H; g.ldc = H;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWH;
-        RNN_TRY(launch_gemm(g, s));
-    }
-    // db = column sums of Delta
-    RNN_TRY(launch_colsum_partial(Delta, part, N, H, s));
-    RNN_TRY(launch_colsum_finish(part, Gr->db, chunks, H, beta, s));
-    // dWx
     if (z.tokens) {
-        // the logits buffer is dead by now and serves as scratch for per-range partial rows
-        RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta,
-                                  Z, (size_t)N * O, N > 32 ? at<int32_t>(ws, pl.seen) : nullptr, s));
-    } else {
+        RNN_TRY(launch_gather_add(static_cast<const int32_t*>(x), Ga->Wx, C, N, H, s));
+    } else {   // C += X gWx^T
         GemmArgs g{};
-        g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;
-        g.M = H; g.N = z.NVin; g.K = N;
-        g.lda = H; g.ldb = z.NVin; g.ldc = z.NVin;
-        g.a_t = true; g.b_t = false; g.beta = beta; g.splitk_ws = splitk; g.prof_id = K_GEMM_DWX;
+        g.A = static_cast<const float*>(x); g.B = Ga->Wx; g.C = C;
+        g.M = N; g.N = H; g.K = z.NVin; g.lda = z.NVin; g.ldb = z.NVin; g.ldc = H;
+        g.a_t = false; g.b_t = true; g.beta = 1; g.prof_id = K_GEMM_U; g.splitk_ws = splitk;
         RNN_TRY(launch_gemm(g, s));
     }
-    return hipSuccess;
+    // time-reversed rows: Crev[t] = C[T-1-t], hrev[t+1] = h_{T-1-t}
+    RNN_TRY(launch_reverse_rows(C, Crev, z.T, (int)BH, s));
+    RNN_TRY(launch_reverse_rows(Hs, hrev + BH, z.T, (int)BH, s));
+    RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
+    RNN_TRY(run_reverse_loop(d, WhT, P->Wh, nullptr, Crev, hrev, nullptr, Rhrev, nullptr, ws, pl, s));
+    RNN_TRY(launch_reverse_rows(Rhrev, Rh, z.T, (int)BH, s));
+    {   // R z = Rh V + gc
+        GemmArgs g{};
+        g.A = Rh; g.B = P->V; g.C = U;
+        g.M = N; g.N = O; g.K = H; g.lda = H; g.ldb = O; g.ldc = O;
+        g.a_t = false; g.b_t = false; g.bias_n = Ga->c; g.beta = 0; g.prof_id = K_GEMM_LOGITS;
+        g.splitk_ws = splitk;
+        RNN_TRY(launch_gemm(g, s));
+        // ... + Hs gV
+        g.A = Hs; g.B = Ga->V; g.bias_n = nullptr; g.beta = 1;
+        RNN_TRY(launch_gemm(g, s));
+    }
+    if (Rz_out)
+        RNN_TRY(hipMemcpyAsync(Rz_out, U, (size_t)N * O * 4, hipMemcpyDeviceToDevice, s));
+    if (ce_metric)
+        RNN_TRY(launch_gn_softmax_metric(Zl, U, N, O, 1.0f / (float)N, s));
+    else if (metric == RNN_GN_METRIC_LOSS)
+        RNN_TRY(launch_scale(U, (size_t)N * O, (float)(2.0 / ((double)N * (double)O)), s));
+    // Gc = column sums of u, then the rest of backpropagation
+    RNN_TRY(launch_colsum_partial(U, at<float>(ws, pl.part), N, O, s));
+    RNN_TRY(launch_colsum_finish(at<float>(ws, pl.part), Out->dc, colsum_chunks(N), O, beta, s));
+    return run_backward_from_dz(d, P, x, h_all, nullptr, Out, nullptr, ws, pl, s);
 }
 
 bool params_ok(const rnn_params* P) {
@@ -434,6 +574,31 @@ int rnn_bptt(const rnn_dims* dims, const rnn_params* params, const void* x, cons
         if (e != hipSuccess) return RNN_EHIP;
     }
     return finish(dims, s, run_bptt(dims, params, x, targets, h_all, dh_last, grads, dh0, workspace, pl, s));
+}
+
+int rnn_gauss_newton_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
+    if (!dims_valid(dims) || !bytes) return RNN_EINVAL;
+    *bytes = make_gn_plan(dims).total;
+    return RNN_OK;
+}
+
+int rnn_gauss_newton_vec(const rnn_dims* dims, const rnn_params* params, const rnn_params* gamma,
+                         const void* x, const float* h_all, int32_t metric, const rnn_grads* out,
+                         float* Rz, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!dims_valid(dims) || !params_ok(params) || !params_ok(gamma) || !x || !h_all || !out)
+        return RNN_EINVAL;
+    if (metric != RNN_GN_METRIC_LOSS && metric != RNN_GN_METRIC_IDENTITY) return RNN_EINVAL;
+    if (dims->flags & RNN_FLAG_BPTT_RECOMPUTE) return RNN_EINVAL;
+    if (!out->dWx || !out->dWh || !out->db || !out->dV || !out->dc) return RNN_EINVAL;
+    if (misaligned4(x) || misaligned(h_all) || misaligned(Rz) || misaligned(out->dWx) ||
+        misaligned(out->dWh) || misaligned(out->db) || misaligned(out->dV) || misaligned(out->dc))
+        return RNN_EINVAL;
+    if (!reference_supported(dims)) return RNN_EUNSUPPORTED;
+    const GnPlan gp = make_gn_plan(dims);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < gp.total)
+        return RNN_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return finish(dims, s, run_gauss_newton(dims, params, gamma, x, h_all, metric, out, Rz, workspace, gp, s));
 }
 
 int rnn_check_tokens(const void* ids, int64_t n, int32_t limit, int32_t* bad_count, void* hip_stream) {

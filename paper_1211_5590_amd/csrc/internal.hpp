@@ -152,6 +152,15 @@ size_t skinny_stat_box_bytes(int N, int O);
 hipError_t launch_skinny_logits(const SkinnyArgs& a, hipStream_t s);   // logits, statistics and loss
 
 // ---------------------------------------------------------------------------------------
+// Small kernels of the Gauss-Newton-vector product (gauss_newton.hip)
+hipError_t launch_reverse_rows(const float* src, float* dst, int T, int row, hipStream_t s);   // dst[t] = src[T-1-t]
+hipError_t launch_gather_add(const int32_t* x, const float* M, float* C, int N, int H, hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+hipError_t launch_scale(float* p, size_t n, float alpha, hipStream_t s);
+// RZ_n <- (p * RZ_n - p (p . RZ_n)) * scale, p = softmax(Z_n)
+hipError_t launch_gn_softmax_metric(const float* Z, float* RZ, int N, int O, float scale, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
 // Token-keyed gradient of the input matrix and id validation
 // scratch (>= scratch_floats floats) and slot_table (>= dwx_table_ints(N, NV) ints) enable the grouped form
 size_t dwx_table_ints(int N, int NV);

@@ -107,3 +107,29 @@ def test_train_stream_rejects_what_it_cannot_run_without_a_gpu():
     assert call(P, fake, 1, None, need) == -2
     assert call(P, fake, 1, fake, need - 1) == -2
     assert call(P, fake, 0, fake, need) == 0          # nothing to do: nothing is launched
+
+
+def test_gauss_newton_rejects_bad_arguments_without_a_gpu():
+    d = good_dims()
+    fake = 0x1000  # never dereferenced: every check below fails before any launch
+    P = rnn.Params(fake, fake, fake, fake, fake)
+    G = rnn.Grads(fake, fake, fake, fake, fake)
+    L = rnn.lib()
+    need = rnn.rnn_gauss_newton_workspace_bytes(d)
+    assert need > rnn.rnn_workspace_bytes(d)
+
+    def call(dims=d, params=P, gamma=P, x=fake, h_all=fake, metric=0, out=G, Rz=None, ws=fake, nbytes=need):
+        return L.rnn_gauss_newton_vec(ctypes.byref(dims), ctypes.byref(params), ctypes.byref(gamma), x, h_all,
+                                      metric, ctypes.byref(out), Rz, ws, nbytes, None)
+    assert call(x=None) == -1
+    assert call(h_all=None) == -1
+    assert call(gamma=rnn.Params(fake, fake, None, fake, fake)) == -1
+    assert call(out=rnn.Grads(fake, fake, fake, None, fake)) == -1
+    assert call(metric=2) == -1
+    assert call(Rz=fake + 4) == -1
+    assert call(dims=good_dims(flags=rnn.FLAG_BPTT_RECOMPUTE)) == -1
+    assert call(dims=good_dims(hidden=0)) == -1
+    assert call(ws=None) == -2
+    assert call(nbytes=rnn.rnn_workspace_bytes(d)) == -2
+    with pytest.raises(rnn.RnnError):
+        rnn.rnn_gauss_newton_workspace_bytes(good_dims(act=7))
