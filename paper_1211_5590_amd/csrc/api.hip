@@ -28,7 +28,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Plan {
     // byte offsets into the workspace
     size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gbox, gpart, vy, seen,
-        total;
+        lstat, total;
 };
 
 // Which kernel family serves these sizes.
@@ -135,6 +135,8 @@ Plan make_plan(const rnn_dims* d) {
     p.gpart = take(small ? strips * N * H * 4 : 0);
     p.vy = take(small ? N * H * 4 : 0);
     p.seen = take(s.tokens && N > 32 ? dwx_table_ints((int)N, s.NVin) * 4 : 0);
+    // row statistics the logits product leaves per 64-column part (fused log-sum-exp)
+    p.lstat = take(s.ce && gemm_fuses_stats((int)N, s.O, s.H) ? N * (size_t)gemm_stat_parts(s.O) * 8 : 0);
     p.total = off;
     return p;
 }
@@ -248,8 +250,17 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
     g.lda = z.H; g.ldb = z.O; g.ldc = z.O;
     g.a_t = false; g.b_t = false; g.bias_n = P->c; g.beta = 0; g.prof_id = K_GEMM_LOGITS;
     g.splitk_ws = at<float>(ws, pl.splitk);
+    // softmax-CE: the product's epilogue leaves (max, sum exp) per row and 64-column part, so the
+    // logits are not read again for the log-sum-exp
+    const bool fused = z.ce && gemm_fuses_stats(N, z.O, z.H);
+    g.row_stats = fused ? at<float>(ws, pl.lstat) : nullptr;
     RNN_TRY(launch_gemm(g, s));
     float* rowloss = at<float>(ws, pl.rowloss);
+    if (fused) {
+        RNN_TRY(launch_ce_merge_stats(g.row_stats, gemm_stat_parts(z.O), Z, static_cast<const int32_t*>(targets),
+                                      at<float>(ws, pl.lse), rowloss, N, z.O, s));
+        return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
+    }
     if (z.ce) {
         RNN_TRY(launch_ce_row_stats(Z, static_cast<const int32_t*>(targets), at<float>(ws, pl.lse),
                                     rowloss, N, z.O, s));

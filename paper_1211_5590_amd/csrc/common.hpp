@@ -19,6 +19,36 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+// Butterfly stages of a wavefront reduction without LDS traffic.  Stages 1 and 2 permute within
+// quads, 4 and 8 mirror within 8 and 16 lanes (equivalent to xor once the smaller stages have
+// run), 16 and 32 swap rows / halves of two registers.
+__device__ __forceinline__ float sum4(float v) { v += dpp<0xB1>(v); v += dpp<0x4E>(v); return v; }
+__device__ __forceinline__ float sum16(float v) { v = sum4(v); v += dpp<0x141>(v); v += dpp<0x140>(v); return v; }
+__device__ __forceinline__ float swap16_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float swap32_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum32(float v) { return swap16_sum(sum16(v)); }
+__device__ __forceinline__ float sum64(float v) { return swap32_sum(sum32(v)); }
+__device__ __forceinline__ float max16(float v) {
+    v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
+    v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
+    return v;
+}
+__device__ __forceinline__ float max32(float v) {
+    v = max16(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
 __device__ __forceinline__ float sigmoidf_fast(float a) {

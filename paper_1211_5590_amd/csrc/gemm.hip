@@ -38,6 +38,7 @@ struct GemmParams {
     int splits;
     int tiles_m, tiles_n;
     int prof_id;
+    float* stats;      // nullable: per row and per 64-column part (max, sum of exp relative to it)
 };
 
 // One operand tile of R rows (R = BM or BN) by BK columns of K, fetched into registers.
@@ -133,7 +134,7 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
     tm = in_group / gsz;
 }
 
-template <int BM, int BN, bool AT, bool BT, bool VEC>
+template <int BM, int BN, bool AT, bool BT, bool VEC, bool STATS>
 __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
     constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA blocks per wavefront, per dim
     __shared__ __attribute__((aligned(16))) float As[2][BK * (BM + PAD)];
@@ -224,6 +225,42 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
                 }
             }
         }
+
+    // Fused row statistics of a log-sum-exp over the columns: every wavefront leaves, for each of
+    // its rows, the maximum of its 64 columns and the sum of exponentials relative to it (the 32
+    // lanes of a half-wave hold 32 columns of the same row in every accumulator register).
+    if (STATS && final_out) {
+        const int nparts = p.tiles_n * 2;
+        const int part = tile_n * 2 + wn;
+        int col[TN];
+        float bias[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            col[j] = n0 + wn * (BN / 2) + 32 * j + lane % 32;
+            bias[j] = (p.bias_n && col[j] < p.N) ? p.bias_n[col[j]] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float v[TN];
+                float m = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    v[j] = acc[i][j][e] + bias[j];
+                    if (col[j] < p.N) m = fmaxf(m, v[j]);
+                }
+                m = max32(m);   // register-to-register lane exchanges: no LDS round trips in the chain
+                float sum = 0.f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (col[j] < p.N) sum += __expf(v[j] - m);
+                sum = sum32(sum);
+                const int row = m0 + wm * (BM / 2) + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+                if (lane % 32 == 0 && row < p.M)
+                    *reinterpret_cast<float2*>(p.stats + ((size_t)row * nparts + part) * 2) = make_float2(m, sum);
+            }
+    }
 }
 
 // C[m,n] = (beta ? C : 0) + sum_s part[s][m][n] + bias[n], fixed summation order.
@@ -317,17 +354,20 @@ SplitPlan plan_split(int M, int N, int K) {
     return {splits, kchunk};
 }
 
-template <int BM, int BN, bool AT, bool BT, bool VEC>
+template <int BM, int BN, bool AT, bool BT, bool VEC, bool STATS = false>
 hipError_t launch_variant(const GemmParams& p, hipStream_t s) {
     dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
     ProfileScope ps(p.prof_id, s);
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, AT, BT, VEC>), grid, dim3(NT), 0, s, p);
+    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, AT, BT, VEC, STATS>), grid, dim3(NT), 0, s, p);
     return hipGetLastError();
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
+
+int gemm_stat_parts(int N) { return 2 * ((N + BN_ - 1) / BN_); }
+bool gemm_fuses_stats(int M, int N, int K) { return plan_split(M, N, K).splits == 1; }
 
 size_t gemm_splitk_floats(int M, int N, int K) {
     const SplitPlan sp = plan_split(M, N, K);
@@ -344,6 +384,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.lda = g.lda; p.ldb = g.ldb;
+    p.stats = sp.splits == 1 ? g.row_stats : nullptr;
     p.kchunk = sp.kchunk; p.beta = g.beta; p.splits = sp.splits; p.prof_id = g.prof_id;
     p.tiles_m = (g.M + bm - 1) / bm;
     p.tiles_n = (g.N + bn - 1) / bn;
@@ -357,7 +398,11 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     hipError_t e;
 #define RNN_GEMM_DISPATCH(AT, BT)                                              \
     e = vec ? launch_variant<BM_, BN_, AT, BT, true>(p, s) : launch_variant<BM_, BN_, AT, BT, false>(p, s)
-    if (!g.a_t && !g.b_t) RNN_GEMM_DISPATCH(false, false);
+    if (p.stats) {   // only the plain-layout product (the output projection) carries the statistics
+        if (g.a_t || g.b_t) return hipErrorInvalidValue;
+        e = vec ? launch_variant<BM_, BN_, false, false, true, true>(p, s)
+                : launch_variant<BM_, BN_, false, false, false, true>(p, s);
+    } else if (!g.a_t && !g.b_t) RNN_GEMM_DISPATCH(false, false);
     else if (g.a_t && !g.b_t) RNN_GEMM_DISPATCH(true, false);
     else if (!g.a_t && g.b_t) RNN_GEMM_DISPATCH(false, true);
     else RNN_GEMM_DISPATCH(true, true);

@@ -22,8 +22,13 @@ struct GemmArgs {
     int beta;             // 0 overwrite, 1 accumulate
     float* splitk_ws;     // nullable when gemm_splitk_floats == 0
     int prof_id;          // kernel id under which the profiler books this product (prof.hpp)
+    // nullable: [M][gemm_stat_parts(N)][2] receives, per row and per 64-column part of the final
+    // result, (max, sum of exp relative to that max); written only when gemm_fuses_stats(M,N,K)
+    float* row_stats;
 };
 size_t gemm_splitk_floats(int M, int N, int K);
+int gemm_stat_parts(int N);
+bool gemm_fuses_stats(int M, int N, int K);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
@@ -113,6 +118,9 @@ hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s);
 // Output layer element-wise / row-wise kernels
 hipError_t launch_ce_row_stats(const float* Z, const int32_t* y, float* lse, float* rowloss,
                                int N, int O, hipStream_t s);
+// the same from the statistics the logits product left: stats [N][parts][2]
+hipError_t launch_ce_merge_stats(const float* stats, int parts, const float* Z, const int32_t* y,
+                                 float* lse, float* rowloss, int N, int O, hipStream_t s);
 // squared-error partial sums over the flat [N*O] arrays: *n_partial (<= N) floats in `partial`
 hipError_t launch_mse_partial(const float* Z, const float* Y, float* partial, int N, int O,
                               int* n_partial, hipStream_t s);

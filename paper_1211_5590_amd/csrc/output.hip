@@ -50,6 +50,34 @@ __global__ __launch_bounds__(256) void ce_row_stats_kernel(const float* __restri
     }
 }
 
+// One wavefront per row: merges the (max, sum exp) pairs the logits product left per 64-column
+// part, in a fixed order, into lse; rowloss = lse - z[y].
+__global__ __launch_bounds__(256) void ce_merge_stats_kernel(const float* __restrict__ stats, int parts,
+                                                             const float* __restrict__ Z,
+                                                             const int32_t* __restrict__ y,
+                                                             float* __restrict__ lse,
+                                                             float* __restrict__ rowloss, int N, int O) {
+    const int lane = threadIdx.x % kWave;
+    const int n = blockIdx.x * 4 + threadIdx.x / kWave;
+    if (n >= N) return;
+    const float2* st = reinterpret_cast<const float2*>(stats) + (size_t)n * parts;
+    float m = -INFINITY, s = 0.f;
+    for (int q = lane; q < parts; q += kWave) {
+        const float2 t = st[q];
+        lse_merge(m, s, t.x, t.y);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off, kWave), s2 = __shfl_xor(s, off, kWave);
+        lse_merge(m, s, m2, s2);
+    }
+    if (lane == 0) {
+        const float l = m + logf(s);
+        lse[n] = l;
+        rowloss[n] = l - Z[(size_t)n * O + y[n]];
+    }
+}
+
 // Mean-squared error is a sum over the flat [N*O] array: workgroup b sums the squared errors of
 // elements [b*per_block, (b+1)*per_block) in a fixed order and leaves one partial.
 template <int VEC>
@@ -286,6 +314,14 @@ hipError_t launch_ce_row_stats(const float* Z, const int32_t* y, float* lse, flo
                                int O, hipStream_t s) {
     ProfileScope ps(K_CE_ROW_STATS, s);
     hipLaunchKernelGGL(ce_row_stats_kernel, dim3(N), dim3(256), 0, s, Z, y, lse, rowloss, O);
+    return hipGetLastError();
+}
+
+hipError_t launch_ce_merge_stats(const float* stats, int parts, const float* Z, const int32_t* y,
+                                 float* lse, float* rowloss, int N, int O, hipStream_t s) {
+    ProfileScope ps(K_CE_ROW_STATS, s);
+    hipLaunchKernelGGL(ce_merge_stats_kernel, dim3((N + 3) / 4), dim3(256), 0, s, stats, parts, Z, y, lse,
+                       rowloss, N, O);
     return hipGetLastError();
 }
 
