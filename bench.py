@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_MFMA_PEAK_TFLOPS = 157.3
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 matrix rate
 N_CU = 256
 LDS_PEAK_GBS_PER_CU = 256 * 2.4   # 16-byte LDS reads: 256 B/clk per compute unit at 2.4 GHz
 
@@ -44,6 +45,8 @@ def parse():
                     help="skip the single-launch SGD driver leg of the headline workload")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
+    ap.add_argument("--bf16x3", action="store_true",
+                    help="opt-in output layer on the bf16 matrix cores (hi/lo split operands, three products)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run a plain 64 MiB device copy (known traffic) to scale profiler counters by")
     return ap.parse_args()
@@ -92,6 +95,7 @@ class Workload:
         self.x_stride = self.x[0].numel() * self.x.element_size() * self.T
         self.y_stride = self.y[0].numel() * self.y.element_size() * self.T
         case["_name"] = name
+        case["_bf16x3"] = bool(flags & rnn.FLAG_BF16X3_OUTPUT)
         case["_variant"] = rnn.rnn_recurrence_variant(self.dims)
         case["_workgroups"] = rnn.rnn_recurrence_workgroups(self.dims)
         self.tokens_per_step = self.T * self.B * self.windows
@@ -190,6 +194,9 @@ def algorithmic_work(kernel, c):
         "mse_row_loss": (2 * f * N * O, 3.0 * N * O),
         "dz": ((3 if not c["loss_kind"] == 0 else 2) * f * N * O, 3.0 * N * O),
         "dwx_tokens": (f * (N * H + I * H), 1.0 * N * H),
+        # float32 matrix in, bf16 hi/lo planes out (row-major and transposed: 4 bytes per element each);
+        # per step: h, V and dZ
+        "split_bf16": (f * 3 * (N * H + H * O + N * O) / 3.0, 6.0 * (N * H + H * O + N * O) / 3.0),
         # time loops: the recurrent matrix once per launch, one state row in and out per step
         "rec_fwd": None, "rec_bwd": None,
         # short-sequence output layer (column strips): V in, Z out, and the strips' shares of the
@@ -260,6 +267,14 @@ def _roofline_entry(name, prof, case):
                     traffic=None, avg_us=us)
     nbytes, flops = work
     sec = us * 1e-6
+    if case.get("_bf16x3") and name in ("gemm_logits", "gemm_dV", "gemm_G"):
+        # hi/lo split operands: three bf16 matrix instructions per product term, so the matrix
+        # cores execute 3x the algorithmic flops; both rates are stated against the bf16 peak
+        ach = flops / sec / 1e12
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=ach / BF16_MFMA_PEAK_TFLOPS, traffic=None, avg_us=us, algorithmic_flops=flops,
+                    dtype="bf16 hi/lo split, f32 accumulate", executed_flops=3.0 * flops,
+                    frac_executed=3.0 * ach / BF16_MFMA_PEAK_TFLOPS)
     if flops / nbytes >= RIDGE:   # above the ridge point: arithmetic bound
         ach = flops / sec / 1e12
         # the batch-1..4 loops multiply on the vector ALUs (same fp32 peak as the matrix cores)
@@ -413,6 +428,8 @@ def main():
         sys.exit(3)
     import paper_1211_5590_amd as rnn
     flags = rnn.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
+    if a.bf16x3:
+        flags |= rnn.FLAG_BF16X3_OUTPUT
     default_steps = {"C1": 200, "C2": 3, "C3": 50, "C4": 10, "C5": 5}
     default_warm = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
     steps = a.steps if a.steps is not None else default_steps[a.workload]
@@ -439,7 +456,8 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warm,
         "ms_per_step": 1e3 * wall / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32 (output-layer products: bf16 hi/lo split, f32 accumulate)" if a.bf16x3 else "f32",
+        "data": "synthetic",
         "config": dict(workload=a.workload, **describe(wl.case),
                        entry_points="rnn_window" if wl.fused else "rnn_forward,rnn_loss,rnn_bptt",
                        recurrence_variant=rnn.rnn_recurrence_variant(wl.dims)),
@@ -483,6 +501,20 @@ def main():
                          roofline=roofline_of(pr, w.case),
                          kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
                                   for k, v in sorted(pr.items())})
+        del w
+        torch.cuda.empty_cache()
+    if "C4" in per and not a.bf16x3 and not a.reference_kernels:
+        # the same configuration with the opt-in bf16 hi/lo split output layer
+        name = "C4"
+        w = Workload(name, flags | rnn.FLAG_BF16X3_OUTPUT)
+        wall_o, _ = w.time_steps(default_steps[name], default_warm[name])
+        pr = w.profile(1)
+        per["C4_bf16x3_output"] = dict(tokens_per_s=w.tokens_per_step * default_steps[name] / wall_o,
+                                       ms_per_step=1e3 * wall_o / default_steps[name],
+                                       flag="RNN_FLAG_BF16X3_OUTPUT",
+                                       roofline=roofline_of(pr, w.case),
+                                       kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
+                                                for k, v in sorted(pr.items())})
         del w
         torch.cuda.empty_cache()
     if per:

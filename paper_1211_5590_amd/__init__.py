@@ -5,7 +5,7 @@ kernels of librnn_mi355x.so.  There is no CPU fallback: loading fails loudly if 
 is missing.
 """
 from .binding import (  # noqa: F401
-    ACT_SIGMOID, ACT_TANH, FLAG_ACCUMULATE, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS, FLAG_SYNC,
+    ACT_SIGMOID, ACT_TANH, FLAG_ACCUMULATE, FLAG_BF16X3_OUTPUT, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS, FLAG_SYNC,
     INPUT_DENSE, INPUT_TOKENS, LOSS_LINEAR_MSE, LOSS_SOFTMAX_CE, Dims, Grads, Params, RnnError,
     exported_symbols, lib, lib_path, rnn_bptt, rnn_check_tokens, rnn_forward, rnn_loss,
     rnn_profile_begin, rnn_profile_end, rnn_recurrence_variant, rnn_recurrence_workgroups, rnn_strerror,

@@ -16,6 +16,7 @@ INPUT_TOKENS, INPUT_DENSE = 0, 1
 ACT_SIGMOID, ACT_TANH = 0, 1
 LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
 FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 4, 8
+FLAG_BF16X3_OUTPUT = 16
 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
            "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",

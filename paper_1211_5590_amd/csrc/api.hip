@@ -28,7 +28,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Plan {
     // byte offsets into the workspace
     size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gbox, gpart, vy, seen,
-        lstat, total;
+        lstat, HsS, HsT, VS, VT, dZS, dZT, splitk3, total;
 };
 
 // Which kernel family serves these sizes.
@@ -54,7 +54,7 @@ bool dims_valid(const rnn_dims* d) {
     if (d->act != RNN_ACT_SIGMOID && d->act != RNN_ACT_TANH) return false;
     if (d->loss_kind != RNN_LOSS_SOFTMAX_CE && d->loss_kind != RNN_LOSS_LINEAR_MSE) return false;
     if (d->flags & ~(RNN_FLAG_ACCUMULATE | RNN_FLAG_SYNC | RNN_FLAG_BPTT_RECOMPUTE |
-                     RNN_FLAG_REFERENCE_KERNELS))
+                     RNN_FLAG_REFERENCE_KERNELS | RNN_FLAG_BF16X3_OUTPUT))
         return false;
     const long long N = (long long)d->seq_len * d->batch;
     // keep every row index and every N*width product the kernels form inside int32 / size_t
@@ -136,7 +136,24 @@ Plan make_plan(const rnn_dims* d) {
     p.vy = take(small ? N * H * 4 : 0);
     p.seen = take(s.tokens && N > 32 ? dwx_table_ints((int)N, s.NVin) * 4 : 0);
     // row statistics the logits product leaves per 64-column part (fused log-sum-exp)
-    p.lstat = take(s.ce && gemm_fuses_stats((int)N, s.O, s.H) ? N * (size_t)gemm_stat_parts(s.O) * 8 : 0);
+    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
+    const bool fuses = bf3 ? bf3_fuses_stats((int)N, s.O, s.H) : gemm_fuses_stats((int)N, s.O, s.H);
+    p.lstat = take(s.ce && fuses ? N * (size_t)gemm_stat_parts(s.O) * 8 : 0);
+    // bf16 hi/lo plane pairs of the output layer's operands (4 bytes per padded element)
+    const size_t Np = (size_t)bf3_pad((int)N), Hp = (size_t)bf3_pad(s.H), Op = (size_t)bf3_pad(s.O);
+    p.HsS = take(bf3 ? N * Hp * 4 : 0);
+    p.HsT = take(bf3 ? H * Np * 4 : 0);
+    p.VS = take(bf3 ? H * Op * 4 : 0);
+    p.VT = take(bf3 ? O * Hp * 4 : 0);
+    p.dZS = take(bf3 ? N * Op * 4 : 0);
+    p.dZT = take(bf3 ? O * Np * 4 : 0);
+    size_t sk3 = 0;
+    if (bf3) {
+        sk3 = bf3_splitk_floats((int)N, s.O, s.H);
+        if (bf3_splitk_floats(s.H, s.O, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.O, (int)N);
+        if (bf3_splitk_floats((int)N, s.H, s.O) > sk3) sk3 = bf3_splitk_floats((int)N, s.H, s.O);
+    }
+    p.splitk3 = take(sk3 * 4);
     p.total = off;
     return p;
 }
@@ -243,6 +260,34 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
         return launch_skinny_logits(k, s);
     }
     float* Z = at<float>(ws, pl.Z);
+    if (d->flags & RNN_FLAG_BF16X3_OUTPUT) {
+        // operands as bf16 hi/lo planes (h also transposed, for dV later; V both ways), then the
+        // product on the bf16 matrix cores
+        const float* Hs = h_all + (size_t)z.B * z.H;
+        RNN_TRY(launch_split_bf16(Hs, N, z.H, z.H, at<uint16_t>(ws, pl.HsS), at<uint16_t>(ws, pl.HsT), s));
+        RNN_TRY(launch_split_bf16(P->V, z.H, z.O, z.O, at<uint16_t>(ws, pl.VS), at<uint16_t>(ws, pl.VT), s));
+        const bool fused = z.ce && bf3_fuses_stats(N, z.O, z.H);
+        Bf3Args b{};
+        b.A = at<uint16_t>(ws, pl.HsS); b.B = at<uint16_t>(ws, pl.VT); b.C = Z;
+        b.M = N; b.N = z.O; b.K = z.H; b.lda = bf3_pad(z.H); b.ldb = bf3_pad(z.H); b.ldc = z.O;
+        b.bias_n = P->c; b.beta = 0; b.splitk_ws = at<float>(ws, pl.splitk3); b.prof_id = K_GEMM_LOGITS;
+        b.row_stats = fused ? at<float>(ws, pl.lstat) : nullptr;
+        RNN_TRY(launch_gemm_bf16x3(b, s));
+        float* rowloss = at<float>(ws, pl.rowloss);
+        if (fused) {
+            RNN_TRY(launch_ce_merge_stats(b.row_stats, gemm_stat_parts(z.O), Z, static_cast<const int32_t*>(targets),
+                                          at<float>(ws, pl.lse), rowloss, N, z.O, s));
+            return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
+        }
+        if (z.ce) {
+            RNN_TRY(launch_ce_row_stats(Z, static_cast<const int32_t*>(targets), at<float>(ws, pl.lse),
+                                        rowloss, N, z.O, s));
+            return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
+        }
+        int n_partial = 0;
+        RNN_TRY(launch_mse_partial(Z, static_cast<const float*>(targets), rowloss, N, z.O, &n_partial, s));
+        return launch_loss_reduce(rowloss, n_partial, (float)(1.0 / ((double)N * (double)z.O)), loss, s);
+    }
     GemmArgs g{};
     g.A = h_all + (size_t)z.B * z.H;  // rows of h_all[1:]
     g.B = P->V; g.C = Z;
@@ -318,9 +363,11 @@ hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT
 
 // Everything of backpropagation that follows d loss / d z (held in the logits buffer of the
 // workspace): dV, G, the reverse loop, dWh, db, dWx.  dc is the caller's.
+// bf3: dZ is also there as bf16 plane pairs (row-major and transposed) next to the planes of h and
+// V that run_loss left, and dV, G run on the bf16 matrix cores.
 hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const void* x, const float* h_all,
                                 const float* dh_last, const rnn_grads* Gr, float* dh0, void* ws,
-                                const Plan& pl, hipStream_t s) {
+                                const Plan& pl, bool bf3, hipStream_t s) {
     const Sizes z = sizes_of(d);
     const int N = (int)z.N, H = z.H, O = z.O;
     const int beta = (d->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
@@ -331,6 +378,19 @@ hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const vo
     float* Delta = at<float>(ws, pl.Delta);
     const float* Hs = h_all + (size_t)z.B * H;  // h_t rows
     const int chunks = colsum_chunks(N);
+    if (bf3) {
+        const int Np = bf3_pad(N), Op = bf3_pad(O);
+        Bf3Args b{};   // dV = Hs^T dZ, K = N
+        b.A = at<uint16_t>(ws, pl.HsT); b.B = at<uint16_t>(ws, pl.dZT); b.C = Gr->dV;
+        b.M = H; b.N = O; b.K = N; b.lda = Np; b.ldb = Np; b.ldc = O;
+        b.beta = beta; b.splitk_ws = at<float>(ws, pl.splitk3); b.prof_id = K_GEMM_DV;
+        RNN_TRY(launch_gemm_bf16x3(b, s));
+        Bf3Args c{};   // G = dZ V^T, K = O
+        c.A = at<uint16_t>(ws, pl.dZS); c.B = at<uint16_t>(ws, pl.VS); c.C = G;
+        c.M = N; c.N = H; c.K = O; c.lda = Op; c.ldb = Op; c.ldc = H;
+        c.beta = 0; c.splitk_ws = at<float>(ws, pl.splitk3); c.prof_id = K_GEMM_G;
+        RNN_TRY(launch_gemm_bf16x3(c, s));
+    } else {
     // dV = Hs^T dZ
     {
         GemmArgs g{};
@@ -348,6 +408,7 @@ hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const vo
         g.lda = O; g.ldb = O; g.ldc = H;
         g.a_t = false; g.b_t = true; g.beta = 0; g.splitk_ws = splitk; g.prof_id = K_GEMM_G;
         RNN_TRY(launch_gemm(g, s));
+    }
     }
     RNN_TRY(run_reverse_loop(d, P->Wh, nullptr, at<float>(ws, pl.WhT), G, h_all, dh_last, Delta, dh0, ws, pl, s));
     // dWh = Delta^T Hprev  (Hprev rows = h_all[0:T])
@@ -417,7 +478,9 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
                       z.ce ? nullptr : static_cast<const float*>(targets), part, N, O,
                       d->loss_kind, s));
     RNN_TRY(launch_colsum_finish(part, Gr->dc, chunks, O, beta, s));
-    return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, s);
+    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
+    if (bf3) RNN_TRY(launch_split_bf16(Z, N, O, O, at<uint16_t>(ws, pl.dZS), at<uint16_t>(ws, pl.dZT), s));
+    return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, bf3, s);
 }
 
 // Extra regions of the Gauss-Newton-vector product behind the ordinary plan.
@@ -519,7 +582,7 @@ hipError_t run_gauss_newton(const rnn_dims* d, const rnn_params* P, const rnn_pa
     // Gc = column sums of u, then the rest of backpropagation
     RNN_TRY(launch_colsum_partial(U, at<float>(ws, pl.part), N, O, s));
     RNN_TRY(launch_colsum_finish(at<float>(ws, pl.part), Out->dc, colsum_chunks(N), O, beta, s));
-    return run_backward_from_dz(d, P, x, h_all, nullptr, Out, nullptr, ws, pl, s);
+    return run_backward_from_dz(d, P, x, h_all, nullptr, Out, nullptr, ws, pl, false, s);
 }
 
 bool params_ok(const rnn_params* P) {
@@ -599,7 +662,7 @@ int rnn_gauss_newton_vec(const rnn_dims* dims, const rnn_params* params, const r
     if (!dims_valid(dims) || !params_ok(params) || !params_ok(gamma) || !x || !h_all || !out)
         return RNN_EINVAL;
     if (metric != RNN_GN_METRIC_LOSS && metric != RNN_GN_METRIC_IDENTITY) return RNN_EINVAL;
-    if (dims->flags & RNN_FLAG_BPTT_RECOMPUTE) return RNN_EINVAL;
+    if (dims->flags & (RNN_FLAG_BPTT_RECOMPUTE | RNN_FLAG_BF16X3_OUTPUT)) return RNN_EINVAL;
     if (!out->dWx || !out->dWh || !out->db || !out->dV || !out->dc) return RNN_EINVAL;
     if (misaligned4(x) || misaligned(h_all) || misaligned(Rz) || misaligned(out->dWx) ||
         misaligned(out->dWh) || misaligned(out->db) || misaligned(out->dV) || misaligned(out->dc))

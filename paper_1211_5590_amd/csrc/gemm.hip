@@ -374,6 +374,22 @@ size_t gemm_splitk_floats(int M, int N, int K) {
     return sp.splits > 1 ? (size_t)sp.splits * M * N : 0;
 }
 
+hipError_t launch_splitk_reduce(const float* part, float* C, const float* bias_n, int M, int N, int ldc,
+                                int splits, int beta, hipStream_t s) {
+    const size_t total = (size_t)M * N;
+    ProfileScope ps(K_SPLITK_REDUCE, s);
+    if (total % 4 == 0) {  // the partial buffer is 16-byte aligned workspace
+        const unsigned blocks = (unsigned)((total / 4 + 15) / 16);
+        hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3(blocks), dim3(256), 0, s, part, C, bias_n, M, N, ldc,
+                           splits, beta);
+    } else {
+        const unsigned blocks = (unsigned)((total + 15) / 16);
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(blocks), dim3(256), 0, s, part, C, bias_n, M, N, ldc,
+                           splits, beta);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     const SplitPlan sp = plan_split(g.M, g.N, g.K);
@@ -409,20 +425,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
 #undef RNN_GEMM_DISPATCH
     if (e != hipSuccess) return e;
 
-    if (sp.splits > 1) {
-        const size_t total = (size_t)g.M * g.N;
-        ProfileScope ps(K_SPLITK_REDUCE, s);
-        if (total % 4 == 0) {  // the partial buffer is 16-byte aligned workspace
-            const unsigned blocks = (unsigned)((total / 4 + 15) / 16);
-            hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3(blocks), dim3(256), 0, s, g.splitk_ws,
-                               g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
-        } else {
-            const unsigned blocks = (unsigned)((total + 15) / 16);
-            hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(blocks), dim3(256), 0, s, g.splitk_ws,
-                               g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta);
-        }
-        e = hipGetLastError();
-    }
+    if (sp.splits > 1) e = launch_splitk_reduce(g.splitk_ws, g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta, s);
     return e;
 }
 

@@ -31,6 +31,35 @@ int gemm_stat_parts(int N);
 bool gemm_fuses_stats(int M, int N, int K);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 
+// C[m,n] = (beta ? C : 0) + sum over splits of part[s][m][n] + bias_n[n], fixed order
+hipError_t launch_splitk_reduce(const float* part, float* C, const float* bias_n, int M, int N, int ldc,
+                                int splits, int beta, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------
+// bf16 hi/lo split products (gemm_bf16x3.hip): C[M,N] = A[M,K] B[N,K]^T + bias_n, float32 result,
+// operands as K-contiguous bf16 plane pairs (hi plane, then lo plane) with leading dimensions
+// bf3_pad(K), pads zero -- the form launch_split_bf16 writes.
+struct Bf3Args {
+    const uint16_t* A;    // [M][lda] hi, then [M][lda] lo
+    const uint16_t* B;    // [N][ldb] hi, then [N][ldb] lo
+    float* C;
+    int M, N, K;
+    int lda, ldb, ldc;
+    const float* bias_n;  // nullable
+    int beta;
+    float* splitk_ws;     // bf3_splitk_floats(M,N,K) floats
+    int prof_id;
+    float* row_stats;     // as in GemmArgs; written only when bf3_fuses_stats(M,N,K)
+};
+int bf3_pad(int k);
+size_t bf3_splitk_floats(int M, int N, int K);
+bool bf3_fuses_stats(int M, int N, int K);
+// float32 [R,C] (leading dimension ld) -> plane pairs: row-major [R][bf3_pad(C)] and/or transposed
+// [C][bf3_pad(R)] (either may be NULL)
+hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* rowmajor, uint16_t* transposed,
+                             hipStream_t s);
+hipError_t launch_gemm_bf16x3(const Bf3Args& g, hipStream_t s);
+
 // ---------------------------------------------------------------------------------------
 // Recurrence (forward and reverse-time loops)
 struct RecFwdArgs {

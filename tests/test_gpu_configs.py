@@ -71,24 +71,40 @@ def test_c2_stream_of_dependent_windows():
             compare(kept[w], ref, check_dh0=False)
 
 
-def test_c4_reduced_length_full_parity():
+OUTPUT_MODES = pytest.mark.parametrize("flags", [0, rnn.FLAG_BF16X3_OUTPUT], ids=["f32", "bf16x3"])
+_c4_cache = {}
+
+
+def c4_reference(key, make):
+    """The oracle's C4 results, computed once for both output-layer modes."""
+    if key not in _c4_cache:
+        _c4_cache[key] = make()
+    return _c4_cache[key]
+
+
+@OUTPUT_MODES
+def test_c4_reduced_length_full_parity(flags):
     case = ri.make_config("C4", seq_len=6)
     print("C4 (T=6) oracle ...", flush=True)
-    ref = oracle.fwd_bptt(case)
-    compare(run_gpu(case), ref)
+    ref = c4_reference("short", lambda: oracle.fwd_bptt(case))
+    compare(run_gpu(case, flags), ref)
 
 
-def test_c4_full_size_sampled():
+@OUTPUT_MODES
+def test_c4_full_size_sampled(flags):
     case = ri.make_config("C4")
     T, B, H, O = case["seq_len"], case["batch"], case["hidden"], case["out_dim"]
     N = T * B
     print("C4 GPU ...", flush=True)
-    got = run_gpu(case)
-    print("C4 oracle forward ...", flush=True)
-    h_ref = oracle.forward(case)
+    got = run_gpu(case, flags)
+
+    def reference():
+        print("C4 oracle forward ...", flush=True)
+        h = oracle.forward(case)
+        print("C4 oracle loss and row statistics (335 GFLOP in double) ...", flush=True)
+        return (h,) + tuple(oracle.loss(case, h, want_lse=True))
+    h_ref, L, lse = c4_reference("full", reference)
     assert np.max(np.abs(got["h_all"] - h_ref)) <= H_ATOL
-    print("C4 oracle loss and row statistics (335 GFLOP in double) ...", flush=True)
-    L, lse = oracle.loss(case, h_ref, want_lse=True)
     assert abs(got["loss"] - L) <= LOSS_RTOL * abs(L)
     # output-layer gradients on sampled columns, from the oracle's states and log-sum-exps
     Hs = h_ref[1:].reshape(N, H)
@@ -108,10 +124,11 @@ def test_c4_full_size_sampled():
         assert np.all(np.isfinite(got[k]))
 
 
-def test_c5_long_dense_sequence_full():
+@OUTPUT_MODES
+def test_c5_long_dense_sequence_full(flags):
     case = ri.make_config("C5")
     print("C5 GPU ...", flush=True)
-    got = run_gpu(case)
+    got = run_gpu(case, flags)
     print("C5 oracle (about 0.4 TFLOP in double) ...", flush=True)
-    ref = oracle.fwd_bptt(case)
+    ref = c4_reference("c5", lambda: oracle.fwd_bptt(case))
     compare(got, ref)
