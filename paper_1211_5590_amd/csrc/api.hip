@@ -229,10 +229,7 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         m.U = U; m.h0 = h0; m.hist = a.hist; m.h_last = h_last; m.ring = a.ring;
         return launch_rec_batch_mfma(m, false, s);
     }
-    if (v.stepwise) {
-        a.WhT = at<float>(ws, pl.WhT);
-        return run_rec_fwd_stepwise(a, s);
-    }
+    if (v.stepwise) return run_rec_fwd_stepwise(a, s);
     return launch_rec_fwd_reference(a, s);
 }
 
@@ -342,17 +339,18 @@ hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT
         m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
         return launch_rec_batch_mfma(m, true, s);
     }
-    if (v.stepwise) {
-        RecBwdArgs a{};
-        a.Wh = Wh; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
-        a.Delta = Delta; a.dh0 = dh0; a.splitk_ws = at<float>(ws, pl.splitk);
-        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
-        return run_rec_bwd_stepwise(a, s);
-    }
+    // the remaining families read the matrix transposed: one copy per call
     const float* WhT = WhT_or_null;
     if (!WhT) {
         RNN_TRY(launch_transpose(Wh, WhT_ws, H, H, s));
         WhT = WhT_ws;
+    }
+    if (v.stepwise) {
+        RecBwdArgs a{};
+        a.Wh = Wh; a.WhT = WhT; a.G = G; a.h_all = h_all; a.dh_last = dh_last;
+        a.Delta = Delta; a.dh0 = dh0; a.splitk_ws = at<float>(ws, pl.splitk);
+        a.H = H; a.T = z.T; a.B = z.B; a.act = d->act;
+        return run_rec_bwd_stepwise(a, s);
     }
     RecBwdArgs a{};
     a.Wh = Wh; a.WhT = WhT; a.G = G; a.h_all = h_all; a.dh_last = dh_last;

@@ -72,11 +72,10 @@ struct RecFwdArgs {
     float* hist;       // [T+1,B,H], or a 2-slot ring [2,B,H] when ring != 0
     float* h_last;     // nullable [B,H]
     int H, T, B, act, ring;
-    float* WhT;        // workspace for a transposed copy of Wh (stepwise path)
 };
 struct RecBwdArgs {
     const float* Wh;      // [H,H]
-    const float* WhT;     // [H,H] transposed copy (reference kernels)
+    const float* WhT;     // [H,H] transposed copy (reference and step-wise kernels)
     const float* G;       // [T,B,H] output-layer contribution to d loss / d h_t
     const float* h_all;   // [T+1,B,H]
     const float* dh_last; // nullable [B,H]

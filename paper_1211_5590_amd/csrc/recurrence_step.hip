@@ -9,15 +9,18 @@
 // work stays fused into the producing kernel and the host does nothing between steps but
 // enqueue.
 //
-// Tiling of a step: a workgroup of 4 wavefronts owns 16 batch rows x 16 output columns (for
-// the 64 x 1024 x 1024 step that is 256 workgroups, one per CU, each streaming its 64 KB slice
-// of Wh and 64 KB of state through LDS in K-chunks of 128, double buffered (few, large chunks: every
-// chunk costs one L2 round trip that the little arithmetic of a chunk cannot hide); the forward loop uses a
-// transposed copy of Wh made once per call so that both directions read the matrix as [k][n]
-// and neighbouring workgroups touch neighbouring bytes); a wavefront owns a quarter
-// of K as a v_mfma_f32_16x16x4_f32 accumulator pair; the halves meet in LDS.  Inside a chunk K is walked in
-// a permuted order (lane group g takes k in [32g, 32g+32)), so a lane's 32 A and 32 B operands
-// are 128 contiguous bytes of LDS each.
+// A step moves little (for the 64 x 1024 x 1024 step 64 KB of state and 64 KB of matrix per
+// workgroup) and computes less, so what it costs is memory round trips: the kernel is built to
+// pay ONE.  A workgroup of 16 wavefronts owns 16 batch rows x 16 output columns (256
+// workgroups for that step, one per CU); every wavefront takes a 64-wide slice of K and
+// requests its whole share of both operands at once, straight into the lane registers the
+// matrix instruction (v_mfma_f32_16x16x4_f32) reads them from: lane (r = lane % 16, g = lane / 16)
+// holds, as four float4, k = k0 + 16 s + 4 g + e of state row r and of matrix row r, so that the
+// four lane groups of one request cover 64 contiguous bytes of a row and both operands walk K in
+// the same permuted order.  No LDS staging, no barrier inside the product; the 16 partial tiles
+// meet in LDS once.  Both operands are K-contiguous ([n][k]): the forward product reads Wh as it
+// is stored, the reverse product a transposed copy made once per call; either way a workgroup's
+// slice of the matrix and its state rows are two contiguous 64 KB blocks.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -27,17 +30,11 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int SM = 16, SN = 16, SK = 128, SLD = SK + 4, NT = 256;
-constexpr int KG = SK / 4;                 // k per lane group inside a chunk
-constexpr int RT = SM / 16;                // 16-row tiles per workgroup
-constexpr int KSPL = 4 / RT;               // wavefronts sharing a row tile, each a slice of K
-constexpr int KW = KG / KSPL;              // k-steps per wavefront per chunk
-constexpr int NA4 = SM * SK / 4 / NT;      // float4 of the state chunk per thread (8)
-constexpr int NB4 = SN * SK / 4 / NT;      // float4 of the matrix chunk per thread (2)
+constexpr int SM = 16, SN = 16, SKC = 64, SWAVES = 16, NT = SWAVES * kWave;
 
 struct StepArgs {
     const float* A;      // [M,H] previous state (forward) or delta_{t+1} (reverse)
-    const float* Wm;     // [H(k),H(n)] matrix of the product: Wh^T (forward) or Wh (reverse)
+    const float* Wm;     // [H(n),H(k)] matrix of the product, K-contiguous: Wh (forward) or Wh^T (reverse)
     float* C;            // [M,H] new state / delta_t
     const float* e0;     // forward: input term rows [M,H], or Wx when ids != NULL; reverse: G_t
     const float* e1;     // forward with ids: bias b; reverse: h_t
@@ -45,127 +42,73 @@ struct StepArgs {
     int M, H;
 };
 
+template <bool VEC>
+__device__ __forceinline__ float4 load_k4(const float* __restrict__ row, int k, int klim) {
+    if (VEC && k + 3 < klim) return *reinterpret_cast<const float4*>(row + k);
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k + 0 < klim) t.x = row[k + 0];
+    if (k + 1 < klim) t.y = row[k + 1];
+    if (k + 2 < klim) t.z = row[k + 2];
+    if (k + 3 < klim) t.w = row[k + 3];
+    return t;
+}
+
 template <int ACT, bool BWD, bool VEC>
 __global__ __launch_bounds__(NT) void rec_step_kernel(StepArgs p) {
-    __shared__ __attribute__((aligned(16))) float As[2][SM][SLD];
-    __shared__ __attribute__((aligned(16))) float Bs[2][SN][SLD];
-    __shared__ float red[4][kWave][4];          // partial tiles of the kh > 0 wavefronts
+    __shared__ float red[SWAVES][4][kWave];     // partial tiles, [wavefront][register][lane]
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int g = lane / 16, nn = lane % 16;
-    const int rt = wave % RT, kh = wave / RT;  // row tile of 16, slice of each lane group's k range
     const int n0 = blockIdx.x * SN, m0 = blockIdx.y * SM;
     const int H = p.H, M = p.M;
-    const int nk = (H + SK - 1) / SK;
+    const int nchunks = (H + SKC - 1) / SKC;
 
-    float4 ra[NA4], rb[NB4];
-    auto load4 = [&](const float* base, int k, int klim) -> float4 {  // 4 floats along k
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (VEC && k + 3 < klim) return *reinterpret_cast<const float4*>(base + k);
-        if (k + 0 < klim) t.x = base[k + 0];
-        if (k + 1 < klim) t.y = base[k + 1];
-        if (k + 2 < klim) t.z = base[k + 2];
-        if (k + 3 < klim) t.w = base[k + 3];
-        return t;
-    };
-    auto fetch = [&](int kc) {
-        const int k0 = kc * SK;
-#pragma unroll
-        for (int i = 0; i < NA4; ++i) {
-            const int idx = tid + NT * i, r = idx / (SK / 4), kq = (idx % (SK / 4)) * 4;
-            ra[i] = (m0 + r < M) ? load4(p.A + (size_t)(m0 + r) * H, k0 + kq, H)
-                                 : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-        // Bs[n][k] = Wm[k0+k][n0+n]: 4 consecutive n of one k; neighbouring workgroups read
-        // neighbouring 64-byte pieces of the same matrix rows
-#pragma unroll
-        for (int i = 0; i < NB4; ++i) {
-            const int idx = tid + NT * i, k = idx / 4, nq = (idx % 4) * 4;
-            rb[i] = (k0 + k < H) ? load4(p.Wm + (size_t)(k0 + k) * H, n0 + nq, H)
-                                 : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto park = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NA4; ++i) {
-            const int idx = tid + NT * i, r = idx / (SK / 4), kq = (idx % (SK / 4)) * 4;
-            *reinterpret_cast<float4*>(&As[buf][r][kq]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NB4; ++i) {
-            const int idx = tid + NT * i, k = idx / 4, nq = (idx % 4) * 4;
-            Bs[buf][nq + 0][k] = rb[i].x;
-            Bs[buf][nq + 1][k] = rb[i].y;
-            Bs[buf][nq + 2][k] = rb[i].z;
-            Bs[buf][nq + 3][k] = rb[i].w;
-        }
-    };
-
-    // Epilogue operands do not depend on the product: request them before the K loop so their
-    // latency (two dependent loads for token input) is hidden behind it.
+    // Epilogue operands do not depend on the product: the four wavefronts that finish the tile
+    // request them first (two dependent loads for token input), behind the operand requests.
+    // thread (lane, i = wave) of those finishes row 4 g + i, column nn
     const int col = n0 + nn;
-    float x0[4], x1[4];
-    {
+    float x0 = 0.f, x1 = 0.f;
+    if (wave < 4) {
         const int cc = min(col, H - 1);
-        int rr[4], id[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) rr[i] = min(m0 + 16 * rt + 4 * g + i, M - 1);
+        const int rr = min(m0 + 4 * g + wave, M - 1);
         if (!BWD && p.ids) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) id[i] = p.ids[rr[i]];
-            const float tb = p.e1[cc];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { x0[i] = p.e0[(size_t)id[i] * H + cc] + tb; x1[i] = 0.f; }
+            x0 = p.e0[(size_t)p.ids[rr] * H + cc] + p.e1[cc];
         } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x0[i] = p.e0[(size_t)rr[i] * H + cc];
-                x1[i] = BWD ? p.e1[(size_t)rr[i] * H + cc] : 0.f;
-            }
+            x0 = p.e0[(size_t)rr * H + cc];
+            if (BWD) x1 = p.e1[(size_t)rr * H + cc];
         }
     }
 
+    const bool a_ok = m0 + nn < M, b_ok = col < H;
+    const float* arow = p.A + (size_t)min(m0 + nn, M - 1) * H;
+    const float* brow = p.Wm + (size_t)min(col, H - 1) * H;
     f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    fetch(0);
-    park(0);
-    __syncthreads();
-    for (int kc = 0; kc < nk; ++kc) {
-        const int cur = kc & 1;
-        if (kc + 1 < nk) fetch(kc + 1);
-        float a[KW], b[KW];
-        const float4* pa = reinterpret_cast<const float4*>(&As[cur][16 * rt + nn][KG * g + KW * kh]);
-        const float4* pb = reinterpret_cast<const float4*>(&Bs[cur][nn][KG * g + KW * kh]);
+    for (int kc = wave; kc < nchunks; kc += SWAVES) {
+        const int k0 = kc * SKC + 4 * g;
+        float4 a[4], b[4];
 #pragma unroll
-        for (int i = 0; i < KW / 4; ++i) {
-            const float4 va = pa[i], vb = pb[i];
-            a[4 * i] = va.x; a[4 * i + 1] = va.y; a[4 * i + 2] = va.z; a[4 * i + 3] = va.w;
-            b[4 * i] = vb.x; b[4 * i + 1] = vb.y; b[4 * i + 2] = vb.z; b[4 * i + 3] = vb.w;
+        for (int s = 0; s < 4; ++s) {
+            a[s] = a_ok ? load_k4<VEC>(arow, k0 + 16 * s, H) : make_float4(0.f, 0.f, 0.f, 0.f);
+            b[s] = b_ok ? load_k4<VEC>(brow, k0 + 16 * s, H) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int s = 0; s < KW; s += 2) {
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[s], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s + 1], b[s + 1], acc1, 0, 0, 0);
+        for (int s = 0; s < 4; ++s) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].x, b[s].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].y, b[s].y, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].z, b[s].z, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].w, b[s].w, acc1, 0, 0, 0);
         }
-        if (kc + 1 < nk) park(cur ^ 1);
-        __syncthreads();
     }
-
-    // the K slices of a row tile meet in LDS; the kh = 0 wavefront finishes the tile
-    if (kh > 0) {
+    // result layout of the 16x16 tile: lane -> column nn; register i -> row 4 g + i
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][lane][i] = acc0[i] + acc1[i];
-    }
+    for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc0[i] + acc1[i];
     __syncthreads();
-    if (kh > 0) return;
+    if (wave >= 4) return;
+    const int row = m0 + 4 * g + wave;
+    if (row >= M || col >= H) return;
+    float v = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = m0 + 16 * rt + 4 * g + i;
-        if (row >= M || col >= H) continue;
-        float v = acc0[i] + acc1[i];
-#pragma unroll
-        for (int w = 1; w < KSPL; ++w) v += red[rt + RT * w][lane][i];
-        const float out = BWD ? (v + x0[i]) * act_grad<ACT>(x1[i]) : activate<ACT>(v + x0[i]);
-        p.C[(size_t)row * H + col] = out;
-    }
+    for (int w = 0; w < SWAVES; ++w) v += red[w][wave][lane];
+    p.C[(size_t)row * H + col] = BWD ? (v + x0) * act_grad<ACT>(x1) : activate<ACT>(v + x0);
 }
 
 template <bool BWD>
@@ -213,12 +156,6 @@ int blocks_for(size_t n) {
 
 hipError_t run_rec_fwd_stepwise(const RecFwdArgs& a, hipStream_t s) {
     const size_t bh = (size_t)a.B * a.H;
-    // one transposed copy per call: both directions then stream the matrix in the same
-    // channel-friendly [k][n] order
-    {
-        hipError_t e = launch_transpose(a.Wh, a.WhT, a.H, a.H, s);
-        if (e != hipSuccess) return e;
-    }
     {
         ProfileScope ps(K_MISC, s);
         hipLaunchKernelGGL(copy_or_zero_kernel, dim3(blocks_for(bh)), dim3(256), 0, s, a.h0, a.hist, bh);
@@ -229,7 +166,7 @@ hipError_t run_rec_fwd_stepwise(const RecFwdArgs& a, hipStream_t s) {
         const size_t in_slot = a.ring ? (size_t)(t & 1) : (size_t)t;
         const size_t out_slot = a.ring ? (size_t)((t + 1) & 1) : (size_t)(t + 1);
         StepArgs p{};
-        p.A = a.hist + in_slot * bh; p.Wm = a.WhT; p.C = a.hist + out_slot * bh;
+        p.A = a.hist + in_slot * bh; p.Wm = a.Wh; p.C = a.hist + out_slot * bh;
         p.M = a.B; p.H = a.H;
         if (a.U) {
             p.e0 = a.U + (size_t)t * bh;
@@ -261,7 +198,7 @@ hipError_t run_rec_bwd_stepwise(const RecBwdArgs& a, hipStream_t s) {
     }
     for (int t = a.T - 2; t >= 0; --t) {
         StepArgs p{};
-        p.A = a.Delta + (size_t)(t + 1) * bh; p.Wm = a.Wh; p.C = a.Delta + (size_t)t * bh;
+        p.A = a.Delta + (size_t)(t + 1) * bh; p.Wm = a.WhT; p.C = a.Delta + (size_t)t * bh;
         p.M = a.B; p.H = a.H;
         p.e0 = a.G + (size_t)t * bh;
         p.e1 = a.h_all + (size_t)(t + 1) * bh;
