@@ -138,7 +138,8 @@ Plan make_plan(const rnn_dims* d) {
     // row statistics the logits product leaves per 64-column part (fused log-sum-exp)
     const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
     const bool fuses = bf3 ? bf3_fuses_stats((int)N, s.O, s.H) : gemm_fuses_stats((int)N, s.O, s.H);
-    p.lstat = take(s.ce && fuses ? N * (size_t)gemm_stat_parts(s.O) * 8 : 0);
+    const size_t parts = bf3 ? (size_t)bf3_stat_parts((int)N, s.O, s.H) : (size_t)gemm_stat_parts(s.O);
+    p.lstat = take(s.ce && fuses ? N * parts * 8 : 0);
     // bf16 hi/lo plane pairs of the output layer's operands (4 bytes per padded element)
     const size_t Np = (size_t)bf3_pad((int)N), Hp = (size_t)bf3_pad(s.H), Op = (size_t)bf3_pad(s.O);
     p.HsS = take(bf3 ? N * Hp * 4 : 0);
@@ -272,7 +273,7 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
         RNN_TRY(launch_gemm_bf16x3(b, s));
         float* rowloss = at<float>(ws, pl.rowloss);
         if (fused) {
-            RNN_TRY(launch_ce_merge_stats(b.row_stats, gemm_stat_parts(z.O), Z, static_cast<const int32_t*>(targets),
+            RNN_TRY(launch_ce_merge_stats(b.row_stats, bf3_stat_parts(N, z.O, z.H), Z, static_cast<const int32_t*>(targets),
                                           at<float>(ws, pl.lse), rowloss, N, z.O, s));
             return launch_loss_reduce(rowloss, N, 1.0f / (float)N, loss, s);
         }

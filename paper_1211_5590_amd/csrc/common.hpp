@@ -19,6 +19,13 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() also waits
+// for every outstanding global access (vmcnt(0)), which would expose the full memory latency of
+// requests that were issued on purpose several iterations ahead of their use.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));

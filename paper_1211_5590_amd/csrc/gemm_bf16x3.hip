@@ -4,20 +4,27 @@
 // once into two bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and a product a b is taken as
 // hi_a hi_b + hi_a lo_b + lo_a hi_b (three matrix instructions; the dropped lo_a lo_b term and
 // the rounding of lo are each below 2^-17 |a b|), so results stay within the float32 path's
-// tolerances at a fifth of its matrix time.
+// tolerances at a fraction of its matrix time.
 //
 // One kernel form serves all three products: C[M,N] = A[M,K] B[N,K]^T with both operands stored
-// K-contiguous as bf16 planes (hi plane, lo plane), which is the layout a matrix instruction
-// wants in its lanes (8 consecutive k of one row per lane).  The operands are brought into that
-// form by split_kernel, one pass that writes the row-major and/or the transposed planes of a
-// float32 matrix, zero-padded to multiples of 32 in K so that the product needs no K tail.
+// K-contiguous in bf16, which is the layout a matrix instruction wants in its lanes (8
+// consecutive k of one row per lane).  Storage of an operand ("split form"): row r holds, for
+// every slab of 32 k, the 32 hi values followed by the 32 lo values -- one 128-byte line per row
+// and slab, so that the product's requests are whole cache lines; K is zero-padded to a multiple
+// of 32 so that the product needs no K tail.  split_kernel brings a float32 matrix into that
+// form in one pass, as it is and/or transposed.
 //
-// Tiling of the product: 256 threads (4 wavefronts as 2x2) own a 128x128 tile, each wavefront
-// 64x64 as 2x2 blocks of 32x32; K advances in slabs of 32 through two LDS buffers (next slab
-// global -> registers while the current one feeds the matrix cores).  LDS rows are 64 bytes
-// (four 16-byte chunks) without padding; chunk c of row r sits at position c ^ ((r >> 2) & 3),
-// which makes both the 16-byte writes (4 lanes per row) and the fragment reads (32 rows, one
-// chunk) conflict-free.  64 KB of LDS per workgroup: two workgroups per compute unit.
+// Tiling of the product (measured on this chip: the matrix and LDS part of a 128x128 tile runs
+// at 70 % of the bf16 peak, but its operand requests, 32 KB per slab and workgroup, saturate
+// the 64 bytes per clock of the compute unit's vector memory path and halve that): large
+// products run 256x256 tiles (8 wavefronts as 2x4, each 128x64 as 4x2 blocks of 32x32; one
+// workgroup per compute unit, half the request bytes per matrix instruction), small ones
+// 128x128 tiles (4 wavefronts as 2x2, each 64x64; two workgroups per compute unit).  K advances
+// in slabs of 32 through two LDS buffers (next slab global -> registers while the current one
+// feeds the matrix cores; the barrier in the loop waits for LDS traffic only).  LDS rows are 64
+// bytes per plane (four 16-byte chunks) without padding; chunk c of row r sits at position
+// c ^ ((r >> 2) & 3), which makes both the 16-byte writes and the fragment reads (32 rows, one
+// chunk) conflict-free.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -33,10 +40,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TB = 128;        // tile edge (rows of A and rows of B per workgroup)
 constexpr int KS = 32;         // K per slab
-constexpr int NT = 256;
-constexpr int PLANE = TB * KS * 2;   // bytes of one operand plane of one slab in LDS (8 KB)
 
 // hi/lo split of 8 floats into two packed bf16x8 (round to nearest even both times)
 __device__ __forceinline__ void split8(const float (&x)[8], uint4& hi, uint4& lo) {
@@ -52,9 +56,12 @@ __device__ __forceinline__ void split8(const float (&x)[8], uint4& hi, uint4& lo
     lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
-// src float32 [R,C] (leading dimension ld) -> bf16 hi/lo planes, row-major [R][Cp] (rm, nullable)
-// and/or transposed [C][Rp] (tr, nullable); Cp, Rp = C, R rounded up to 32, pads written as 0.
-// A plane pair is hi followed by lo.  One 64x64 tile per workgroup, through LDS.
+// position (in bf16 elements) of k inside a split-form row: slab * 64 + (k % 32), lo at + 32
+__host__ __device__ inline size_t split_pos(int k) { return (size_t)(k / KS) * (2 * KS) + (size_t)(k % KS); }
+
+// src float32 [R,C] (leading dimension ld) -> split form, as it is [R][2 Cp] (rm, nullable) and/or
+// transposed [C][2 Rp] (tr, nullable); Cp, Rp = C, R rounded up to 32, pads written as 0.
+// One 64x64 tile per workgroup, through LDS.
 __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ src, int R, int C, int ld,
                                                     uint16_t* __restrict__ rm, uint16_t* __restrict__ tr,
                                                     int Cp, int Rp, int vec) {
@@ -83,7 +90,6 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ sr
     }
     __syncthreads();
     if (rm) {
-        uint16_t* lo_plane = rm + (size_t)R * Cp;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = tid / 8 + 32 * i, c8 = (tid % 8) * 8;
@@ -93,14 +99,13 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ sr
                 for (int j = 0; j < 8; ++j) x[j] = tile[row * TS + c8 + j];
                 uint4 hi, lo;
                 split8(x, hi, lo);
-                const size_t at = (size_t)(r0 + row) * Cp + c0 + c8;
-                *reinterpret_cast<uint4*>(rm + at) = hi;
-                *reinterpret_cast<uint4*>(lo_plane + at) = lo;
+                uint16_t* at = rm + (size_t)(r0 + row) * (2 * Cp) + split_pos(c0 + c8);
+                *reinterpret_cast<uint4*>(at) = hi;
+                *reinterpret_cast<uint4*>(at + KS) = lo;
             }
         }
     }
     if (tr) {
-        uint16_t* lo_plane = tr + (size_t)C * Rp;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int col = tid / 8 + 32 * i, r8 = (tid % 8) * 8;
@@ -110,22 +115,22 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ sr
                 for (int j = 0; j < 8; ++j) x[j] = tile[(r8 + j) * TS + col];
                 uint4 hi, lo;
                 split8(x, hi, lo);
-                const size_t at = (size_t)(c0 + col) * Rp + r0 + r8;
-                *reinterpret_cast<uint4*>(tr + at) = hi;
-                *reinterpret_cast<uint4*>(lo_plane + at) = lo;
+                uint16_t* at = tr + (size_t)(c0 + col) * (2 * Rp) + split_pos(r0 + r8);
+                *reinterpret_cast<uint4*>(at) = hi;
+                *reinterpret_cast<uint4*>(at + KS) = lo;
             }
         }
     }
 }
 
 struct Bf3Params {
-    const uint16_t* A;   // hi plane [M][lda], lo plane follows at A + M*lda
-    const uint16_t* B;   // hi plane [N][ldb], lo plane follows at B + N*ldb
+    const uint16_t* A;   // split form [M][2 lda]
+    const uint16_t* B;   // split form [N][2 ldb]
     float* C;            // final output, or split-K partials [splits][M][N]
     const float* bias_n;
     float* stats;        // as in the float32 product: (max, sum exp) per row and 64-column part
     int M, N;
-    int lda, ldb, ldc;   // lda, ldb in elements, multiples of 32
+    int lda, ldb, ldc;   // lda, ldb: padded K in elements (multiples of 32)
     int slabs;           // K slabs of 32 in total
     int slabs_per_split;
     int splits, beta;
@@ -151,128 +156,140 @@ __device__ __forceinline__ void tile_coords_bf3(int bid, int tiles_m, int tiles_
 // byte offset of chunk c (16 bytes = 8 bf16 of k) of row r inside one LDS plane
 __device__ __forceinline__ int lds_chunk(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
 
-template <bool STATS>
-__global__ __launch_bounds__(NT) void gemm_bf16x3_kernel(Bf3Params p) {
-    // [buffer][A hi, A lo, B hi, B lo]
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][4][PLANE];
+// WGM x WGN wavefronts, each TM x TN blocks of 32x32
+template <int WGM, int WGN, int TM, int TN, bool STATS>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16x3_kernel(Bf3Params p) {
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NTH = WGM * WGN * 64;
+    constexpr int APLANE = BM * 64, BPLANE = BN * 64;       // bytes of one plane of one slab
+    constexpr int STAGE = 2 * APLANE + 2 * BPLANE;           // A hi, A lo, B hi, B lo
+    constexpr int NA = BM * 8 / NTH, NB = BN * 8 / NTH;      // 16-byte chunks per thread and slab
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [2][STAGE]
 
     const int tid = threadIdx.x;
     const int lane = tid % 64, wave = tid / 64;
-    const int wm = wave / 2, wn = wave % 2;
+    const int wm = wave / WGN, wn = wave % WGN;
 
     int tile_m, tile_n;
     tile_coords_bf3(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * TB, n0 = tile_n * TB;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int sbeg = blockIdx.z * p.slabs_per_split;
     const int send = min(p.slabs, sbeg + p.slabs_per_split);
-    const int nk = send - sbeg;
+    const int nk = send - sbeg;     // every split has at least one slab
 
-    // global -> LDS staging: per plane 128 rows x 4 chunks = 512 chunks, two per thread
-    const int srow = tid / 4, schunk = tid % 4;
-    // rows past the end repeat the last one (their results are never stored)
-    const int ra0 = min(m0 + srow, p.M - 1), ra1 = min(m0 + srow + 64, p.M - 1);
-    const int rb0 = min(n0 + srow, p.N - 1), rb1 = min(n0 + srow + 64, p.N - 1);
-    const size_t kofs = (size_t)sbeg * KS + schunk * 8;
-    const uint16_t* ga00 = p.A + (size_t)ra0 * p.lda + kofs;        // [row half][hi, lo]
-    const uint16_t* ga10 = p.A + (size_t)ra1 * p.lda + kofs;
-    const uint16_t* ga01 = ga00 + (size_t)p.M * p.lda;
-    const uint16_t* ga11 = ga10 + (size_t)p.M * p.lda;
-    const uint16_t* gb00 = p.B + (size_t)rb0 * p.ldb + kofs;
-    const uint16_t* gb10 = p.B + (size_t)rb1 * p.ldb + kofs;
-    const uint16_t* gb01 = gb00 + (size_t)p.N * p.ldb;
-    const uint16_t* gb11 = gb10 + (size_t)p.N * p.ldb;
-    const int soff0 = lds_chunk(srow, schunk), soff1 = lds_chunk(srow + 64, schunk);
-
-    u32x4 st0, st1, st2, st3, st4, st5, st6, st7;
-#define BF3_FETCH(slab)                                                              \
-    do {                                                                             \
-        const size_t k_ = (size_t)(slab) * KS;                                       \
-        st0 = *reinterpret_cast<const u32x4*>(ga00 + k_);                          \
-        st1 = *reinterpret_cast<const u32x4*>(ga10 + k_);                          \
-        st2 = *reinterpret_cast<const u32x4*>(ga01 + k_);                          \
-        st3 = *reinterpret_cast<const u32x4*>(ga11 + k_);                          \
-        st4 = *reinterpret_cast<const u32x4*>(gb00 + k_);                          \
-        st5 = *reinterpret_cast<const u32x4*>(gb10 + k_);                          \
-        st6 = *reinterpret_cast<const u32x4*>(gb01 + k_);                          \
-        st7 = *reinterpret_cast<const u32x4*>(gb11 + k_);                          \
+    // global -> LDS staging: a row of a slab is 8 chunks (4 hi, 4 lo) = one 128-byte line; rows
+    // past the end repeat the last one (their results are never stored)
+    const uint16_t* ga[NA];
+    const uint16_t* gb[NB];
+    int sa_off[NA], sb_off[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int c = tid + NTH * i, row = c / 8, cc = c % 8;
+        ga[i] = p.A + (size_t)min(m0 + row, p.M - 1) * (2 * p.lda) + (size_t)sbeg * (2 * KS) + cc * 8;
+        sa_off[i] = (cc / 4) * APLANE + lds_chunk(row, cc % 4);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int c = tid + NTH * i, row = c / 8, cc = c % 8;
+        gb[i] = p.B + (size_t)min(n0 + row, p.N - 1) * (2 * p.ldb) + (size_t)sbeg * (2 * KS) + cc * 8;
+        sb_off[i] = 2 * APLANE + (cc / 4) * BPLANE + lds_chunk(row, cc % 4);
+    }
+    u32x4 ra[NA], rb[NB];
+#define BF3_FETCH(slab)                                                                         \
+    do {                                                                                        \
+        const size_t k_ = (size_t)(slab) * (2 * KS);                                            \
+        _Pragma("unroll") for (int i = 0; i < NA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + k_); \
+        _Pragma("unroll") for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + k_); \
     } while (0)
-#define BF3_PARK(buf)                                                                \
-    do {                                                                             \
-        *reinterpret_cast<u32x4*>(&lds[buf][0][soff0]) = st0;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][0][soff1]) = st1;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][1][soff0]) = st2;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][1][soff1]) = st3;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][2][soff0]) = st4;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][2][soff1]) = st5;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][3][soff0]) = st6;                      \
-        *reinterpret_cast<u32x4*>(&lds[buf][3][soff1]) = st7;                      \
+#define BF3_PARK(buf)                                                                           \
+    do {                                                                                        \
+        _Pragma("unroll") for (int i = 0; i < NA; ++i)                                          \
+            *reinterpret_cast<u32x4*>(lds + (buf) * STAGE + sa_off[i]) = ra[i];                 \
+        _Pragma("unroll") for (int i = 0; i < NB; ++i)                                          \
+            *reinterpret_cast<u32x4*>(lds + (buf) * STAGE + sb_off[i]) = rb[i];                 \
     } while (0)
 
-    f32x16 acc[2][2];
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (nk > 0) {
-        BF3_FETCH(sbeg * 0);
-        BF3_PARK(0);
-    }
+    BF3_FETCH(0);
+    BF3_PARK(0);
     __syncthreads();
 
     // fragment addresses: row = wave block + 32 i + lane % 32, chunk = 2 s + lane / 32
-    int foff_a[2][2], foff_b[2][2];   // [i or j][k step]
+    int foff_a[TM][2], foff_b[TN][2];   // [block][k step]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int s = 0; s < 2; ++s) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            foff_a[i][s] = lds_chunk(wm * 64 + 32 * i + lane % 32, 2 * s + lane / 32);
-            foff_b[i][s] = lds_chunk(wn * 64 + 32 * i + lane % 32, 2 * s + lane / 32);
-        }
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) BF3_FETCH(kt + 1);
+        for (int i = 0; i < TM; ++i) foff_a[i][s] = lds_chunk(wm * TM * 32 + 32 * i + lane % 32, 2 * s + lane / 32);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 ah[2], al[2], bh[2], bl[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                ah[i] = *reinterpret_cast<const bf16x8*>(&lds[cur][0][foff_a[i][s]]);
-                al[i] = *reinterpret_cast<const bf16x8*>(&lds[cur][1][foff_a[i][s]]);
-                bh[i] = *reinterpret_cast<const bf16x8*>(&lds[cur][2][foff_b[i][s]]);
-                bl[i] = *reinterpret_cast<const bf16x8*>(&lds[cur][3][foff_b[i][s]]);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
-                }
-        }
-        if (more) BF3_PARK(cur ^ 1);
-        __syncthreads();
+        for (int j = 0; j < TN; ++j)
+            foff_b[j][s] = 2 * APLANE + lds_chunk(wn * TN * 32 + 32 * j + lane % 32, 2 * s + lane / 32);
     }
+
+    // products of one slab out of LDS buffer `cur` (a literal, so that every offset is an immediate)
+#define BF3_COMPUTE(cur)                                                                              \
+    _Pragma("unroll") for (int s = 0; s < 2; ++s) {                                                   \
+        bf16x8 ah[TM], al[TM], bh[TN], bl[TN];                                                        \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                              \
+            ah[i] = *reinterpret_cast<const bf16x8*>(lds + (cur) * STAGE + foff_a[i][s]);             \
+            al[i] = *reinterpret_cast<const bf16x8*>(lds + (cur) * STAGE + APLANE + foff_a[i][s]);    \
+        }                                                                                             \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                              \
+            bh[j] = *reinterpret_cast<const bf16x8*>(lds + (cur) * STAGE + foff_b[j][s]);             \
+            bl[j] = *reinterpret_cast<const bf16x8*>(lds + (cur) * STAGE + BPLANE + foff_b[j][s]);    \
+        }                                                                                             \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0); \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0); \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0); \
+    }
+
+    // A double iteration computes slabs kt and kt + 1 out of LDS buffers 0 and 1.  Requests and
+    // parks are unconditional (past the end they repeat the last slab, which nobody reads).
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        BF3_FETCH(kt + 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the matrix work
+        BF3_COMPUTE(0)
+        __builtin_amdgcn_sched_barrier(0);
+        BF3_PARK(1);
+        lds_barrier();
+        BF3_FETCH(min(kt + 2, nk - 1));
+        __builtin_amdgcn_sched_barrier(0);
+        BF3_COMPUTE(1)
+        __builtin_amdgcn_sched_barrier(0);
+        BF3_PARK(0);
+        lds_barrier();
+    }
+    if (kt < nk) { BF3_COMPUTE(0) }   // odd count: the last slab sits in buffer 0
+#undef BF3_COMPUTE
+#undef BF3_FETCH
+#undef BF3_PARK
 
     // Accumulator layout of a 32x32 block: lane -> column lane%32; register e -> row
     // 8*(e/4) + 4*(lane/32) + e%4.
     float* Cout = p.C + (p.splits > 1 ? (size_t)blockIdx.z * p.M * p.ldc : 0);
     const bool final_out = p.splits == 1;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn * 64 + 32 * j + lane % 32;
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * TN * 32 + 32 * j + lane % 32;
             if (col >= p.N) continue;
             const float bias = (final_out && p.bias_n) ? p.bias_n[col] : 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * 64 + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+                const int row = m0 + wm * TM * 32 + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
                 if (row < p.M) {
                     float* dst = Cout + (size_t)row * p.ldc + col;
                     float v = acc[i][j][e] + bias;
@@ -283,50 +300,58 @@ __global__ __launch_bounds__(NT) void gemm_bf16x3_kernel(Bf3Params p) {
         }
 
     if (STATS && final_out) {
-        const int nparts = p.tiles_n * 2;
-        const int part = tile_n * 2 + wn;
-        int col[2];
-        float bias[2];
+        static_assert(TN == 2, "a part of the row statistics is 64 columns");
+        const int nparts = p.tiles_n * WGN;
+        const int part = tile_n * WGN + wn;
+        int col[TN];
+        float bias[TN];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            col[j] = n0 + wn * 64 + 32 * j + lane % 32;
+        for (int j = 0; j < TN; ++j) {
+            col[j] = n0 + wn * TN * 32 + 32 * j + lane % 32;
             bias[j] = (p.bias_n && col[j] < p.N) ? p.bias_n[col[j]] : 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                float v[2];
+                float v[TN];
                 float m = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < TN; ++j) {
                     v[j] = acc[i][j][e] + bias[j];
                     if (col[j] < p.N) m = fmaxf(m, v[j]);
                 }
                 m = max32(m);
                 float sum = 0.f;
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < TN; ++j)
                     if (col[j] < p.N) sum += __expf(v[j] - m);
                 sum = sum32(sum);
-                const int row = m0 + wm * 64 + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+                const int row = m0 + wm * TM * 32 + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
                 if (lane % 32 == 0 && row < p.M)
                     *reinterpret_cast<float2*>(p.stats + ((size_t)row * nparts + part) * 2) = make_float2(m, sum);
             }
     }
 }
 
-struct Bf3Split { int splits, slabs_per_split; };
+// Tile configuration and K cut of a product.
+struct Bf3Plan { bool big; int tile, slots, splits, slabs_per_split; };
 
-// Two workgroups per compute unit: 512 resident tiles.  A product whose tiles do not fill whole
-// rounds of them cuts K (deterministic partials, summed by the float32 path's reduce kernel).
-Bf3Split plan_bf3(int M, int N, int K) {
-    const int tiles = ((M + TB - 1) / TB) * ((N + TB - 1) / TB);
+// Large products: 256x256 tiles, one workgroup per compute unit (256 resident tiles); small ones:
+// 128x128 tiles, two per compute unit (512).  A product whose tiles do not fill whole rounds of
+// the resident workgroups cuts K (deterministic partials, summed by the float32 path's reduce
+// kernel).
+Bf3Plan plan_bf3(int M, int N, int K) {
+    Bf3Plan pl;
+    pl.big = M >= 512 && N >= 512;
+    pl.tile = pl.big ? 256 : 128;
+    pl.slots = pl.big ? 256 : 512;
+    const int tiles = ((M + pl.tile - 1) / pl.tile) * ((N + pl.tile - 1) / pl.tile);
     const int slabs = (K + KS - 1) / KS;
     int splits = 1;
     if (slabs >= 64) {
-        const double slots = 512.0, out_bytes = 4.0 * M * (double)N;
-        const double t_full = 6.0 * M * N * (double)K / 800e12;   // three products at a typical rate
+        const double slots = pl.slots, out_bytes = 4.0 * M * (double)N;
+        const double t_full = 6.0 * M * N * (double)K / 1000e12;   // three products at a typical rate
         double best = 1e30;
         const int cap = slabs / 32 < 16 ? slabs / 32 : 16;
         for (int sp = 1; sp <= cap; ++sp) {
@@ -335,21 +360,49 @@ Bf3Split plan_bf3(int M, int N, int K) {
             if (t < best * 0.97) { best = t; splits = sp; }
         }
     }
-    int per = (slabs + splits - 1) / splits;
-    splits = (slabs + per - 1) / per;
-    return {splits, per};
+    pl.slabs_per_split = (slabs + splits - 1) / splits;
+    pl.splits = (slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
+    return pl;
 }
+
+template <int WGM, int WGN, int TM, int TN>
+hipError_t launch_bf3(const Bf3Params& p, hipStream_t s) {
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t smem = 2 * (size_t)(2 * WGM * TM * 32 * 64 + 2 * WGN * TN * 32 * 64);
+    dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
+    static bool raised[2] = {false, false};   // per kernel form: allow more than 64 KB of dynamic LDS
+    if (!raised[p.stats ? 1 : 0]) {
+        hipError_t e = p.stats
+            ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16x3_kernel<WGM, WGN, TM, TN, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)
+            : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16x3_kernel<WGM, WGN, TM, TN, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        raised[p.stats ? 1 : 0] = true;
+    }
+    if (p.stats) hipLaunchKernelGGL((gemm_bf16x3_kernel<WGM, WGN, TM, TN, true>), grid, dim3(NTH), smem, s, p);
+    else hipLaunchKernelGGL((gemm_bf16x3_kernel<WGM, WGN, TM, TN, false>), grid, dim3(NTH), smem, s, p);
+    return hipGetLastError();
+}
+
+
 
 }  // namespace
 
 int bf3_pad(int k) { return (k + KS - 1) / KS * KS; }
 
 size_t bf3_splitk_floats(int M, int N, int K) {
-    const Bf3Split sp = plan_bf3(M, N, K);
-    return sp.splits > 1 ? (size_t)sp.splits * M * N : 0;
+    const Bf3Plan pl = plan_bf3(M, N, K);
+    return pl.splits > 1 ? (size_t)pl.splits * M * N : 0;
 }
 
 bool bf3_fuses_stats(int M, int N, int K) { return plan_bf3(M, N, K).splits == 1; }
+
+// 64-column parts per row the statistics of an M x N x K product come in
+int bf3_stat_parts(int M, int N, int K) {
+    const int tile = plan_bf3(M, N, K).tile;
+    return (N + tile - 1) / tile * (tile / 64);
+}
 
 hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* rowmajor, uint16_t* transposed,
                              hipStream_t s) {
@@ -367,27 +420,24 @@ hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* r
 hipError_t launch_gemm_bf16x3(const Bf3Args& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.lda % KS || g.ldb % KS || g.lda < g.K || g.ldb < g.K)
         return hipErrorInvalidValue;
-    const Bf3Split sp = plan_bf3(g.M, g.N, g.K);
-    if (sp.splits > 1 && !g.splitk_ws) return hipErrorInvalidValue;
+    const Bf3Plan pl = plan_bf3(g.M, g.N, g.K);
+    if (pl.splits > 1 && !g.splitk_ws) return hipErrorInvalidValue;
     Bf3Params p;
     p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
     p.M = g.M; p.N = g.N; p.lda = g.lda; p.ldb = g.ldb;
     p.slabs = (g.K + KS - 1) / KS;
-    p.slabs_per_split = sp.slabs_per_split; p.splits = sp.splits; p.beta = g.beta;
-    p.tiles_m = (g.M + TB - 1) / TB;
-    p.tiles_n = (g.N + TB - 1) / TB;
-    p.stats = sp.splits == 1 ? g.row_stats : nullptr;
-    if (sp.splits > 1) { p.C = g.splitk_ws; p.ldc = g.N; } else { p.C = g.C; p.ldc = g.ldc; }
-    dim3 grid(p.tiles_m * p.tiles_n, 1, sp.splits);
+    p.slabs_per_split = pl.slabs_per_split; p.splits = pl.splits; p.beta = g.beta;
+    p.tiles_m = (g.M + pl.tile - 1) / pl.tile;
+    p.tiles_n = (g.N + pl.tile - 1) / pl.tile;
+    p.stats = pl.splits == 1 ? g.row_stats : nullptr;
+    if (pl.splits > 1) { p.C = g.splitk_ws; p.ldc = g.N; } else { p.C = g.C; p.ldc = g.ldc; }
     {
         ProfileScope ps(g.prof_id, s);
-        if (p.stats) hipLaunchKernelGGL(gemm_bf16x3_kernel<true>, grid, dim3(NT), 0, s, p);
-        else hipLaunchKernelGGL(gemm_bf16x3_kernel<false>, grid, dim3(NT), 0, s, p);
-        hipError_t e = hipGetLastError();
+        const hipError_t e = pl.big ? launch_bf3<2, 4, 4, 2>(p, s) : launch_bf3<2, 2, 2, 2>(p, s);
         if (e != hipSuccess) return e;
     }
-    if (sp.splits > 1)
-        return launch_splitk_reduce(g.splitk_ws, g.C, g.bias_n, g.M, g.N, g.ldc, sp.splits, g.beta, s);
+    if (pl.splits > 1)
+        return launch_splitk_reduce(g.splitk_ws, g.C, g.bias_n, g.M, g.N, g.ldc, pl.splits, g.beta, s);
     return hipSuccess;
 }
 

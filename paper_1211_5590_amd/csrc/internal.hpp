@@ -37,11 +37,11 @@ hipError_t launch_splitk_reduce(const float* part, float* C, const float* bias_n
 
 // ---------------------------------------------------------------------------------------
 // bf16 hi/lo split products (gemm_bf16x3.hip): C[M,N] = A[M,K] B[N,K]^T + bias_n, float32 result,
-// operands as K-contiguous bf16 plane pairs (hi plane, then lo plane) with leading dimensions
-// bf3_pad(K), pads zero -- the form launch_split_bf16 writes.
+// operands K-contiguous in "split form" (per row and slab of 32 k: 32 hi values, then 32 lo values;
+// K padded with zeros to bf3_pad(K)) -- the form launch_split_bf16 writes; 4 bytes per padded element.
 struct Bf3Args {
-    const uint16_t* A;    // [M][lda] hi, then [M][lda] lo
-    const uint16_t* B;    // [N][ldb] hi, then [N][ldb] lo
+    const uint16_t* A;    // [M][2 lda]
+    const uint16_t* B;    // [N][2 ldb]
     float* C;
     int M, N, K;
     int lda, ldb, ldc;
@@ -49,13 +49,14 @@ struct Bf3Args {
     int beta;
     float* splitk_ws;     // bf3_splitk_floats(M,N,K) floats
     int prof_id;
-    float* row_stats;     // as in GemmArgs; written only when bf3_fuses_stats(M,N,K)
+    float* row_stats;     // [M][bf3_stat_parts(M,N,K)][2]; written only when bf3_fuses_stats(M,N,K)
 };
+int bf3_stat_parts(int M, int N, int K);
 int bf3_pad(int k);
 size_t bf3_splitk_floats(int M, int N, int K);
 bool bf3_fuses_stats(int M, int N, int K);
-// float32 [R,C] (leading dimension ld) -> plane pairs: row-major [R][bf3_pad(C)] and/or transposed
-// [C][bf3_pad(R)] (either may be NULL)
+// float32 [R,C] (leading dimension ld) -> split form, as it is [R][2 bf3_pad(C)] and/or transposed
+// [C][2 bf3_pad(R)] (either may be NULL)
 hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* rowmajor, uint16_t* transposed,
                              hipStream_t s);
 hipError_t launch_gemm_bf16x3(const Bf3Args& g, hipStream_t s);

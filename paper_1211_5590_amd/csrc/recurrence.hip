@@ -39,12 +39,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int NL = 20;         // independent global loads in flight per thread during setup
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global load and store, which would put a DRAM round trip on each step of the
-// time loop; the steps exchange the state vector through LDS, so LDS ordering is enough.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
+// The time loops use lds_barrier() (common.hpp): __syncthreads() also waits for every outstanding
+// global load and store, which would put a DRAM round trip on each step; the steps exchange the
+// state vector through LDS, so LDS ordering is enough.
 
 // i / d for 0 <= i < 2^24 and d > 0 without the integer-division expansion
 __device__ __forceinline__ int fast_div(int i, int d, float inv) {

@@ -85,10 +85,6 @@ __device__ long long g_trace[257 * 16];
 #define TS_FLUSH
 #endif
 
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 __device__ __forceinline__ float max64(float v) {
     v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
     v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
