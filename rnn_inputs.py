@@ -177,3 +177,46 @@ def make_direction(case: dict, seed: int, scale: float = 1.0) -> dict:
     rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED, seed]))
     return {k: (scale * rng.standard_normal(size=np.shape(case[k]))).astype(np.float32)
             for k in ("Wx", "Wh", "b", "V", "c")}
+
+
+# ---------------------------------------------------------------------------------------
+# Feed-forward classifier workloads (the paper's neural-network training benchmark: 10-class
+# classification of a 784-dimensional input with 0, 1 x 500 or 3 x 1000 hidden units, batches of
+# 1, 10 or 60).  Its data set is not available: inputs are uniform in [0,1) like pixel
+# intensities, labels uniform over the classes.
+MLP_CONFIGS = {
+    "MLP0": dict(in_dim=784, hidden=0, n_hidden=0, out_dim=10),
+    "MLP1": dict(in_dim=784, hidden=500, n_hidden=1, out_dim=10),
+    "MLP3": dict(in_dim=784, hidden=1000, n_hidden=3, out_dim=10),
+}
+
+
+def mlp_layer_shapes(in_dim, hidden, n_hidden, out_dim):
+    """[(fan_out, fan_in)] of the n_hidden + 1 layers, input side first."""
+    widths = [in_dim] + [hidden] * n_hidden + [out_dim]
+    return [(widths[l + 1], widths[l]) for l in range(n_hidden + 1)]
+
+
+def make_mlp_case(in_dim, hidden, n_hidden, out_dim, batch, n_batches=1, *, act=ACT_TANH, seed=BASE_SEED + 77,
+                  bias_std=0.0, wscale=1.0):
+    """One feed-forward problem: X float32 [n_batches*batch, in_dim] ~ U[0,1), y int32 labels,
+    W[l] float32 [fan_out, fan_in] ~ N(0, wscale/sqrt(fan_in)), b[l] float32 [fan_out]."""
+    s_x, s_y, s_w, s_b = np.random.SeedSequence(seed).spawn(4)
+    rows = batch * n_batches
+    out = dict(in_dim=in_dim, hidden=hidden, n_hidden=n_hidden, out_dim=out_dim, batch=batch,
+               n_batches=n_batches, act=act)
+    out["X"] = np.random.default_rng(s_x).random(size=(rows, in_dim), dtype=np.float32)
+    out["y"] = np.random.default_rng(s_y).integers(0, out_dim, size=rows).astype(np.int32)
+    shapes = mlp_layer_shapes(in_dim, hidden, n_hidden, out_dim)
+    out["W"] = [(np.random.default_rng(s).normal(0.0, wscale / np.sqrt(sh[1]), size=sh)).astype(np.float32)
+                for s, sh in zip(s_w.spawn(len(shapes)), shapes)]
+    rb = np.random.default_rng(s_b)
+    out["b"] = [(rb.normal(0.0, bias_std, size=sh[0]) if bias_std > 0 else np.zeros(sh[0])).astype(np.float32)
+                for sh in shapes]
+    return out
+
+
+def make_mlp_config(name: str, batch: int, n_batches: int = 1, **overrides):
+    cfg = dict(MLP_CONFIGS[name])
+    cfg.update(overrides)
+    return make_mlp_case(batch=batch, n_batches=n_batches, **cfg)
