@@ -252,6 +252,48 @@ int rnn_gauss_newton_vec(const rnn_dims *dims, const rnn_params *params, const r
                          const void *x, const float *h_all, int32_t metric, const rnn_grads *out,
                          float *Rz, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Second workload: training steps of a feed-forward classifier (the paper's neural-network
+ * training benchmark: 10-class classification of a 784-dimensional input by logistic regression,
+ * one hidden layer of 500 units, or three of 1000; stochastic gradient descent on single
+ * examples or mini-batches of 10 and 60; examples per second).  The paper prints no equations
+ * and names no hidden non-linearity; the textbook network is used:
+ *
+ *     a_0 = x;  a_l = act(W_l a_{l-1} + b_l), l = 1..n_hidden;  z = W_L a_{L-1} + b_L
+ *     loss = mean over the batch of ( logsumexp(z) - z[y] )                 (natural log)
+ *     after every batch:  W_l <- W_l - lr dloss/dW_l,   b_l <- b_l - lr dloss/db_l
+ *
+ * rnn_mlp_train runs n_batches consecutive batches in one call (the paper's function objects
+ * offer the same as a repeat count, "several iterations at once"): nothing returns to the host
+ * between batches, every batch is 3 n_hidden + 3 launches on hip_stream.
+ *   dims     host struct; act = RNN_ACT_* of the hidden layers; flags: RNN_FLAG_SYNC only;
+ *            n_hidden + 1 <= RNN_MLP_MAX_LAYERS; batch <= 1024 (else RNN_EUNSUPPORTED)
+ *   params   host struct of device pointers, layer l = 0..n_hidden (input side first):
+ *            W[l] float32 [fan_out_l, fan_in_l] row-major, b[l] float32 [fan_out_l]; 16-byte
+ *            aligned; UPDATED IN PLACE
+ *   X        device float32 [n_batches*batch, in_dim], 16-byte aligned;  y device int32
+ *            [n_batches*batch], values in [0, out_dim) (not checked)
+ *   losses   device float32 [n_batches]: mean loss of every batch, computed with the parameters
+ *            before that batch's update; NULL = not wanted
+ *   workspace  rnn_mlp_workspace_bytes() bytes, 16-byte aligned, needs no set-up
+ * Asynchronous like the other calls; sums run in a fixed order (run-to-run identical results).
+ */
+#define RNN_MLP_MAX_LAYERS 16
+typedef struct {
+    int32_t in_dim;     /* width of the input                                  */
+    int32_t hidden;     /* width of every hidden layer (ignored if n_hidden=0) */
+    int32_t n_hidden;   /* number of hidden layers, 0 = logistic regression    */
+    int32_t out_dim;    /* number of classes                                   */
+    int32_t batch;      /* examples per update                                 */
+    int32_t act;        /* RNN_ACT_* of the hidden layers                      */
+    uint32_t flags;     /* RNN_FLAG_SYNC                                       */
+} rnn_mlp_dims;
+typedef struct { float *W[RNN_MLP_MAX_LAYERS], *b[RNN_MLP_MAX_LAYERS]; } rnn_mlp_params; /* device pointers */
+int rnn_mlp_workspace_bytes(const rnn_mlp_dims *dims, size_t *bytes);
+int rnn_mlp_train(const rnn_mlp_dims *dims, const rnn_mlp_params *params, const float *X,
+                  const int32_t *y, int64_t n_batches, float lr, float *losses,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static description of an error code (host string, never NULL). */
 const char *rnn_strerror(int code);
 

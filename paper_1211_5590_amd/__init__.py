@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     rnn_train_stream, rnn_train_stream_status, rnn_train_stream_workspace_bytes,
     rnn_window, rnn_window_workspace_bytes, rnn_window_workspace_init,
     GN_METRIC_IDENTITY, GN_METRIC_LOSS, rnn_gauss_newton_vec, rnn_gauss_newton_workspace_bytes,
+    MlpDims, MlpParams, mlp_params, rnn_mlp_train, rnn_mlp_workspace_bytes,
 )

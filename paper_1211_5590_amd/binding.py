@@ -23,7 +23,9 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
            "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
-           "rnn_window", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec")
+           "rnn_window", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
+           "rnn_mlp_workspace_bytes", "rnn_mlp_train")
+MLP_MAX_LAYERS = 16
 GN_METRIC_LOSS, GN_METRIC_IDENTITY = 0, 1
 
 
@@ -50,6 +52,21 @@ class Params(ctypes.Structure):
 
 class Grads(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("dWx", "dWh", "db", "dV", "dc")]
+
+
+class MlpDims(ctypes.Structure):
+    _fields_ = [("in_dim", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_hidden", ctypes.c_int32),
+                ("out_dim", ctypes.c_int32), ("batch", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+    @classmethod
+    def of(cls, case: dict, flags: int = 0) -> "MlpDims":
+        return cls(case["in_dim"], case["hidden"], case["n_hidden"], case["out_dim"], case["batch"],
+                   case["act"], flags)
+
+
+class MlpParams(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p * MLP_MAX_LAYERS), ("b", ctypes.c_void_p * MLP_MAX_LAYERS)]
 
 
 _lib = None
@@ -104,6 +121,11 @@ def lib():
         L.rnn_gauss_newton_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
         L.rnn_gauss_newton_vec.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), ctypes.POINTER(Params),
                                            vp, vp, ctypes.c_int32, ctypes.POINTER(Grads), vp, vp, sz, vp]
+        L.rnn_mlp_workspace_bytes.argtypes = [ctypes.POINTER(MlpDims), ctypes.POINTER(sz)]
+        L.rnn_mlp_train.argtypes = [ctypes.POINTER(MlpDims), ctypes.POINTER(MlpParams), vp, vp, ctypes.c_int64,
+                                    ctypes.c_float, vp, vp, sz, vp]
+        for name in ("rnn_mlp_workspace_bytes", "rnn_mlp_train"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec"):
             getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_train_stream_workspace_bytes", "rnn_train_stream", "rnn_train_stream_status",
@@ -223,6 +245,30 @@ def rnn_gauss_newton_vec(dims, params, gamma, x, h_all, metric, out, Rz, workspa
     pr, ga, gr = _params(params), _params(gamma), _grads(out)
     rc = lib().rnn_gauss_newton_vec(ctypes.byref(dims), ctypes.byref(pr), ctypes.byref(ga), _p(x), _p(h_all),
                                     int(metric), ctypes.byref(gr), _p(Rz), wp, wb, _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+def rnn_mlp_workspace_bytes(dims: MlpDims) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().rnn_mlp_workspace_bytes(ctypes.byref(dims), ctypes.byref(n)))
+    return n.value
+
+
+def mlp_params(W, b) -> MlpParams:
+    """Pointer struct of the per-layer weight and bias tensors (lists, input side first)."""
+    p = MlpParams()
+    for l, (w, v) in enumerate(zip(W, b)):
+        p.W[l], p.b[l] = _p(w), _p(v)
+    return p
+
+
+def rnn_mlp_train(dims, W, b, X, y, n_batches, lr, losses, workspace, stream=None, check=True):
+    wp, wb = _ws(workspace)
+    pr = W if isinstance(W, MlpParams) else mlp_params(W, b)
+    rc = lib().rnn_mlp_train(ctypes.byref(dims), ctypes.byref(pr), _p(X), _p(y), int(n_batches), float(lr),
+                             _p(losses), wp, wb, _stream(stream))
     if check:
         _check(rc)
     return rc

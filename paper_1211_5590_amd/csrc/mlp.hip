@@ -1,0 +1,369 @@
+// Training step of a feed-forward classifier (the paper's neural-network training benchmark:
+// 10-class classification of a 784-dimensional input by logistic regression, one hidden layer
+// of 500 units or three of 1000, stochastic gradient descent on batches of 1, 10 or 60):
+//
+//     a_l = act(W_l a_{l-1} + b_l),  z = W_L a_{L-1} + b_L,  loss = mean(logsumexp(z) - z[y]),
+//     W_l <- W_l - lr dloss/dW_l,  b_l <- b_l - lr dloss/db_l      after every batch.
+//
+// At these sizes a step moves a few megabytes of weights and computes almost nothing, so what it
+// costs is launches and memory round trips.  A step is 3 L + 3 launches (L hidden layers), each
+// built like the batched recurrence's step kernel to pay one round trip: a workgroup owns a
+// 16 x 16 tile of the result, its 16 wavefronts split the contraction in slices of 64 and request
+// their whole share of both operands at once, straight into the lane registers
+// v_mfma_f32_16x16x4_f32 reads them from; the partial tiles meet in LDS once and the epilogue is
+// fused (bias + activation forward, activation derivative backward).  The update kernel forms
+// dW = dZ^T a in matrix-core tiles over the batch and applies it in place together with the
+// bias update, so gradients never exist in memory.  No atomics: results are run-to-run identical.
+#include "../../include/rnn.h"
+
+#include "common.hpp"
+#include "internal.hpp"
+#include "prof.hpp"
+
+#include <math.h>
+
+namespace rnn {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MW = 16, MNT = MW * kWave, MKC = 64;
+
+template <bool VEC>
+__device__ __forceinline__ float4 ld_k4(const float* __restrict__ row, int k, int klim) {
+    if (VEC && k + 3 < klim) return *reinterpret_cast<const float4*>(row + k);
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k + 0 < klim) t.x = row[k + 0];
+    if (k + 1 < klim) t.y = row[k + 1];
+    if (k + 2 < klim) t.z = row[k + 2];
+    if (k + 3 < klim) t.w = row[k + 3];
+    return t;
+}
+
+template <int ACT>
+__device__ __forceinline__ float apply_act(float a) {
+    return ACT == 0 ? sigmoidf_fast(a) : (ACT == 1 ? tanhf_fast(a) : a);
+}
+
+// C[M,N] = act(A[M,K] W[N,K]^T + bias[N]);  ACT 0 sigmoid, 1 tanh, 2 none.
+// grid (ceil(N/16), ceil(M/16)), 1024 threads.  Lane (r = lane % 16, g = lane / 16) of a wavefront
+// holds k = k0 + 16 s + 4 g + e of row r of A and of row r of W: the same permuted walk of K for both.
+template <int ACT, bool VEC>
+__global__ __launch_bounds__(MNT) void mlp_fwd_kernel(const float* __restrict__ A, const float* __restrict__ W,
+                                                      const float* __restrict__ bias, float* __restrict__ C,
+                                                      int M, int N, int K) {
+    __shared__ float red[MW][4][kWave];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int g = lane / 16, nn = lane % 16;
+    const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16;
+    const int col = n0 + nn;
+    const float bv = (wave < 4 && col < N) ? bias[col] : 0.f;   // requested before the product
+    const bool a_ok = m0 + nn < M, b_ok = col < N;
+    const float* arow = A + (size_t)min(m0 + nn, M - 1) * K;
+    const float* brow = W + (size_t)min(col, N - 1) * K;
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const int nchunks = (K + MKC - 1) / MKC;
+    for (int kc = wave; kc < nchunks; kc += MW) {
+        const int k0 = kc * MKC + 4 * g;
+        float4 a[4], b[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            a[s] = a_ok ? ld_k4<VEC>(arow, k0 + 16 * s, K) : make_float4(0.f, 0.f, 0.f, 0.f);
+            b[s] = b_ok ? ld_k4<VEC>(brow, k0 + 16 * s, K) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].x, b[s].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].y, b[s].y, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].z, b[s].z, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s].w, b[s].w, acc1, 0, 0, 0);
+        }
+    }
+    // result layout of the 16x16 tile: lane -> column nn; register i -> row 4 g + i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc0[i] + acc1[i];
+    __syncthreads();
+    if (wave >= 4) return;
+    const int row = m0 + 4 * g + wave;
+    if (row >= M || col >= N) return;
+    float v = bv;
+#pragma unroll
+    for (int w = 0; w < MW; ++w) v += red[w][wave][lane];
+    C[(size_t)row * N + col] = apply_act<ACT>(v);
+}
+
+// dZprev[M,Kin] = (dZ[M,Nout] W[Nout,Kin]) * act'(Aprev[M,Kin]): the contraction runs over the rows
+// of W, so W is the n-contiguous operand (one value per request, 16 lanes = 64 contiguous bytes).
+// grid (ceil(Kin/16), ceil(M/16)), 1024 threads.
+template <int ACT>
+__global__ __launch_bounds__(MNT) void mlp_bwd_data_kernel(const float* __restrict__ dZ, const float* __restrict__ W,
+                                                           const float* __restrict__ Aprev, float* __restrict__ dZprev,
+                                                           int M, int Nout, int Kin) {
+    __shared__ float red[MW][4][kWave];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int g = lane / 16, nn = lane % 16;
+    const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16;
+    const int col = n0 + nn;
+    float hv = 0.f;
+    if (wave < 4 && col < Kin && m0 + 4 * g + wave < M) hv = Aprev[(size_t)(m0 + 4 * g + wave) * Kin + col];
+    const bool a_ok = m0 + nn < M, b_ok = col < Kin;
+    const float* arow = dZ + (size_t)min(m0 + nn, M - 1) * Nout;
+    const float* bcol = W + min(col, Kin - 1);
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const int nchunks = (Nout + MKC - 1) / MKC;
+    for (int kc = wave; kc < nchunks; kc += MW) {
+        const int k0 = kc * MKC + 4 * g;
+        float a[16], b[16];
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = k0 + 16 * s + e;
+                const bool k_ok = k < Nout;
+                a[4 * s + e] = (a_ok && k_ok) ? arow[k] : 0.f;
+                b[4 * s + e] = (b_ok && k_ok) ? bcol[(size_t)k * Kin] : 0.f;
+            }
+#pragma unroll
+        for (int q = 0; q < 16; q += 2) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], b[q], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q + 1], b[q + 1], acc1, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc0[i] + acc1[i];
+    __syncthreads();
+    if (wave >= 4) return;
+    const int row = m0 + 4 * g + wave;
+    if (row >= M || col >= Kin) return;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < MW; ++w) v += red[w][wave][lane];
+    dZprev[(size_t)row * Kin + col] = v * (ACT == 0 ? act_grad<0>(hv) : act_grad<1>(hv));
+}
+
+// W[n,k] -= lr sum_m dZ[m,n] Aprev[m,k];  b[n] -= lr sum_m dZ[m,n].
+// A wavefront owns 16 rows of W by 64 columns (four 16x16 tiles sharing the dZ operand) and walks
+// the batch four rows at a time; grid (ceil(Kin/256), ceil(Nout/16)), 256 threads.
+__global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict__ dZ, const float* __restrict__ Aprev,
+                                                         float* __restrict__ W, float* __restrict__ b, int M,
+                                                         int Nout, int Kin, float lr) {
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int q = lane / 16, r = lane % 16;
+    const int n0 = blockIdx.y * 16;
+    const int k0 = (blockIdx.x * 4 + wave) * 64;
+    if (blockIdx.x == 0 && wave == 0 && lane < 16 && n0 + lane < Nout) {
+        float s = 0.f;
+        for (int m = 0; m < M; ++m) s += dZ[(size_t)m * Nout + n0 + lane];
+        b[n0 + lane] -= lr * s;
+    }
+    if (k0 >= Kin) return;
+    const bool n_ok = n0 + r < Nout;
+    const int ncol = min(n0 + r, Nout - 1);
+    f32x4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int mb = 0; mb < M; mb += 16) {
+        float a[4], x[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int m = mb + 4 * u + q;
+            const bool m_ok = m < M;
+            const int mm = min(m, M - 1);
+            a[u] = (m_ok && n_ok) ? dZ[(size_t)mm * Nout + ncol] : 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int k = k0 + 16 * t + r;
+                x[u][t] = (m_ok && k < Kin) ? Aprev[(size_t)mm * Kin + k] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], x[u][t], acc[t], 0, 0, 0);
+    }
+    // tile layout: lane -> column r (k index); register i -> row 4 q + i (n index)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int k = k0 + 16 * t + r;
+        if (k >= Kin) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = n0 + 4 * q + i;
+            if (n < Nout) W[(size_t)n * Kin + k] -= lr * acc[t][i];
+        }
+    }
+}
+
+// One workgroup: per row log-sum-exp, the row's loss, dZ = (softmax - onehot) / M in place over
+// the logits, and the batch's mean loss (rows summed in order).  M <= 1024.
+__global__ __launch_bounds__(256) void mlp_ce_kernel(float* __restrict__ Z, const int32_t* __restrict__ y,
+                                                     float* __restrict__ loss, int M, int O) {
+    __shared__ float rowloss[1024];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const float inv = 1.0f / (float)M;
+    for (int row = wave; row < M; row += 4) {
+        float* z = Z + (size_t)row * O;
+        float m = -INFINITY;
+        for (int k = lane; k < O; k += kWave) m = fmaxf(m, z[k]);
+        m = wave_max(m);
+        float s = 0.f;
+        for (int k = lane; k < O; k += kWave) s += __expf(z[k] - m);
+        s = wave_sum(s);
+        const float lse = m + logf(s);
+        const int yy = y[row];
+        if (lane == 0) rowloss[row] = lse - z[yy];
+        for (int k = lane; k < O; k += kWave) {
+            float d = __expf(z[k] - lse);
+            if (k == yy) d -= 1.f;
+            z[k] = d * inv;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float s = 0.f;
+        for (int r = 0; r < M; ++r) s += rowloss[r];
+        *loss = s * inv;
+    }
+}
+
+struct Widths { int w[RNN_MLP_MAX_LAYERS + 2]; int layers; };
+
+bool mlp_dims_ok(const rnn_mlp_dims* d) {
+    if (!d) return false;
+    if (d->in_dim <= 0 || d->out_dim <= 0 || d->batch <= 0 || d->n_hidden < 0) return false;
+    if (d->n_hidden + 1 > RNN_MLP_MAX_LAYERS) return false;
+    if (d->n_hidden > 0 && d->hidden <= 0) return false;
+    if (d->act != RNN_ACT_SIGMOID && d->act != RNN_ACT_TANH) return false;
+    if (d->flags & ~RNN_FLAG_SYNC) return false;
+    if (d->in_dim > (1 << 20) || d->hidden > (1 << 20) || d->out_dim > (1 << 20)) return false;
+    return true;
+}
+
+Widths widths_of(const rnn_mlp_dims* d) {
+    Widths w;
+    w.layers = d->n_hidden + 1;
+    w.w[0] = d->in_dim;
+    for (int l = 1; l <= d->n_hidden; ++l) w.w[l] = d->hidden;
+    w.w[w.layers] = d->out_dim;
+    return w;
+}
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+// workspace: activations of the hidden layers, logits / dZ of the output layer, two dZ buffers of
+// the hidden width
+struct MlpPlan { size_t act[RNN_MLP_MAX_LAYERS + 1], Z, d0, d1, total; };
+
+MlpPlan mlp_plan(const rnn_mlp_dims* d) {
+    const Widths w = widths_of(d);
+    MlpPlan p{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
+    for (int l = 1; l < w.layers; ++l) p.act[l] = take((size_t)d->batch * w.w[l] * 4);
+    p.Z = take((size_t)d->batch * d->out_dim * 4);
+    p.d0 = take((size_t)d->batch * (d->n_hidden ? d->hidden : 1) * 4);
+    p.d1 = take((size_t)d->batch * (d->n_hidden ? d->hidden : 1) * 4);
+    p.total = off;
+    return p;
+}
+
+bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hipError_t launch_fwd(int act, const float* A, const float* W, const float* b, float* C, int M, int N, int K,
+                      hipStream_t s) {
+    dim3 grid((N + 15) / 16, (M + 15) / 16);
+    const bool vec = K % 4 == 0 && al16(A) && al16(W);
+    ProfileScope ps(K_MLP_FWD, s);
+#define RNN_MLP_FWD(ACT)                                                                              \
+    do {                                                                                              \
+        if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<ACT, true>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K);  \
+        else hipLaunchKernelGGL((mlp_fwd_kernel<ACT, false>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K);     \
+    } while (0)
+    if (act == 0) RNN_MLP_FWD(0); else if (act == 1) RNN_MLP_FWD(1); else RNN_MLP_FWD(2);
+#undef RNN_MLP_FWD
+    return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace rnn
+
+extern "C" {
+
+int rnn_mlp_workspace_bytes(const rnn_mlp_dims* dims, size_t* bytes) {
+    if (!rnn::mlp_dims_ok(dims) || !bytes) return RNN_EINVAL;
+    *bytes = rnn::mlp_plan(dims).total;
+    return RNN_OK;
+}
+
+int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const float* X, const int32_t* y,
+                  int64_t n_batches, float lr, float* losses, void* workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+    using namespace rnn;
+    if (!mlp_dims_ok(dims) || !params || !X || !y || n_batches < 0) return RNN_EINVAL;
+    if (dims->batch > 1024) return RNN_EUNSUPPORTED;
+    const Widths w = widths_of(dims);
+    for (int l = 0; l < w.layers; ++l)
+        if (!params->W[l] || !params->b[l] || !al16(params->W[l]) || !al16(params->b[l])) return RNN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) || (reinterpret_cast<uintptr_t>(y) & 3u) ||
+        (reinterpret_cast<uintptr_t>(losses) & 3u))
+        return RNN_EINVAL;
+    const MlpPlan pl = mlp_plan(dims);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
+        return RNN_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    const int B = dims->batch, L = w.layers;
+    float* Z = reinterpret_cast<float*>(ws + pl.Z);
+    float* dbuf[2] = {reinterpret_cast<float*>(ws + pl.d0), reinterpret_cast<float*>(ws + pl.d1)};
+    float* scratch_loss = dbuf[0];   // when the caller wants no losses (free until backpropagation starts)
+    for (int64_t i = 0; i < n_batches; ++i) {
+        const float* a_prev = X + (size_t)i * B * dims->in_dim;
+        // forward
+        for (int l = 0; l < L; ++l) {
+            float* out = l + 1 < L ? reinterpret_cast<float*>(ws + pl.act[l + 1]) : Z;
+            if (launch_fwd(l + 1 < L ? dims->act : 2, a_prev, params->W[l], params->b[l], out, B, w.w[l + 1],
+                           w.w[l], s) != hipSuccess)
+                return RNN_EHIP;
+            a_prev = out;
+        }
+        {
+            ProfileScope ps(K_MLP_CE, s);
+            hipLaunchKernelGGL(mlp_ce_kernel, dim3(1), dim3(256), 0, s, Z, y + (size_t)i * B,
+                               losses ? losses + i : scratch_loss, B, dims->out_dim);
+            if (hipGetLastError() != hipSuccess) return RNN_EHIP;
+        }
+        // backward: layer l needs dZ_l; it first sends dZ_{l-1} down (with the weights before their
+        // update), then updates W_l and b_l in place
+        const float* dz = Z;
+        for (int l = L - 1; l >= 0; --l) {
+            const float* a_in = l > 0 ? reinterpret_cast<const float*>(ws + pl.act[l])
+                                      : X + (size_t)i * B * dims->in_dim;
+            float* dz_prev = dbuf[l & 1];
+            if (l > 0) {
+                dim3 grid((w.w[l] + 15) / 16, (B + 15) / 16);
+                ProfileScope ps(K_MLP_BWD, s);
+                if (dims->act == 0)
+                    hipLaunchKernelGGL(mlp_bwd_data_kernel<0>, grid, dim3(MNT), 0, s, dz, params->W[l], a_in,
+                                       dz_prev, B, w.w[l + 1], w.w[l]);
+                else
+                    hipLaunchKernelGGL(mlp_bwd_data_kernel<1>, grid, dim3(MNT), 0, s, dz, params->W[l], a_in,
+                                       dz_prev, B, w.w[l + 1], w.w[l]);
+                if (hipGetLastError() != hipSuccess) return RNN_EHIP;
+            }
+            {
+                dim3 grid((w.w[l] + 255) / 256, (w.w[l + 1] + 15) / 16);
+                ProfileScope ps(K_MLP_UPDATE, s);
+                hipLaunchKernelGGL(mlp_update_kernel, grid, dim3(256), 0, s, dz, a_in, params->W[l], params->b[l],
+                                   B, w.w[l + 1], w.w[l], lr);
+                if (hipGetLastError() != hipSuccess) return RNN_EHIP;
+            }
+            dz = dz_prev;
+        }
+    }
+    if (dims->flags & RNN_FLAG_SYNC)
+        if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
+    return RNN_OK;
+}
+
+}  // extern "C"

@@ -28,7 +28,8 @@ const char* const kNames[K_COUNT] = {
     "splitk_reduce", "transpose",
     "rec_fwd", "rec_bwd", "ce_row_stats", "mse_row_loss", "loss_reduce", "dz",
     "colsum_partial", "colsum_finish", "dwx_tokens", "check_tokens",
-    "skinny_logits", "skinny_back", "skinny_reverse", "misc", "train_stream", "window", "gn_metric", "split_bf16"};
+    "skinny_logits", "skinny_back", "skinny_reverse", "misc", "train_stream", "window", "gn_metric", "split_bf16",
+    "mlp_fwd", "mlp_ce", "mlp_bwd_data", "mlp_update"};
 }  // namespace
 
 void profile_before(int, hipStream_t s) {

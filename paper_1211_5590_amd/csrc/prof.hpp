@@ -13,6 +13,7 @@ enum KernelId : int {
     K_REC_FWD, K_REC_BWD, K_CE_ROW_STATS, K_MSE_ROW_LOSS, K_LOSS_REDUCE, K_DZ,
     K_COLSUM_PARTIAL, K_COLSUM_FINISH, K_DWX_TOKENS, K_CHECK_TOKENS,
     K_SKINNY_LOGITS, K_SKINNY_BACK, K_SKINNY_REVERSE, K_MISC, K_TRAIN_STREAM, K_WINDOW, K_GN_METRIC, K_SPLIT_BF16,
+    K_MLP_FWD, K_MLP_CE, K_MLP_BWD, K_MLP_UPDATE,
     K_COUNT
 };
 

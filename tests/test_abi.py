@@ -133,3 +133,30 @@ def test_gauss_newton_rejects_bad_arguments_without_a_gpu():
     assert call(nbytes=rnn.rnn_workspace_bytes(d)) == -2
     with pytest.raises(rnn.RnnError):
         rnn.rnn_gauss_newton_workspace_bytes(good_dims(act=7))
+
+
+def test_mlp_rejects_bad_arguments_without_a_gpu():
+    d = rnn.MlpDims(784, 500, 1, 10, 60, 1, 0)
+    need = rnn.rnn_mlp_workspace_bytes(d)
+    assert need > 0
+    fake = 0x1000
+    L = rnn.lib()
+    P = rnn.MlpParams()
+    for l in range(2):
+        P.W[l], P.b[l] = fake, fake
+
+    def call(dims=d, params=P, X=fake, y=fake, n=1, ws=fake, nbytes=need):
+        return L.rnn_mlp_train(ctypes.byref(dims), ctypes.byref(params), X, y, n, 0.1, None, ws, nbytes, None)
+    assert call(X=None) == -1
+    assert call(y=None) == -1
+    assert call(n=-1) == -1
+    assert call(X=fake + 4) == -1
+    missing = rnn.MlpParams()
+    missing.W[0], missing.b[0] = fake, fake
+    assert call(params=missing) == -1
+    assert call(dims=rnn.MlpDims(784, 0, 1, 10, 60, 1, 0)) == -1      # hidden layers need a width
+    assert call(dims=rnn.MlpDims(784, 500, 16, 10, 60, 1, 0)) == -1    # too many layers
+    assert call(dims=rnn.MlpDims(784, 500, 1, 10, 60, 1, 1)) == -1     # flag the call does not take
+    assert call(dims=rnn.MlpDims(784, 500, 1, 10, 2000, 1, 0)) == -3   # batch beyond what the kernels serve
+    assert call(ws=None) == -2
+    assert call(nbytes=need - 1) == -2
