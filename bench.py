@@ -43,6 +43,8 @@ def parse():
                     help="time rnn_forward -> rnn_loss -> rnn_bptt even where rnn_window serves the shape")
     ap.add_argument("--no-train-stream", action="store_true",
                     help="skip the single-launch SGD driver leg of the headline workload")
+    ap.add_argument("--no-mlp", action="store_true",
+                    help="skip the feed-forward classifier workloads (the paper's second benchmark)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
     ap.add_argument("--bf16x3", action="store_true",
@@ -408,6 +410,58 @@ def train_stream_leg(windows, reps=3, lr=0.1):
     }
 
 
+def mlp_leg(n_batches=400, lr=0.01):
+    """The paper's neural-network training benchmark shapes (784 inputs, 10 classes; logistic
+    regression, 1 x 500 and 3 x 1000 hidden units; batches of 1, 10, 60) through rnn_mlp_train:
+    examples per second of `n_batches` consecutive SGD steps in one call, HIP-event timed on the
+    call's stream, plus the per-kernel times of one configuration."""
+    import numpy as np
+    import torch
+    import paper_1211_5590_amd as rnn
+    import rnn_inputs as ri
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    out = {}
+    for name in ("MLP0", "MLP1", "MLP3"):
+        for batch in (1, 10, 60):
+            case = ri.make_mlp_config(name, batch, n_batches=n_batches)
+            dims = rnn.MlpDims.of(case)
+            W, b = [dev(w) for w in case["W"]], [dev(v) for v in case["b"]]
+            X, y = dev(case["X"]), dev(case["y"])
+            losses = torch.zeros(n_batches, device="cuda")
+            ws = torch.empty(rnn.rnn_mlp_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
+            pr = rnn.mlp_params(W, b)
+            rnn.rnn_mlp_train(dims, pr, None, X, y, 20, lr, losses, ws)          # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            rnn.rnn_mlp_train(dims, pr, None, X, y, n_batches, lr, losses, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            n_params = sum(w.numel() + v.numel() for w, v in zip(W, b))
+            entry = dict(examples_per_s=n_batches * batch / wall, us_per_batch=1e6 * wall / n_batches,
+                         gpu_event_us_per_batch=1e3 * e0.elapsed_time(e1) / n_batches,
+                         launches_per_batch=3 * case["n_hidden"] + 3, parameters=n_params,
+                         loss_first=float(losses[0]), loss_last=float(losses[-1]))
+            if name == "MLP3" and batch == 60:
+                rnn.rnn_profile_begin(1 << 16)
+                rnn.rnn_mlp_train(dims, pr, None, X, y, 50, lr, losses, ws)
+                prof = rnn.rnn_profile_end()
+                entry["kernels"] = {k: dict(launches=c, avg_us_raw=round(1e3 * ms / c, 3)) for k, (c, ms) in sorted(prof.items())}
+                # the update pass reads and rewrites every weight once: 8 bytes per parameter per launch set
+                upd = prof.get("mlp_update")
+                if upd:
+                    us = 1e3 * upd[1] / upd[0]
+                    nbytes = 8.0 * n_params / (case["n_hidden"] + 1)
+                    entry["roofline"] = dict(kernel="mlp_update", bound="hbm", achieved=nbytes / (us * 1e-6) / 1e9,
+                                             peak=HBM_PEAK_GBS, unit="GB/s", frac=nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                             traffic=None, avg_us=us, algorithmic_bytes=nbytes,
+                                             note="average over the layers' update launches; event bracket not removed")
+            out[f"{name}_batch{batch}"] = entry
+    return out
+
+
 def describe(c):
     return dict(in_dim=c["in_dim"], hidden=c["hidden"], out_dim=c["out_dim"], seq_len=c["seq_len"],
                 batch=c["batch"], windows=c["windows"],
@@ -522,6 +576,9 @@ def main():
 
     if a.workload == "C2" and not a.reference_kernels and not a.no_train_stream:
         out["train_stream"] = train_stream_leg(a.windows)
+
+    if a.workload == "C2" and not a.no_mlp and not a.reference_kernels and not a.bf16x3:
+        out["mlp_workloads"] = mlp_leg()
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)

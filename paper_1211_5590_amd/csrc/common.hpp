@@ -45,6 +45,14 @@ __device__ __forceinline__ float swap32_sum(float v) {
 }
 __device__ __forceinline__ float sum32(float v) { return swap16_sum(sum16(v)); }
 __device__ __forceinline__ float sum64(float v) { return swap32_sum(sum32(v)); }
+__device__ __forceinline__ float max64(float v) {
+    v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
+    v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 __device__ __forceinline__ float max16(float v) {
     v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
     v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(MNT) void mlp_fwd_kernel(const float* __restrict__ 
 // dZprev[M,Kin] = (dZ[M,Nout] W[Nout,Kin]) * act'(Aprev[M,Kin]): the contraction runs over the rows
 // of W, so W is the n-contiguous operand (one value per request, 16 lanes = 64 contiguous bytes).
 // grid (ceil(Kin/16), ceil(M/16)), 1024 threads.
-template <int ACT>
+template <int ACT, bool VEC>
 __global__ __launch_bounds__(MNT) void mlp_bwd_data_kernel(const float* __restrict__ dZ, const float* __restrict__ W,
                                                            const float* __restrict__ Aprev, float* __restrict__ dZprev,
                                                            int M, int Nout, int Kin) {
@@ -115,14 +115,15 @@ __global__ __launch_bounds__(MNT) void mlp_bwd_data_kernel(const float* __restri
         const int k0 = kc * MKC + 4 * g;
         float a[16], b[16];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s) {
+            const float4 av = a_ok ? ld_k4<VEC>(arow, k0 + 16 * s, Nout) : make_float4(0.f, 0.f, 0.f, 0.f);
+            a[4 * s] = av.x; a[4 * s + 1] = av.y; a[4 * s + 2] = av.z; a[4 * s + 3] = av.w;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int k = k0 + 16 * s + e;
-                const bool k_ok = k < Nout;
-                a[4 * s + e] = (a_ok && k_ok) ? arow[k] : 0.f;
-                b[4 * s + e] = (b_ok && k_ok) ? bcol[(size_t)k * Kin] : 0.f;
+                b[4 * s + e] = (b_ok && k < Nout) ? bcol[(size_t)k * Kin] : 0.f;
             }
+        }
 #pragma unroll
         for (int q = 0; q < 16; q += 2) {
             acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], b[q], acc0, 0, 0, 0);
@@ -143,7 +144,10 @@ __global__ __launch_bounds__(MNT) void mlp_bwd_data_kernel(const float* __restri
 
 // W[n,k] -= lr sum_m dZ[m,n] Aprev[m,k];  b[n] -= lr sum_m dZ[m,n].
 // A wavefront owns 16 rows of W by 64 columns (four 16x16 tiles sharing the dZ operand) and walks
-// the batch four rows at a time; grid (ceil(Kin/256), ceil(Nout/16)), 256 threads.
+// the batch four rows per matrix instruction; grid (ceil(Kin/256), ceil(Nout/16)), 256 threads.
+// MB > 0: the batch has at most 16 MB rows and every operand (and the tile of W itself) is
+// requested before the first product, one memory round trip for the whole update; MB = 0: any batch.
+template <int MB>
 __global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict__ dZ, const float* __restrict__ Aprev,
                                                          float* __restrict__ W, float* __restrict__ b, int M,
                                                          int Nout, int Kin, float lr) {
@@ -151,10 +155,15 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict
     const int q = lane / 16, r = lane % 16;
     const int n0 = blockIdx.y * 16;
     const int k0 = (blockIdx.x * 4 + wave) * 64;
-    if (blockIdx.x == 0 && wave == 0 && lane < 16 && n0 + lane < Nout) {
+    if (blockIdx.x == 0 && wave == 0) {
+        // bias: lane (q, r) sums the rows m = q, q + 4, ... of column n0 + r; the four partial sums
+        // of a column meet through lane exchanges in a fixed order
         float s = 0.f;
-        for (int m = 0; m < M; ++m) s += dZ[(size_t)m * Nout + n0 + lane];
-        b[n0 + lane] -= lr * s;
+        if (n0 + r < Nout)
+            for (int m = q; m < M; m += 4) s += dZ[(size_t)m * Nout + n0 + r];
+        s += __shfl_xor(s, 16, kWave);
+        s += __shfl_xor(s, 32, kWave);
+        if (q == 0 && n0 + r < Nout) b[n0 + r] -= lr * s;
     }
     if (k0 >= Kin) return;
     const bool n_ok = n0 + r < Nout;
@@ -162,27 +171,43 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict
     f32x4 acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int mb = 0; mb < M; mb += 16) {
-        float a[4], x[4][4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int m = mb + 4 * u + q;
-            const bool m_ok = m < M;
-            const int mm = min(m, M - 1);
-            a[u] = (m_ok && n_ok) ? dZ[(size_t)mm * Nout + ncol] : 0.f;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int k = k0 + 16 * t + r;
-                x[u][t] = (m_ok && k < Kin) ? Aprev[(size_t)mm * Kin + k] : 0.f;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], x[u][t], acc[t], 0, 0, 0);
-    }
     // tile layout: lane -> column r (k index); register i -> row 4 q + i (n index)
+    float wv[4][4];
+    if (MB > 0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = k0 + 16 * t + r, n = n0 + 4 * q + i;
+                wv[t][i] = (k < Kin && n < Nout) ? W[(size_t)n * Kin + k] : 0.f;
+            }
+    }
+    constexpr int UB = MB > 0 ? MB : 1;
+    const int mend = MB > 0 ? 16 * MB : M;
+    for (int mb = 0; mb < mend; mb += 16 * UB) {
+        float a[UB][4], x[UB][4][4];
+#pragma unroll
+        for (int v = 0; v < UB; ++v)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int m = mb + 16 * v + 4 * u + q;
+                const bool m_ok = m < M;
+                const int mm = min(m, M - 1);
+                a[v][u] = (m_ok && n_ok) ? dZ[(size_t)mm * Nout + ncol] : 0.f;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int k = k0 + 16 * t + r;
+                    x[v][u][t] = (m_ok && k < Kin) ? Aprev[(size_t)mm * Kin + k] : 0.f;
+                }
+            }
+#pragma unroll
+        for (int v = 0; v < UB; ++v)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[v][u], x[v][u][t], acc[t], 0, 0, 0);
+    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int k = k0 + 16 * t + r;
@@ -190,28 +215,30 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int n = n0 + 4 * q + i;
-            if (n < Nout) W[(size_t)n * Kin + k] -= lr * acc[t][i];
+            if (n >= Nout) continue;
+            float* dst = W + (size_t)n * Kin + k;
+            *dst = (MB > 0 ? wv[t][i] : *dst) - lr * acc[t][i];
         }
     }
 }
 
-// One workgroup: per row log-sum-exp, the row's loss, dZ = (softmax - onehot) / M in place over
-// the logits, and the batch's mean loss (rows summed in order).  M <= 1024.
-__global__ __launch_bounds__(256) void mlp_ce_kernel(float* __restrict__ Z, const int32_t* __restrict__ y,
-                                                     float* __restrict__ loss, int M, int O) {
+// One workgroup of 16 wavefronts: per row log-sum-exp, the row's loss, dZ = (softmax - onehot) / M
+// in place over the logits, and the batch's mean loss (rows summed in order).  M <= 1024.
+__global__ __launch_bounds__(1024) void mlp_ce_kernel(float* __restrict__ Z, const int32_t* __restrict__ y,
+                                                      float* __restrict__ loss, int M, int O) {
     __shared__ float rowloss[1024];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const float inv = 1.0f / (float)M;
-    for (int row = wave; row < M; row += 4) {
+    for (int row = wave; row < M; row += 16) {
         float* z = Z + (size_t)row * O;
+        const int yy = y[row];
         float m = -INFINITY;
         for (int k = lane; k < O; k += kWave) m = fmaxf(m, z[k]);
-        m = wave_max(m);
+        m = max64(m);
         float s = 0.f;
         for (int k = lane; k < O; k += kWave) s += __expf(z[k] - m);
-        s = wave_sum(s);
-        const float lse = m + logf(s);
-        const int yy = y[row];
+        s = sum64(s);
+        const float lse = m + __logf(s);
         if (lane == 0) rowloss[row] = lse - z[yy];
         for (int k = lane; k < O; k += kWave) {
             float d = __expf(z[k] - lse);
@@ -220,10 +247,11 @@ __global__ __launch_bounds__(256) void mlp_ce_kernel(float* __restrict__ Z, cons
         }
     }
     __syncthreads();
-    if (tid == 0) {
+    if (wave == 0) {   // fixed order: lane l adds rows l, l + 64, ...; then the lanes in a fixed tree
         float s = 0.f;
-        for (int r = 0; r < M; ++r) s += rowloss[r];
-        *loss = s * inv;
+        for (int r = lane; r < M; r += kWave) s += rowloss[r];
+        s = sum64(s);
+        if (lane == 0) *loss = s * inv;
     }
 }
 
@@ -329,7 +357,7 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
         }
         {
             ProfileScope ps(K_MLP_CE, s);
-            hipLaunchKernelGGL(mlp_ce_kernel, dim3(1), dim3(256), 0, s, Z, y + (size_t)i * B,
+            hipLaunchKernelGGL(mlp_ce_kernel, dim3(1), dim3(1024), 0, s, Z, y + (size_t)i * B,
                                losses ? losses + i : scratch_loss, B, dims->out_dim);
             if (hipGetLastError() != hipSuccess) return RNN_EHIP;
         }
@@ -343,19 +371,24 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
             if (l > 0) {
                 dim3 grid((w.w[l] + 15) / 16, (B + 15) / 16);
                 ProfileScope ps(K_MLP_BWD, s);
-                if (dims->act == 0)
-                    hipLaunchKernelGGL(mlp_bwd_data_kernel<0>, grid, dim3(MNT), 0, s, dz, params->W[l], a_in,
-                                       dz_prev, B, w.w[l + 1], w.w[l]);
-                else
-                    hipLaunchKernelGGL(mlp_bwd_data_kernel<1>, grid, dim3(MNT), 0, s, dz, params->W[l], a_in,
-                                       dz_prev, B, w.w[l + 1], w.w[l]);
+                const bool vec = w.w[l + 1] % 4 == 0;   // dZ rows stay 16-byte aligned (workspace regions are)
+#define RNN_MLP_BWD(ACT, VEC)                                                                              \
+    hipLaunchKernelGGL((mlp_bwd_data_kernel<ACT, VEC>), grid, dim3(MNT), 0, s, dz, params->W[l], a_in, dz_prev, \
+                       B, w.w[l + 1], w.w[l])
+                if (dims->act == 0) { if (vec) RNN_MLP_BWD(0, true); else RNN_MLP_BWD(0, false); }
+                else { if (vec) RNN_MLP_BWD(1, true); else RNN_MLP_BWD(1, false); }
+#undef RNN_MLP_BWD
                 if (hipGetLastError() != hipSuccess) return RNN_EHIP;
             }
             {
                 dim3 grid((w.w[l] + 255) / 256, (w.w[l + 1] + 15) / 16);
                 ProfileScope ps(K_MLP_UPDATE, s);
-                hipLaunchKernelGGL(mlp_update_kernel, grid, dim3(256), 0, s, dz, a_in, params->W[l], params->b[l],
-                                   B, w.w[l + 1], w.w[l], lr);
+#define RNN_MLP_UPD(MB)                                                                                    \
+    hipLaunchKernelGGL(mlp_update_kernel<MB>, grid, dim3(256), 0, s, dz, a_in, params->W[l], params->b[l], B, \
+                       w.w[l + 1], w.w[l], lr)
+                if (B <= 16) RNN_MLP_UPD(1); else if (B <= 32) RNN_MLP_UPD(2); else if (B <= 64) RNN_MLP_UPD(4);
+                else RNN_MLP_UPD(0);
+#undef RNN_MLP_UPD
                 if (hipGetLastError() != hipSuccess) return RNN_EHIP;
             }
             dz = dz_prev;

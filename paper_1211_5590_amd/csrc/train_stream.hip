@@ -85,14 +85,6 @@ __device__ long long g_trace[257 * 16];
 #define TS_FLUSH
 #endif
 
-__device__ __forceinline__ float max64(float v) {
-    v = fmaxf(v, dpp<0xB1>(v)); v = fmaxf(v, dpp<0x4E>(v));
-    v = fmaxf(v, dpp<0x141>(v)); v = fmaxf(v, dpp<0x140>(v));
-    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
 // merge of (max, sum of exponentials) pairs over the 64 lanes, result in every lane
 __device__ __forceinline__ void lse_merge64(float& m, float& s) {
     { const float m2 = dpp<0xB1>(m), s2 = dpp<0xB1>(s); lse_merge(m, s, m2, s2); }
