@@ -43,6 +43,8 @@ def parse():
                     help="time rnn_forward -> rnn_loss -> rnn_bptt even where rnn_window serves the shape")
     ap.add_argument("--no-train-stream", action="store_true",
                     help="skip the single-launch SGD driver leg of the headline workload")
+    ap.add_argument("--only-mlp", action="store_true",
+                    help="run only the feed-forward classifier workloads and print their JSON line")
     ap.add_argument("--no-mlp", action="store_true",
                     help="skip the feed-forward classifier workloads (the paper's second benchmark)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
@@ -481,6 +483,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     import paper_1211_5590_amd as rnn
+    if a.only_mlp:
+        print(json.dumps({"metric": "classifier training examples/sec", "unit": "examples/s", "n_gpus": 1,
+                          "dtype": "f32", "data": "synthetic", "mlp_workloads": mlp_leg()}))
+        return
     flags = rnn.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     if a.bf16x3:
         flags |= rnn.FLAG_BF16X3_OUTPUT

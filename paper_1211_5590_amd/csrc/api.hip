@@ -28,7 +28,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Plan {
     // byte offsets into the workspace
     size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gbox, gpart, vy, seen,
-        lstat, HsS, HsT, VS, VT, dZS, dZT, splitk3, total;
+        lstat, HsS, HsT, VS, VT, dZS, dZT, DT, splitk3, total;
 };
 
 // Which kernel family serves these sizes.
@@ -148,11 +148,13 @@ Plan make_plan(const rnn_dims* d) {
     p.VT = take(bf3 ? O * Hp * 4 : 0);
     p.dZS = take(bf3 ? N * Op * 4 : 0);
     p.dZT = take(bf3 ? O * Np * 4 : 0);
+    p.DT = take(bf3 ? H * Np * 4 : 0);
     size_t sk3 = 0;
     if (bf3) {
         sk3 = bf3_splitk_floats((int)N, s.O, s.H);
         if (bf3_splitk_floats(s.H, s.O, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.O, (int)N);
         if (bf3_splitk_floats((int)N, s.H, s.O) > sk3) sk3 = bf3_splitk_floats((int)N, s.H, s.O);
+        if (bf3_splitk_floats(s.H, s.H, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.H, (int)N);
     }
     p.splitk3 = take(sk3 * 4);
     p.total = off;
@@ -411,7 +413,17 @@ hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const vo
     }
     RNN_TRY(run_reverse_loop(d, P->Wh, nullptr, at<float>(ws, pl.WhT), G, h_all, dh_last, Delta, dh0, ws, pl, s));
     // dWh = Delta^T Hprev  (Hprev rows = h_all[0:T])
-    {
+    if (bf3) {
+        // both operands transposed into split form (the planes of h^T used by dV are free again)
+        const int Np = bf3_pad(N);
+        RNN_TRY(launch_split_bf16(Delta, N, H, H, nullptr, at<uint16_t>(ws, pl.DT), s));
+        RNN_TRY(launch_split_bf16(h_all, N, H, H, nullptr, at<uint16_t>(ws, pl.HsT), s));
+        Bf3Args b{};
+        b.A = at<uint16_t>(ws, pl.DT); b.B = at<uint16_t>(ws, pl.HsT); b.C = Gr->dWh;
+        b.M = H; b.N = H; b.K = N; b.lda = Np; b.ldb = Np; b.ldc = H;
+        b.beta = beta; b.splitk_ws = at<float>(ws, pl.splitk3); b.prof_id = K_GEMM_DWH;
+        RNN_TRY(launch_gemm_bf16x3(b, s));
+    } else {
         GemmArgs g{};
         g.A = Delta; g.B = h_all; g.C = Gr->dWh;
         g.M = H; g.N = H; g.K = N;
