@@ -98,8 +98,8 @@ class Workload:
         self.G = rnn.Grads(*[self.g["d" + k].data_ptr() for k in ("Wx", "Wh", "b", "V", "c")])
         self.x_stride = self.x[0].numel() * self.x.element_size() * self.T
         self.y_stride = self.y[0].numel() * self.y.element_size() * self.T
-        case["_name"] = name
         case["_bf16x3"] = bool(flags & rnn.FLAG_BF16X3_OUTPUT)
+        case["_name"] = name + ("B" if case["_bf16x3"] else "")   # key of the counter-based traffic table
         case["_variant"] = rnn.rnn_recurrence_variant(self.dims)
         case["_workgroups"] = rnn.rnn_recurrence_workgroups(self.dims)
         self.tokens_per_step = self.T * self.B * self.windows
