@@ -31,6 +31,8 @@
 
 #include <math.h>
 
+#include <atomic>
+
 namespace rnn {
 namespace {
 
@@ -370,15 +372,16 @@ hipError_t launch_bf3(const Bf3Params& p, hipStream_t s) {
     constexpr int NTH = WGM * WGN * 64;
     constexpr size_t smem = 2 * (size_t)(2 * WGM * TM * 32 * 64 + 2 * WGN * TN * 32 * 64);
     dim3 grid(p.tiles_m * p.tiles_n, 1, p.splits);
-    static bool raised[2] = {false, false};   // per kernel form: allow more than 64 KB of dynamic LDS
-    if (!raised[p.stats ? 1 : 0]) {
+    // per kernel form, once per process (one GPU): allow more than 64 KB of dynamic LDS
+    static std::atomic<bool> raised[2];
+    if (!raised[p.stats ? 1 : 0].load(std::memory_order_acquire)) {
         hipError_t e = p.stats
             ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16x3_kernel<WGM, WGN, TM, TN, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)
             : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16x3_kernel<WGM, WGN, TM, TN, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        raised[p.stats ? 1 : 0] = true;
+        raised[p.stats ? 1 : 0].store(true, std::memory_order_release);
     }
     if (p.stats) hipLaunchKernelGGL((gemm_bf16x3_kernel<WGM, WGN, TM, TN, true>), grid, dim3(NTH), smem, s, p);
     else hipLaunchKernelGGL((gemm_bf16x3_kernel<WGM, WGN, TM, TN, false>), grid, dim3(NTH), smem, s, p);

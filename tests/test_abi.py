@@ -160,3 +160,18 @@ def test_mlp_rejects_bad_arguments_without_a_gpu():
     assert call(dims=rnn.MlpDims(784, 500, 1, 10, 2000, 1, 0)) == -3   # batch beyond what the kernels serve
     assert call(ws=None) == -2
     assert call(nbytes=need - 1) == -2
+
+
+def test_split_product_flag_is_taken_only_where_it_applies():
+    d = good_dims(flags=rnn.FLAG_BF16X3_OUTPUT)
+    assert rnn.rnn_workspace_bytes(d) > rnn.rnn_workspace_bytes(good_dims())   # room for the bf16 operands
+    fake = 0x1000
+    P = rnn.Params(fake, fake, fake, fake, fake)
+    G = rnn.Grads(fake, fake, fake, fake, fake)
+    L = rnn.lib()
+    n = ctypes.c_size_t(0)
+    # the one-launch kernels and the Gauss-Newton product do not take the flag
+    assert L.rnn_window_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == -1
+    assert L.rnn_train_stream_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == -1
+    assert L.rnn_gauss_newton_vec(ctypes.byref(d), ctypes.byref(P), ctypes.byref(P), fake, fake, 0,
+                                  ctypes.byref(G), None, fake, 1 << 30, None) == -1

@@ -56,3 +56,19 @@ def test_accumulate_recompute_and_row_sums():
     twice = r.results()
     for k in ("dWx", "dWh", "db", "dV", "dc"):
         grad_close("2x" + k, twice[k], 2.0 * ref[k])
+
+
+def test_split_products_stay_close_to_the_float32_path_and_repeat_exactly():
+    """The error bound the split rests on (each product term within 2^-16 relative): the split path
+    must land far closer to the float32 path than the tolerance against the oracle asks, and give
+    the same bits on every run (fixed summation order, no atomics)."""
+    i, h, o, T, B, extra = BIG_CASES["lm_split_k"]
+    case = ri.make_case(i, h, o, T, B, seed=901, **extra)
+    f32 = run_gpu(case, 0)
+    a = run_gpu(case, BF3)
+    b = run_gpu(case, BF3)
+    assert abs(a["loss"] - f32["loss"]) <= 2e-6 * abs(f32["loss"])
+    for k in ("dV", "dc", "dWh", "dWx", "db"):
+        assert np.array_equal(a[k], b[k]), k
+        scale = np.abs(f32[k]).max()
+        assert np.abs(a[k] - f32[k]).max() <= 5e-5 * scale, (k, np.abs(a[k] - f32[k]).max() / scale)
