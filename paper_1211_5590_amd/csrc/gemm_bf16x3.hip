@@ -301,7 +301,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16x3_kernel(Bf3Params p)
             }
         }
 
-    if (STATS && final_out) {
+    if constexpr (STATS) if (final_out) {
         static_assert(TN == 2, "a part of the row statistics is 64 columns");
         const int nparts = p.tiles_n * WGN;
         const int part = tile_n * WGN + wn;
