@@ -464,6 +464,47 @@ def mlp_leg(n_batches=400, lr=0.01):
     return out
 
 
+def gauss_newton_leg(names=("C3", "C4", "C5"), reps=5):
+    """One Gauss-Newton-vector product (R-operator sweep, loss metric, reverse sweep) per call of
+    rnn_gauss_newton_vec on the named configurations, with the states of one forward pass:
+    HIP-event time per product and its per-kernel times."""
+    import numpy as np
+    import torch
+    import paper_1211_5590_amd as rnn
+    import rnn_inputs as ri
+    out = {}
+    for name in names:
+        w = Workload(name, 0, None, three_calls=True)
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = w.L.rnn_forward(ctypes.byref(w.dims), ctypes.byref(w.P), w.x.data_ptr(), None, w.h_all.data_ptr(),
+                             w.carry[0].data_ptr(), w.ws.data_ptr(), w.ws.numel(), stream)
+        assert rc == 0, rc
+        gamma = ri.make_direction(w.case, 1)
+        g = {k: torch.from_numpy(np.ascontiguousarray(gamma[k])).cuda() for k in ("Wx", "Wh", "b", "V", "c")}
+        res = {"d" + k: torch.zeros_like(v) for k, v in w.p.items()}
+        gws = torch.empty(rnn.rnn_gauss_newton_workspace_bytes(w.dims), dtype=torch.uint8, device="cuda")
+        rnn.rnn_workspace_init(w.dims, gws)
+        call = lambda: rnn.rnn_gauss_newton_vec(w.dims, w.p, g, w.x, w.h_all, rnn.GN_METRIC_LOSS, res, None, gws)
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rnn.rnn_profile_begin(1 << 16)
+        call()
+        prof = rnn.rnn_profile_end()
+        top = sorted(prof.items(), key=lambda kv: -kv[1][1])[:6]
+        out[name] = dict(ms_per_product=ms, tokens_per_s=w.tokens_per_step / (ms * 1e-3),
+                         kernels={k: dict(launches=c, total_ms_raw=round(t, 4)) for k, (c, t) in top})
+        del w, gws, res, g
+        torch.cuda.empty_cache()
+    return out
+
+
 def describe(c):
     return dict(in_dim=c["in_dim"], hidden=c["hidden"], out_dim=c["out_dim"], seq_len=c["seq_len"],
                 batch=c["batch"], windows=c["windows"],
@@ -585,6 +626,8 @@ def main():
 
     if a.workload == "C2" and not a.no_mlp and not a.reference_kernels and not a.bf16x3:
         out["mlp_workloads"] = mlp_leg()
+    if a.workload == "C2" and per and not a.reference_kernels and not a.bf16x3:
+        out["gauss_newton_vec"] = gauss_newton_leg([n for n in ("C3", "C4", "C5") if n in per])
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)
