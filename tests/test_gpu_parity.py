@@ -134,6 +134,25 @@ def test_results_are_bit_identical_run_to_run():
         assert first["loss"] == again["loss"]
 
 
+@pytest.mark.parametrize("name", ["lm_hidden_500", "lm_hidden_300_two_groups", "lm_batched_wide_stepwise",
+                                  "lm_batched_mfma_shape"])
+def test_multi_workgroup_loops_repeat_exactly_100_times(name):
+    """A broken exchange or barrier between the workgroups of a time loop shows up as run-to-run
+    noise: 100 repetitions of forward + BPTT must give the same bits every time."""
+    case = make(name)
+    r = Runner(case)
+    r.step()
+    first = {k: v.clone() for k, v in r.grads.items()}
+    h_first, dh0_first = r.h_all.clone(), r.dh0.clone()
+    for _ in range(100):
+        r.forward(); r.loss_(); r.bptt()
+        assert torch.equal(r.h_all, h_first)
+        assert torch.equal(r.dh0, dh0_first)
+        for k, v in r.grads.items():
+            assert torch.equal(v, first[k]), k
+    assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
+
+
 def test_two_windows_chain_state_forward_and_gradient_backward():
     full = ri.make_case(200, 48, 200, 12, 2, seed=77, wdist=("normal", 0.3), bias_std=0.1, **LM)
     ref = oracle.fwd_bptt(full)
