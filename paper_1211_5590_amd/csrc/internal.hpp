@@ -94,6 +94,7 @@ struct RecResArgs {
     int32_t* flags;              // exchange boxes in the workspace (P > 1): [2][B][H] 64-bit words, 8-byte aligned
     int32_t* status;             // device status word: set to 1 when a bounded wait expires
     int spin_limit;              // <= 0: default
+    int xcd_pack;                // set by the launcher: workgroup p of a sequence is blockIdx.x / 8 (see the kernel)
     // forward
     const float* Wx; const float* b; const int32_t* x; const float* U; const float* h0;
     float* hist; float* h_last; int ring;

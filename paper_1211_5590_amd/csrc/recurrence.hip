@@ -507,6 +507,14 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
 template <int ACT, bool BWD>
 __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
+    if (a.xcd_pack) {
+        // Workgroups are dealt to the 8 XCDs in turn; with 8 times the workgroups launched and
+        // only every eighth working, the P workgroups of a sequence share one die (and its L2),
+        // which shortens the state exchange.  The others leave at once.
+        if (blockIdx.x & 7) return;
+        rec_resident_body<ACT, BWD>(a, blockIdx.x >> 3, blockIdx.y, smem);
+        return;
+    }
     rec_resident_body<ACT, BWD>(a, blockIdx.x, blockIdx.y, smem);
 }
 
@@ -621,6 +629,11 @@ hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hip
     }
     ProfileScope ps(bwd ? K_REC_BWD : K_REC_FWD, s);
     dim3 grid(pl.P, a.B), block(kThreads);
+    a.xcd_pack = 0;
+    if (pl.P > 1 && pl.P <= 32 && pl.P * 8 * a.B <= 256) {   // the padded grid still fits the chip
+        a.xcd_pack = 1;
+        grid.x = pl.P * 8;
+    }
     if (pl.P > 1) {
         void* args[] = {&a};
         return hipLaunchCooperativeKernel(fn, grid, block, args, (unsigned)pl.smem, s);
