@@ -324,8 +324,16 @@ struct SplitPlan {
     int splits, kchunk;
 };
 
-SplitPlan plan_split(int M, int N, int K) {
+// Row tile of a product: 128, or 64 where 128-row tiles would leave most compute units without a
+// workgroup (few rows, no K to cut): twice the workgroups keep twice the requests in flight.
+int pick_bm(int M, int N, int K) {
     const int tiles = ((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_);
+    return (tiles < 128 && K <= 512 && M > 64) ? 64 : 128;
+}
+
+SplitPlan plan_split(int M, int N, int K) {
+    const int bm_ = pick_bm(M, N, K);
+    const int tiles = ((M + bm_ - 1) / bm_) * ((N + BN_ - 1) / BN_);
     int splits = 1;
     if (tiles < 256 && K > 512) {
         const int by_k = (K + 255) / 256;          // at least 256 of K per split
@@ -394,7 +402,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
     const SplitPlan sp = plan_split(g.M, g.N, g.K);
     if (sp.splits > 1 && !g.splitk_ws) return hipErrorInvalidValue;
-    const int bm = BM_, bn = BN_;
+    const int bm = pick_bm(g.M, g.N, g.K), bn = BN_;
 
     GemmParams p;
     p.A = g.A; p.B = g.B; p.bias_n = g.bias_n;
@@ -412,12 +420,17 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     const bool vec = aligned16(g.A) && aligned16(g.B) && g.lda % 4 == 0 && g.ldb % 4 == 0;
 
     hipError_t e;
-#define RNN_GEMM_DISPATCH(AT, BT)                                              \
-    e = vec ? launch_variant<BM_, BN_, AT, BT, true>(p, s) : launch_variant<BM_, BN_, AT, BT, false>(p, s)
+#define RNN_GEMM_DISPATCH(AT, BT)                                                                \
+    do {                                                                                         \
+        if (bm == 64) e = vec ? launch_variant<64, BN_, AT, BT, true>(p, s) : launch_variant<64, BN_, AT, BT, false>(p, s); \
+        else e = vec ? launch_variant<BM_, BN_, AT, BT, true>(p, s) : launch_variant<BM_, BN_, AT, BT, false>(p, s);      \
+    } while (0)
     if (p.stats) {   // only the plain-layout product (the output projection) carries the statistics
         if (g.a_t || g.b_t) return hipErrorInvalidValue;
-        e = vec ? launch_variant<BM_, BN_, false, false, true, true>(p, s)
-                : launch_variant<BM_, BN_, false, false, false, true>(p, s);
+        if (bm == 64) e = vec ? launch_variant<64, BN_, false, false, true, true>(p, s)
+                              : launch_variant<64, BN_, false, false, false, true>(p, s);
+        else e = vec ? launch_variant<BM_, BN_, false, false, true, true>(p, s)
+                     : launch_variant<BM_, BN_, false, false, false, true>(p, s);
     } else if (!g.a_t && !g.b_t) RNN_GEMM_DISPATCH(false, false);
     else if (g.a_t && !g.b_t) RNN_GEMM_DISPATCH(true, false);
     else if (!g.a_t && g.b_t) RNN_GEMM_DISPATCH(false, true);
