@@ -28,7 +28,7 @@ inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Plan {
     // byte offsets into the workspace
     size_t Z, lse, rowloss, U, G, Delta, WhT, hring, part, splitk, scratch, flags, statbox, gbox, gpart, vy, seen,
-        lstat, HsS, HsT, VS, VT, dZS, dZT, DT, splitk3, total;
+        lstat, HsS, HsT, VS, VT, dZS, dZT, DT, XS, WxS, splitk3, total;
 };
 
 // Which kernel family serves these sizes.
@@ -149,12 +149,17 @@ Plan make_plan(const rnn_dims* d) {
     p.dZS = take(bf3 ? N * Op * 4 : 0);
     p.dZT = take(bf3 ? O * Np * 4 : 0);
     p.DT = take(bf3 ? H * Np * 4 : 0);
+    // dense input: X transposed, for dWx (the input projection itself stays float32: the hidden
+    // states it feeds are held to a tighter tolerance than the gradients)
+    p.XS = take(bf3 && !s.tokens ? (size_t)s.NVin * Np * 4 : 0);
+    p.WxS = take(0);
     size_t sk3 = 0;
     if (bf3) {
         sk3 = bf3_splitk_floats((int)N, s.O, s.H);
         if (bf3_splitk_floats(s.H, s.O, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.O, (int)N);
         if (bf3_splitk_floats((int)N, s.H, s.O) > sk3) sk3 = bf3_splitk_floats((int)N, s.H, s.O);
         if (bf3_splitk_floats(s.H, s.H, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.H, (int)N);
+        if (!s.tokens && bf3_splitk_floats(s.H, s.NVin, (int)N) > sk3) sk3 = bf3_splitk_floats(s.H, s.NVin, (int)N);
     }
     p.splitk3 = take(sk3 * 4);
     p.total = off;
@@ -439,6 +444,16 @@ hipError_t run_backward_from_dz(const rnn_dims* d, const rnn_params* P, const vo
         // the logits buffer is dead by now and serves as scratch for per-range partial rows
         RNN_TRY(launch_dwx_tokens(static_cast<const int32_t*>(x), Delta, Gr->dWx, N, z.NVin, H, beta,
                                   Z, (size_t)N * O, N > 32 ? at<int32_t>(ws, pl.seen) : nullptr, s));
+    } else if (bf3) {
+        // dWx = Delta^T X: Delta^T is in split form already (dWh), X is transposed into it now
+        const int Np = bf3_pad(N);
+        RNN_TRY(launch_split_bf16(static_cast<const float*>(x), N, z.NVin, z.NVin, nullptr,
+                                  at<uint16_t>(ws, pl.XS), s));
+        Bf3Args b{};
+        b.A = at<uint16_t>(ws, pl.DT); b.B = at<uint16_t>(ws, pl.XS); b.C = Gr->dWx;
+        b.M = H; b.N = z.NVin; b.K = N; b.lda = Np; b.ldb = Np; b.ldc = z.NVin;
+        b.beta = beta; b.splitk_ws = at<float>(ws, pl.splitk3); b.prof_id = K_GEMM_DWX;
+        RNN_TRY(launch_gemm_bf16x3(b, s));
     } else {
         GemmArgs g{};
         g.A = Delta; g.B = static_cast<const float*>(x); g.C = Gr->dWx;

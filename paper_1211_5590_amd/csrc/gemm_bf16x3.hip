@@ -355,7 +355,7 @@ Bf3Plan plan_bf3(int M, int N, int K) {
         const double slots = pl.slots, out_bytes = 4.0 * M * (double)N;
         const double t_full = 6.0 * M * N * (double)K / 1000e12;   // three products at a typical rate
         double best = 1e30;
-        const int cap = slabs / 32 < 16 ? slabs / 32 : 16;
+        const int cap = slabs / 8 < 512 ? slabs / 8 : 512;   // at least 8 slabs (256 of K) per cut
         for (int sp = 1; sp <= cap; ++sp) {
             const double rounds = ceil(tiles * sp / slots) / sp;
             const double t = t_full * rounds * slots / tiles + (sp > 1 ? 2.0 * sp * out_bytes / 3e12 : 0.0);
