@@ -68,7 +68,7 @@ extern "C" {
 #define RNN_FLAG_BPTT_RECOMPUTE 4u /* rnn_bptt recomputes logits; no prior rnn_loss needed      */
 #define RNN_FLAG_REFERENCE_KERNELS 8u /* use only the shape-agnostic kernels (A/B testing)      */
 /* Opt-in reduced-precision output layer: the large products Z = H V + c, dV = H^T dZ, G = dZ V^T
- * (and dWh = Delta^T H_prev) run on the bf16 matrix cores with float32 accumulation, every float32
+ * (and dWh = Delta^T H_prev, dense-input dWx = Delta^T X) run on the bf16 matrix cores with float32 accumulation, every float32
  * operand split into two bf16 numbers (hi + lo) and each product taken as hi*hi + hi*lo + lo*hi
  * (error per product term below 2^-16 relative; parameters, results and everything else stay
  * float32).  Set it on rnn_workspace_bytes, rnn_loss and rnn_bptt alike (the workspace grows by
