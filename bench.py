@@ -464,7 +464,7 @@ def mlp_leg(n_batches=400, lr=0.01):
     return out
 
 
-def gauss_newton_leg(names=("C3", "C4", "C5"), reps=5):
+def gauss_newton_leg(names=("C3", "C4", "C5"), reps=5, flags=0):
     """One Gauss-Newton-vector product (R-operator sweep, loss metric, reverse sweep) per call of
     rnn_gauss_newton_vec on the named configurations, with the states of one forward pass:
     HIP-event time per product and its per-kernel times."""
@@ -474,7 +474,7 @@ def gauss_newton_leg(names=("C3", "C4", "C5"), reps=5):
     import rnn_inputs as ri
     out = {}
     for name in names:
-        w = Workload(name, 0, None, three_calls=True)
+        w = Workload(name, flags, None, three_calls=True)
         stream = torch.cuda.current_stream().cuda_stream
         rc = w.L.rnn_forward(ctypes.byref(w.dims), ctypes.byref(w.P), w.x.data_ptr(), None, w.h_all.data_ptr(),
                              w.carry[0].data_ptr(), w.ws.data_ptr(), w.ws.numel(), stream)
@@ -628,6 +628,8 @@ def main():
         out["mlp_workloads"] = mlp_leg()
     if a.workload == "C2" and per and not a.reference_kernels and not a.bf16x3:
         out["gauss_newton_vec"] = gauss_newton_leg([n for n in ("C3", "C4", "C5") if n in per])
+        if "C4" in per:
+            out["gauss_newton_vec"]["C4_bf16x3_output"] = gauss_newton_leg(["C4"], flags=rnn.FLAG_BF16X3_OUTPUT)["C4"]
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)

@@ -73,8 +73,8 @@ extern "C" {
  * (error per product term below 2^-16 relative; parameters, results and everything else stay
  * float32).  Set it on rnn_workspace_bytes, rnn_loss and rnn_bptt alike (the workspace grows by
  * the bf16 copies of the operands).  Ignored where the column-strip kernels of a short single
- * sequence serve the output layer; rejected by rnn_gauss_newton_vec, rnn_window and
- * rnn_train_stream. */
+ * sequence serve the output layer; rnn_gauss_newton_vec takes it too (its five output-layer
+ * products); rejected by rnn_window and rnn_train_stream. */
 #define RNN_FLAG_BF16X3_OUTPUT 16u
 
 typedef struct {

@@ -512,7 +512,7 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
 // Extra regions of the Gauss-Newton-vector product behind the ordinary plan.
 struct GnPlan {
     Plan base;
-    size_t logits, Rh, hrev, splitk_c, total;
+    size_t logits, Rh, hrev, splitk_c, RhS, gVT, total;
 };
 
 GnPlan make_gn_plan(const rnn_dims* d) {
@@ -526,6 +526,9 @@ GnPlan make_gn_plan(const rnn_dims* d) {
     p.Rh = take(N * H * 4);
     p.hrev = take((N + B) * H * 4);
     p.splitk_c = take(gemm_splitk_floats((int)N, (int)H, (int)H) * 4);   // Hprev gWh^T
+    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;                // split forms of R h and gamma.V^T
+    p.RhS = take(bf3 ? N * (size_t)bf3_pad(s.H) * 4 : 0);
+    p.gVT = take(bf3 ? O * (size_t)bf3_pad(s.H) * 4 : 0);
     p.total = off;
     return p;
 }
@@ -557,7 +560,23 @@ hipError_t run_gauss_newton(const rnn_dims* d, const rnn_params* P, const rnn_pa
     const float* Hs = h_all + BH;
     const bool ce_metric = metric == RNN_GN_METRIC_LOSS && z.ce;
 
-    if (ce_metric) {   // logits of the current parameters, for the softmax in the metric
+    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
+    const int Hp = bf3_pad(H);
+    auto big = [&](const uint16_t* A, const uint16_t* B, float* dst, const float* bias, int acc, int prof) {
+        Bf3Args b{};   // [N,O] = A[N,H] B[O,H]^T (+ bias), the shape of all three forward-side products
+        b.A = A; b.B = B; b.C = dst;
+        b.M = N; b.N = O; b.K = H; b.lda = Hp; b.ldb = Hp; b.ldc = O;
+        b.bias_n = bias; b.beta = acc; b.splitk_ws = at<float>(ws, pl.splitk3); b.prof_id = prof;
+        return launch_gemm_bf16x3(b, s);
+    };
+    if (bf3) {   // operands of the large products in split form
+        RNN_TRY(launch_split_bf16(Hs, N, H, H, at<uint16_t>(ws, pl.HsS), at<uint16_t>(ws, pl.HsT), s));
+        RNN_TRY(launch_split_bf16(P->V, H, O, O, at<uint16_t>(ws, pl.VS), at<uint16_t>(ws, pl.VT), s));
+        RNN_TRY(launch_split_bf16(Ga->V, H, O, O, nullptr, at<uint16_t>(ws, gp.gVT), s));
+    }
+    if (ce_metric && bf3) {
+        RNN_TRY(big(at<uint16_t>(ws, pl.HsS), at<uint16_t>(ws, pl.VT), Zl, P->c, 0, K_GEMM_LOGITS));
+    } else if (ce_metric) {   // logits of the current parameters, for the softmax in the metric
         GemmArgs g{};
         g.A = Hs; g.B = P->V; g.C = Zl;
         g.M = N; g.N = O; g.K = H; g.lda = H; g.ldb = O; g.ldc = O;
@@ -588,7 +607,11 @@ hipError_t run_gauss_newton(const rnn_dims* d, const rnn_params* P, const rnn_pa
     RNN_TRY(launch_transpose(P->Wh, WhT, H, H, s));
     RNN_TRY(run_reverse_loop(d, WhT, P->Wh, nullptr, Crev, hrev, nullptr, Rhrev, nullptr, ws, pl, s));
     RNN_TRY(launch_reverse_rows(Rhrev, Rh, z.T, (int)BH, s));
-    {   // R z = Rh V + gc
+    if (bf3) {   // R z = Rh V + gc + Hs gV
+        RNN_TRY(launch_split_bf16(Rh, N, H, H, at<uint16_t>(ws, gp.RhS), nullptr, s));
+        RNN_TRY(big(at<uint16_t>(ws, gp.RhS), at<uint16_t>(ws, pl.VT), U, Ga->c, 0, K_GEMM_LOGITS));
+        RNN_TRY(big(at<uint16_t>(ws, pl.HsS), at<uint16_t>(ws, gp.gVT), U, nullptr, 1, K_GEMM_LOGITS));
+    } else {   // R z = Rh V + gc
         GemmArgs g{};
         g.A = Rh; g.B = P->V; g.C = U;
         g.M = N; g.N = O; g.K = H; g.lda = H; g.ldb = O; g.ldc = O;
@@ -608,7 +631,8 @@ hipError_t run_gauss_newton(const rnn_dims* d, const rnn_params* P, const rnn_pa
     // Gc = column sums of u, then the rest of backpropagation
     RNN_TRY(launch_colsum_partial(U, at<float>(ws, pl.part), N, O, s));
     RNN_TRY(launch_colsum_finish(at<float>(ws, pl.part), Out->dc, colsum_chunks(N), O, beta, s));
-    return run_backward_from_dz(d, P, x, h_all, nullptr, Out, nullptr, ws, pl, false, s);
+    if (bf3) RNN_TRY(launch_split_bf16(U, N, O, O, at<uint16_t>(ws, pl.dZS), at<uint16_t>(ws, pl.dZT), s));
+    return run_backward_from_dz(d, P, x, h_all, nullptr, Out, nullptr, ws, pl, bf3, s);
 }
 
 bool params_ok(const rnn_params* P) {
@@ -688,7 +712,7 @@ int rnn_gauss_newton_vec(const rnn_dims* dims, const rnn_params* params, const r
     if (!dims_valid(dims) || !params_ok(params) || !params_ok(gamma) || !x || !h_all || !out)
         return RNN_EINVAL;
     if (metric != RNN_GN_METRIC_LOSS && metric != RNN_GN_METRIC_IDENTITY) return RNN_EINVAL;
-    if (dims->flags & (RNN_FLAG_BPTT_RECOMPUTE | RNN_FLAG_BF16X3_OUTPUT)) return RNN_EINVAL;
+    if (dims->flags & RNN_FLAG_BPTT_RECOMPUTE) return RNN_EINVAL;
     if (!out->dWx || !out->dWh || !out->db || !out->dV || !out->dc) return RNN_EINVAL;
     if (misaligned4(x) || misaligned(h_all) || misaligned(Rz) || misaligned(out->dWx) ||
         misaligned(out->dWh) || misaligned(out->db) || misaligned(out->dV) || misaligned(out->dc))

@@ -105,3 +105,16 @@ def test_symmetry_of_the_product_on_the_gpu():
     assert abs(ab - ba) <= 1e-3 * max(abs(ab), abs(ba))
     aa = sum(float(np.vdot(np.asarray(a[k], np.float64), Ga["d" + k])) for k in PNAMES)
     assert aa >= 0.0
+
+
+@pytest.mark.parametrize("name", ["lm_multi_tile", "lm_batched_wide_stepwise", "dense_tanh_mse", "lm_hidden_500",
+                                  "lm_long_id_list_chunked_scatter"])
+def test_gauss_newton_vec_with_the_split_products(name):
+    """The same product with its five output-layer products on the bf16 matrix cores
+    (RNN_FLAG_BF16X3_OUTPUT), at the same tolerances."""
+    case = make(name)
+    gamma = ri.make_direction(case, 12)
+    r = GnRunner(case, rnn.FLAG_BF16X3_OUTPUT)
+    r.forward()
+    got = r.gauss_newton(gamma, rnn.GN_METRIC_LOSS)
+    check(got, r.Rz.cpu().numpy(), oracle.gauss_newton_vec(case, gamma, metric=0, want_Rz=True))
