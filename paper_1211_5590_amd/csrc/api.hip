@@ -499,14 +499,22 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         return launch_rec_bwd_with_strips(r, v.bwd, k, s);
     }
 
+    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
+    if (bf3) {
+        // logits -> d loss / d logits straight into split form (no float32 copy: nothing reads one) and dc
+        int used = 0;
+        RNN_TRY(launch_dz_split(Z, at<float>(ws, pl.lse), z.ce ? static_cast<const int32_t*>(targets) : nullptr,
+                                z.ce ? nullptr : static_cast<const float*>(targets), part, N, O, d->loss_kind,
+                                at<uint16_t>(ws, pl.dZS), at<uint16_t>(ws, pl.dZT), &used, s));
+        RNN_TRY(launch_colsum_finish(part, Gr->dc, used, O, beta, s));
+        return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, true, s);
+    }
     // logits -> d loss / d logits (in place) and dc
     RNN_TRY(launch_dz(Z, at<float>(ws, pl.lse), z.ce ? static_cast<const int32_t*>(targets) : nullptr,
                       z.ce ? nullptr : static_cast<const float*>(targets), part, N, O,
                       d->loss_kind, s));
     RNN_TRY(launch_colsum_finish(part, Gr->dc, chunks, O, beta, s));
-    const bool bf3 = (d->flags & RNN_FLAG_BF16X3_OUTPUT) != 0;
-    if (bf3) RNN_TRY(launch_split_bf16(Z, N, O, O, at<uint16_t>(ws, pl.dZS), at<uint16_t>(ws, pl.dZT), s));
-    return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, bf3, s);
+    return run_backward_from_dz(d, P, x, h_all, dh_last, Gr, dh0, ws, pl, false, s);
 }
 
 // Extra regions of the Gauss-Newton-vector product behind the ordinary plan.

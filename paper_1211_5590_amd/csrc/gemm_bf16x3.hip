@@ -61,36 +61,12 @@ __device__ __forceinline__ void split8(const float (&x)[8], uint4& hi, uint4& lo
 // position (in bf16 elements) of k inside a split-form row: slab * 64 + (k % 32), lo at + 32
 __host__ __device__ inline size_t split_pos(int k) { return (size_t)(k / KS) * (2 * KS) + (size_t)(k % KS); }
 
-// src float32 [R,C] (leading dimension ld) -> split form, as it is [R][2 Cp] (rm, nullable) and/or
-// transposed [C][2 Rp] (tr, nullable); Cp, Rp = C, R rounded up to 32, pads written as 0.
-// One 64x64 tile per workgroup, through LDS.
-__global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ src, int R, int C, int ld,
-                                                    uint16_t* __restrict__ rm, uint16_t* __restrict__ tr,
-                                                    int Cp, int Rp, int vec) {
+// A 64x64 float32 tile in LDS (row stride 65) -> its part of the split forms (see split_kernel).
+__device__ __forceinline__ void write_split_tile(const float* __restrict__ tile, int r0, int c0, int R, int C,
+                                                 uint16_t* __restrict__ rm, uint16_t* __restrict__ tr, int Cp,
+                                                 int Rp) {
     constexpr int TS = 65;
-    __shared__ float tile[64 * TS];
     const int tid = threadIdx.x;
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = tid / 16 + 16 * i, c4 = (tid % 16) * 4;
-        const int gr = r0 + row, gc = c0 + c4;
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (gr < R) {
-            const float* p = src + (size_t)gr * ld + gc;
-            if (vec && gc + 3 < C) {
-                t = *reinterpret_cast<const float4*>(p);
-            } else {
-                if (gc + 0 < C) t.x = p[0];
-                if (gc + 1 < C) t.y = p[1];
-                if (gc + 2 < C) t.z = p[2];
-                if (gc + 3 < C) t.w = p[3];
-            }
-        }
-        float* d = tile + row * TS + c4;
-        d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
-    }
-    __syncthreads();
     if (rm) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -122,6 +98,112 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ sr
                 *reinterpret_cast<uint4*>(at + KS) = lo;
             }
         }
+    }
+}
+
+// src float32 [R,C] (leading dimension ld) -> split form, as it is [R][2 Cp] (rm, nullable) and/or
+// transposed [C][2 Rp] (tr, nullable); Cp, Rp = C, R rounded up to 32, pads written as 0.
+// One 64x64 tile per workgroup, through LDS.
+__global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ src, int R, int C, int ld,
+                                                    uint16_t* __restrict__ rm, uint16_t* __restrict__ tr,
+                                                    int Cp, int Rp, int vec) {
+    constexpr int TS = 65;
+    __shared__ float tile[64 * TS];
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = tid / 16 + 16 * i, c4 = (tid % 16) * 4;
+        const int gr = r0 + row, gc = c0 + c4;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gr < R) {
+            const float* p = src + (size_t)gr * ld + gc;
+            if (vec && gc + 3 < C) {
+                t = *reinterpret_cast<const float4*>(p);
+            } else {
+                if (gc + 0 < C) t.x = p[0];
+                if (gc + 1 < C) t.y = p[1];
+                if (gc + 2 < C) t.z = p[2];
+                if (gc + 3 < C) t.w = p[3];
+            }
+        }
+        float* d = tile + row * TS + c4;
+        d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
+    }
+    __syncthreads();
+    write_split_tile(tile, r0, c0, R, C, rm, tr, Cp, Rp);
+}
+
+// d loss / d z straight into split form: what dz + split_kernel do in two passes over [N,O], in one
+// (the float32 dZ is never written: with the split products nothing reads it).  LOSS 0:
+// (exp(z - lse) - onehot(y)) * scale; LOSS 1: (z - Y) * scale.  A workgroup walks the 64-row tiles
+// of rows [blockIdx.x * rpg, + rpg) of one 64-column strip and leaves the column sums of its rows
+// in part[blockIdx.x][O] (for dc; summed in a fixed order).  rpg is a multiple of 64.
+template <int LOSS>
+__global__ __launch_bounds__(256) void dz_split_kernel(const float* __restrict__ Z, const float* __restrict__ lse,
+                                                       const int32_t* __restrict__ y, const float* __restrict__ Y,
+                                                       float* __restrict__ part, int N, int O, float scale,
+                                                       uint16_t* __restrict__ rm, uint16_t* __restrict__ tr, int Op,
+                                                       int Np, int rpg, int vec) {
+    constexpr int TS = 65;
+    __shared__ float tile[64 * TS];
+    const int tid = threadIdx.x;
+    const int c0 = blockIdx.y * 64;
+    const int r_begin = blockIdx.x * rpg, r_end = min(r_begin + rpg, Np);
+    const int c4 = (tid % 16) * 4, gc = c0 + c4;
+    float cs[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int r0 = r_begin; r0 < r_end; r0 += 64) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = tid / 16 + 16 * i, gr = r0 + row;
+            float d[4] = {0.f, 0.f, 0.f, 0.f};
+            if (gr < N) {
+                const float* p = Z + (size_t)gr * O + gc;
+                float zv[4] = {0.f, 0.f, 0.f, 0.f}, tv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (vec && gc + 3 < O) {
+                    const float4 a = *reinterpret_cast<const float4*>(p);
+                    zv[0] = a.x; zv[1] = a.y; zv[2] = a.z; zv[3] = a.w;
+                    if (LOSS == 1) {
+                        const float4 b = *reinterpret_cast<const float4*>(Y + (size_t)gr * O + gc);
+                        tv[0] = b.x; tv[1] = b.y; tv[2] = b.z; tv[3] = b.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gc + e < O) {
+                            zv[e] = p[e];
+                            if (LOSS == 1) tv[e] = Y[(size_t)gr * O + gc + e];
+                        }
+                }
+                if (LOSS == 0) {
+                    const float l = lse[gr];
+                    const int yy = y[gr];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gc + e < O) d[e] = (__expf(zv[e] - l) - (yy == gc + e ? 1.f : 0.f)) * scale;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gc + e < O) d[e] = (zv[e] - tv[e]) * scale;
+                }
+            }
+            float* dst = tile + row * TS + c4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { dst[e] = d[e]; cs[e] += d[e]; }
+        }
+        __syncthreads();
+        write_split_tile(tile, r0, c0, N, O, rm, tr, Op, Np);
+        __syncthreads();
+    }
+    // column sums: the 16 row lanes of a column meet in LDS, added in lane order
+    float* red = tile;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[(tid / 16) * 64 + c4 + e] = cs[e];
+    __syncthreads();
+    if (tid < 64 && c0 + tid < O) {
+        float sum = 0.f;
+        for (int r = 0; r < 16; ++r) sum += red[r * 64 + tid];
+        part[(size_t)blockIdx.x * O + c0 + tid] = sum;
     }
 }
 
@@ -417,6 +499,32 @@ hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* r
     if (grid.y > 65535u) return hipErrorInvalidValue;
     ProfileScope ps(K_SPLIT_BF16, s);
     hipLaunchKernelGGL(split_kernel, grid, dim3(256), 0, s, src, R, C, ld, rowmajor, transposed, Cp, Rp, vec);
+    return hipGetLastError();
+}
+
+// Z [N,O] -> d loss / d z in split form (as it is and transposed) plus per-chunk column sums in
+// part[chunks][O]; *chunks_out (<= colsum_chunks(N)) chunks are written.
+hipError_t launch_dz_split(const float* Z, const float* lse, const int32_t* y, const float* Y, float* part, int N,
+                           int O, int loss_kind, uint16_t* rowmajor, uint16_t* transposed, int* chunks_out,
+                           hipStream_t s) {
+    const int Op = bf3_pad(O), Np = bf3_pad(N);
+    const int chunks = colsum_chunks(N);
+    int rpg = (N + chunks - 1) / chunks;
+    rpg = (rpg + 63) / 64 * 64;
+    const int used = (Np + rpg - 1) / rpg;          // covers the zero pad rows of the transposed form too
+    *chunks_out = used;
+    const int vec = (O % 4 == 0 && (reinterpret_cast<uintptr_t>(Z) & 15u) == 0 &&
+                     (loss_kind == 0 || (reinterpret_cast<uintptr_t>(Y) & 15u) == 0)) ? 1 : 0;
+    dim3 grid(used, (Op + 63) / 64);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    const float scale = loss_kind == 0 ? 1.0f / (float)N : (float)(2.0 / ((double)N * (double)O));
+    ProfileScope ps(K_DZ, s);
+    if (loss_kind == 0)
+        hipLaunchKernelGGL(dz_split_kernel<0>, grid, dim3(256), 0, s, Z, lse, y, Y, part, N, O, scale, rowmajor,
+                           transposed, Op, Np, rpg, vec);
+    else
+        hipLaunchKernelGGL(dz_split_kernel<1>, grid, dim3(256), 0, s, Z, lse, y, Y, part, N, O, scale, rowmajor,
+                           transposed, Op, Np, rpg, vec);
     return hipGetLastError();
 }
 

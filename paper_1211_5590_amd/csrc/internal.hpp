@@ -60,6 +60,10 @@ bool bf3_fuses_stats(int M, int N, int K);
 hipError_t launch_split_bf16(const float* src, int R, int C, int ld, uint16_t* rowmajor, uint16_t* transposed,
                              hipStream_t s);
 hipError_t launch_gemm_bf16x3(const Bf3Args& g, hipStream_t s);
+// logits -> d loss / d z directly in split form (both orientations) + per-chunk column sums for dc
+hipError_t launch_dz_split(const float* Z, const float* lse, const int32_t* y, const float* Y, float* part, int N,
+                           int O, int loss_kind, uint16_t* rowmajor, uint16_t* transposed, int* chunks_out,
+                           hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // Recurrence (forward and reverse-time loops)
