@@ -464,6 +464,21 @@ def mlp_leg(n_batches=400, lr=0.01):
     return out
 
 
+def mlp_cpu_baseline(seconds=3.0):
+    """The classifier oracle (float64 numpy) timed on the host cores: three hidden layers, batch 60."""
+    import rnn_inputs as ri
+    from oracle import mlp
+    case = ri.make_mlp_config("MLP3", 60, n_batches=4)
+    t0 = time.perf_counter()
+    done = 0
+    while done < 1 or time.perf_counter() - t0 < seconds:
+        mlp.train(case, 0.01, n_batches=4)
+        done += 4
+    dt = time.perf_counter() - t0
+    return dict(value=done * 60 / dt, unit="examples/s", kind="oracle", cores=os.cpu_count(),
+                sample=f"{done} batches of 60, 784-1000-1000-1000-10, float64 numpy", seconds=dt)
+
+
 def gauss_newton_leg(names=("C3", "C4", "C5"), reps=5, flags=0):
     """One Gauss-Newton-vector product (R-operator sweep, loss metric, reverse sweep) per call of
     rnn_gauss_newton_vec on the named configurations, with the states of one forward pass:
@@ -626,6 +641,8 @@ def main():
 
     if a.workload == "C2" and not a.no_mlp and not a.reference_kernels and not a.bf16x3:
         out["mlp_workloads"] = mlp_leg()
+        if not a.no_cpu_baseline:
+            out["mlp_workloads"]["cpu_baseline"] = mlp_cpu_baseline()
     if a.workload == "C2" and per and not a.reference_kernels and not a.bf16x3:
         out["gauss_newton_vec"] = gauss_newton_leg([n for n in ("C3", "C4", "C5") if n in per])
         if "C4" in per:
