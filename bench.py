@@ -255,8 +255,17 @@ def on_chip_roofline(name, us, c):
                 flops=flops)
 
 
+MEASURED = {}   # filled by main(): the chip's measured ceilings (rnn_measure_ceilings)
+
+
 def roofline_entry(name, prof, case):
     r = _roofline_entry(name, prof, case)
+    if MEASURED and r.get("achieved") is not None:
+        key = ("hbm_copy_GBps" if r["bound"] == "hbm" else
+               "mfma_bf16_TFLOPs" if r.get("dtype", "").startswith("bf16") else "mfma_f32_TFLOPs")
+        peak = max(MEASURED[key], MEASURED["hbm_read_GBps"]) if key == "hbm_copy_GBps" else MEASURED[key]
+        r["peak_measured"] = peak
+        r["frac_measured"] = (r.get("frac_executed", r["frac"]) * r["peak"]) / peak
     oc = on_chip_roofline(name, prof[name]["avg_us"], case)
     if oc:
         r["on_chip"] = oc
@@ -543,6 +552,10 @@ def main():
         print(json.dumps({"metric": "classifier training examples/sec", "unit": "examples/s", "n_gpus": 1,
                           "dtype": "f32", "data": "synthetic", "mlp_workloads": mlp_leg()}))
         return
+    scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    MEASURED.update(rnn.rnn_measure_ceilings(scratch))
+    del scratch
+    torch.cuda.empty_cache()
     flags = rnn.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     if a.bf16x3:
         flags |= rnn.FLAG_BF16X3_OUTPUT
@@ -585,6 +598,10 @@ def main():
                             avg_us_raw=round(v["avg_us_raw"], 3),
                             total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
         "event_bracket_us": round(wl.bracket_us, 3),
+        "measured_ceilings": dict(MEASURED, note="saturating kernels of the library itself on this GPU: "
+                                  "device-memory copy (read + written bytes) and read (the larger is the HBM ceiling), 32x32x2 f32 and 32x32x16 bf16 "
+                                  "matrix products, 16-byte LDS reads; frac_measured in the roofline entries "
+                                  "is stated against these, frac against the published peaks"),
     }
     fused_headline = wl.fused
     del wl

@@ -311,8 +311,8 @@ const char *rnn_recurrence_variant(const rnn_dims *dims);
 int rnn_recurrence_workgroups(const rnn_dims *dims);
 
 /*
- * Per-kernel timing for roofline reports (the paper keeps a synchronous mode "for profiling
- * execution time of the different GPU kernels"; this is the asynchronous equivalent).  Between
+ * Per-kernel timing for roofline reports (the paper's GPU backend has a synchronous mode for
+ * timing each kernel, section on the CUDA backend; this is the asynchronous equivalent).  Between
  * rnn_profile_begin and rnn_profile_end every kernel the library launches is bracketed by two
  * HIP events on its stream (at most max_launches launches are recorded, later ones are not).
  * rnn_profile_end waits for the recorded events and fills counts[k] / total_ms[k] (host arrays
@@ -323,6 +323,20 @@ int rnn_profile_begin(int max_launches);
 int rnn_profile_end(int n_kernels, int64_t *counts, double *total_ms);
 int rnn_profile_kernel_count(void);
 const char *rnn_profile_kernel_name(int kernel_id);
+
+/*
+ * Measured ceilings of the device the calling thread has current, for roofline reports beside
+ * the published peaks (not an operation of the paper).  Runs four saturating kernels on
+ * `stream` and waits for them: results_host[0] = device-memory copy rate in GB/s (bytes read +
+ * bytes written), [1] = fp32 matrix-core rate in TFLOP/s (32x32x2 products), [2] = bf16
+ * matrix-core rate in TFLOP/s (32x32x16 products), [3] = LDS read rate in GB/s (16-byte reads,
+ * all compute units), [4] = device-memory read rate in GB/s.  `scratch` is device memory the caller owns (16-byte aligned, at least
+ * 128 MiB; the copy moves min(scratch_bytes / 2, 1 GiB) from its first half to its second, and
+ * the contents are overwritten); results_host is a host array of 5 doubles.  Allocates no
+ * device memory; creates and destroys two HIP events.  RNN_EINVAL on a null, misaligned or
+ * short scratch, RNN_EHIP if a HIP call fails.
+ */
+int rnn_measure_ceilings(void *scratch, size_t scratch_bytes, double *results_host, void *stream);
 
 #ifdef __cplusplus
 }

@@ -7,7 +7,7 @@ is missing.
 from .binding import (  # noqa: F401
     ACT_SIGMOID, ACT_TANH, FLAG_ACCUMULATE, FLAG_BF16X3_OUTPUT, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS, FLAG_SYNC,
     INPUT_DENSE, INPUT_TOKENS, LOSS_LINEAR_MSE, LOSS_SOFTMAX_CE, Dims, Grads, Params, RnnError,
-    exported_symbols, lib, lib_path, rnn_bptt, rnn_check_tokens, rnn_forward, rnn_loss,
+    exported_symbols, lib, lib_path, rnn_bptt, rnn_check_tokens, rnn_forward, rnn_loss, rnn_measure_ceilings,
     rnn_profile_begin, rnn_profile_end, rnn_recurrence_variant, rnn_recurrence_workgroups, rnn_strerror,
     rnn_workspace_bytes, rnn_workspace_init, rnn_workspace_status,
     rnn_train_stream, rnn_train_stream_status, rnn_train_stream_workspace_bytes,

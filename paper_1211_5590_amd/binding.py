@@ -24,7 +24,7 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
            "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
            "rnn_window", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
-           "rnn_mlp_workspace_bytes", "rnn_mlp_train")
+           "rnn_mlp_workspace_bytes", "rnn_mlp_train", "rnn_measure_ceilings")
 MLP_MAX_LAYERS = 16
 GN_METRIC_LOSS, GN_METRIC_IDENTITY = 0, 1
 
@@ -124,7 +124,8 @@ def lib():
         L.rnn_mlp_workspace_bytes.argtypes = [ctypes.POINTER(MlpDims), ctypes.POINTER(sz)]
         L.rnn_mlp_train.argtypes = [ctypes.POINTER(MlpDims), ctypes.POINTER(MlpParams), vp, vp, ctypes.c_int64,
                                     ctypes.c_float, vp, vp, sz, vp]
-        for name in ("rnn_mlp_workspace_bytes", "rnn_mlp_train"):
+        L.rnn_measure_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+        for name in ("rnn_mlp_workspace_bytes", "rnn_mlp_train", "rnn_measure_ceilings"):
             getattr(L, name).restype = ctypes.c_int
         for name in ("rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec"):
             getattr(L, name).restype = ctypes.c_int
@@ -279,6 +280,15 @@ def rnn_check_tokens(ids, n, limit, bad_count, stream=None, check=True):
     if check:
         _check(rc)
     return rc
+
+
+def rnn_measure_ceilings(scratch, stream=None) -> dict:
+    """Measured device-memory, matrix-core and LDS rates of the current device (scratch: a device
+    tensor of at least 128 MiB that may be overwritten)."""
+    res = (ctypes.c_double * 5)()
+    _check(lib().rnn_measure_ceilings(_p(scratch), scratch.numel() * scratch.element_size(), res, _stream(stream)))
+    return {"hbm_copy_GBps": res[0], "mfma_f32_TFLOPs": res[1], "mfma_bf16_TFLOPs": res[2], "lds_read_GBps": res[3],
+            "hbm_read_GBps": res[4]}
 
 
 def rnn_profile_begin(max_launches: int = 1 << 16) -> None:

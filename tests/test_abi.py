@@ -174,3 +174,13 @@ def test_split_product_flag_is_taken_only_where_it_applies():
     assert L.rnn_window_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == -1
     assert L.rnn_train_stream_workspace_bytes(ctypes.byref(d), ctypes.byref(n)) == -1
     assert rnn.rnn_gauss_newton_workspace_bytes(d) > rnn.rnn_gauss_newton_workspace_bytes(good_dims())
+
+
+def test_measure_ceilings_rejects_bad_arguments_without_a_gpu():
+    L = rnn.lib()
+    res = (ctypes.c_double * 5)()
+    fake = 0x100000
+    assert L.rnn_measure_ceilings(None, 1 << 30, res, None) == -1
+    assert L.rnn_measure_ceilings(fake, 1 << 30, None, None) == -1
+    assert L.rnn_measure_ceilings(fake, (128 << 20) - 1, res, None) == -1     # scratch too short
+    assert L.rnn_measure_ceilings(fake + 8, 1 << 30, res, None) == -1       # misaligned

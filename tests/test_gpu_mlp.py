@@ -88,3 +88,4 @@ def test_split_calls_equal_one_call():
     assert np.array_equal(losses.cpu().numpy(), whole["losses"])
     for l in range(2):
         assert np.array_equal(W[l].cpu().numpy(), whole["W"][l])
+
