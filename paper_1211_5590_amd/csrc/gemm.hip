@@ -8,9 +8,13 @@
 // wavefront owns (BM/2) x (BN/2) as 32x32 MFMA blocks held in accumulation registers.
 // K advances in slabs of 16 through two LDS buffers: the next slab is fetched from global
 // memory into registers while the current one feeds the MFMAs, then parked in the other
-// buffer (one barrier per slab).  LDS keeps both operands K-major ([k][row]) so the MFMA
-// operand fetch of a wavefront (lane -> row = lane%32, k = lane/32) reads 32 consecutive
-// words per half-wave.
+// buffer (one barrier per slab).  An operand whose K runs along memory keeps that order in LDS
+// ([row][16 k], 16-byte chunks XOR-swizzled by row so that both the 16-byte stores and the 16-byte
+// fragment reads are conflict-free); an operand stored K-major stays K-major ([k][row], scalar
+// fragment reads of 32 consecutive words per half-wave).  A wavefront walks the 16 k of a slab
+// in the order k = 8j + 4(lane/32) + e, the same for both operands, so that one 16-byte read
+// feeds four matrix instructions (plain k order when both operands are K-major).  Interior tiles fetch whole slabs with one uniform base per slab
+// and loop-invariant per-lane offsets; only edge tiles and a ragged last slab take the checked path.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
@@ -48,21 +52,45 @@ template <int R, bool KCONTIG, bool VEC>
 struct TileLoader {
     static constexpr int NV4 = R * BK / 4 / NT;  // float4 per thread
     float4 v[NV4];
+    unsigned off[NV4];   // interior tiles: element offset of this lane's float4 from the slab's base
+    bool interior;       // uniform over the workgroup: every row of the tile exists, 16-byte loads legal
 
-    __device__ __forceinline__ void load(const float* __restrict__ src, int ld, int r0, int k0,
-                                         int rlim, int klim, int tid) {
+    __device__ __forceinline__ static void coords(int i, int tid, int& r, int& k) {
+        if (KCONTIG) {
+            r = tid / 4 + (NT / 4) * i;
+            k = (tid % 4) * 4;
+        } else {
+            constexpr int Q = R / 4;  // float4 per k-row
+            const int idx = tid + NT * i;
+            k = idx / Q;
+            r = (idx % Q) * 4;
+        }
+    }
+
+    __device__ __forceinline__ void init(int ld, int r0, int rlim, int tid) {
+        interior = VEC && r0 + R <= rlim;
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
             int r, k;
-            if (KCONTIG) {
-                r = tid / 4 + (NT / 4) * i;
-                k = (tid % 4) * 4;
-            } else {
-                constexpr int Q = R / 4;  // float4 per k-row
-                const int idx = tid + NT * i;
-                k = idx / Q;
-                r = (idx % Q) * 4;
-            }
+            coords(i, tid, r, k);
+            off[i] = KCONTIG ? (unsigned)r * (unsigned)ld + (unsigned)k : (unsigned)k * (unsigned)ld + (unsigned)r;
+        }
+    }
+
+    // One slab into registers, to be parked by store().  Interior tiles and whole slabs: one
+    // uniform base per slab, loop-invariant lane offsets, no checks; otherwise every limit checked.
+    __device__ __forceinline__ void load(const float* __restrict__ src, int ld, int r0, int k0,
+                                         int rlim, int klim, int tid) {
+        if (interior && k0 + BK <= klim) {
+            const float* base = KCONTIG ? src + (size_t)r0 * ld + k0 : src + (size_t)k0 * ld + r0;
+#pragma unroll
+            for (int i = 0; i < NV4; ++i) v[i] = *reinterpret_cast<const float4*>(base + off[i]);
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            int r, k;
+            coords(i, tid, r, k);
             const int gr = r0 + r, gk = k0 + k;
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
             if (KCONTIG) {
@@ -94,25 +122,23 @@ struct TileLoader {
         }
     }
 
-    // LDS tile layout: S[k][r], row stride R + PAD
+    // LDS tile layout: KCONTIG S[r][16] with the 4-float chunk c of row r at position
+    // c ^ ((r >> 1) & 3); otherwise S[k][r] with row stride R + PAD
     __device__ __forceinline__ void store(float* __restrict__ S, int tid) const {
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
-            if (KCONTIG) {
-                const int r = tid / 4 + (NT / 4) * i;
-                const int k = (tid % 4) * 4;
-                S[(k + 0) * (R + PAD) + r] = v[i].x;
-                S[(k + 1) * (R + PAD) + r] = v[i].y;
-                S[(k + 2) * (R + PAD) + r] = v[i].z;
-                S[(k + 3) * (R + PAD) + r] = v[i].w;
-            } else {
-                constexpr int Q = R / 4;
-                const int idx = tid + NT * i;
-                const int k = idx / Q;
-                const int r = (idx % Q) * 4;
-                *reinterpret_cast<float4*>(&S[k * (R + PAD) + r]) = v[i];
-            }
+            int r, k;
+            coords(i, tid, r, k);
+            if (KCONTIG) *reinterpret_cast<float4*>(&S[r * BK + 4 * ((k / 4) ^ ((r >> 1) & 3))]) = v[i];
+            else *reinterpret_cast<float4*>(&S[k * (R + PAD) + r]) = v[i];
         }
+    }
+
+    // the four values k = 8j + 4g + e (e = 0..3) of tile row `row`
+    __device__ __forceinline__ static float4 fragment(const float* __restrict__ S, int row, int j, int g) {
+        if (KCONTIG) return *reinterpret_cast<const float4*>(&S[row * BK + 4 * ((2 * j + g) ^ ((row >> 1) & 3))]);
+        const float* q = S + (8 * j + 4 * g) * (R + PAD) + row;
+        return make_float4(q[0], q[R + PAD], q[2 * (R + PAD)], q[3 * (R + PAD)]);
     }
 };
 
@@ -162,6 +188,12 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    const int arow = wm * (BM / 2) + lane % 32;
+    const int brow = wn * (BN / 2) + lane % 32;
+    const int ksub = lane / 32;
+
+    la.init(p.lda, m0, p.M, tid);
+    lb.init(p.ldb, n0, p.N, tid);
     if (nk > 0) {
         la.load(p.A, p.lda, m0, kbeg, p.M, kend, tid);
         lb.load(p.B, p.ldb, n0, kbeg, p.N, kend, tid);
@@ -169,10 +201,6 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         lb.store(Bs[0], tid);
     }
     __syncthreads();
-
-    const int arow = wm * (BM / 2) + lane % 32;
-    const int brow = wn * (BN / 2) + lane % 32;
-    const int ksub = lane / 32;
 
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
@@ -183,18 +211,44 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         }
         const float* as = As[cur];
         const float* bs = Bs[cur];
+        if constexpr (!AT || BT) {
+            // both halves of the slab's fragments are requested before the first product
+            float4 a[2][TM], b[2][TN];
 #pragma unroll
-        for (int kk = 0; kk < BK / 2; ++kk) {
-            float a[TM], b[TN];
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + ksub) * (BM + PAD) + arow + 32 * i];
+                for (int i = 0; i < TM; ++i) a[j][i] = TileLoader<BM, !AT, VEC>::fragment(as, arow + 32 * i, j, ksub);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + ksub) * (BN + PAD) + brow + 32 * j];
+                for (int i = 0; i < TN; ++i) b[j][i] = TileLoader<BN, BT, VEC>::fragment(bs, brow + 32 * i, j, ksub);
+            }
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < TN; ++jj) {
+                            const float av = e == 0 ? a[j][i].x : e == 1 ? a[j][i].y : e == 2 ? a[j][i].z : a[j][i].w;
+                            const float bv = e == 0 ? b[j][jj].x : e == 1 ? b[j][jj].y : e == 2 ? b[j][jj].z : b[j][jj].w;
+                            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][jj], 0, 0, 0);
+                        }
+            }
+        } else {
+            // both operands K-major in LDS: plain k order, two rows of K per product
+#pragma unroll
+            for (int kk = 0; kk < BK / 2; ++kk) {
+                float a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + ksub) * (BM + PAD) + arow + 32 * i];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + ksub) * (BN + PAD) + brow + 32 * j];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
         }
         if (more) {
             la.store(As[cur ^ 1], tid);
