@@ -13,8 +13,9 @@
 // fragment reads are conflict-free); an operand stored K-major stays K-major ([k][row], scalar
 // fragment reads of 32 consecutive words per half-wave).  A wavefront walks the 16 k of a slab
 // in the order k = 8j + 4(lane/32) + e, the same for both operands, so that one 16-byte read
-// feeds four matrix instructions (plain k order when both operands are K-major).  Interior tiles fetch whole slabs with one uniform base per slab
-// and loop-invariant per-lane offsets; only edge tiles and a ragged last slab take the checked path.
+// feeds four matrix instructions (plain k order when both operands are K-major).  Interior tiles
+// fetch whole slabs with one uniform base per slab and loop-invariant per-lane offsets; only edge
+// tiles and a ragged last slab take the checked path.
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
