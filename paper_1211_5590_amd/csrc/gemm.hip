@@ -1,19 +1,19 @@
-// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32), used for every product that
+// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_16x16x4_f32), used for every product that
 // the path batches over time outside the loop (the paper's Scan property 8: per-step
 // vector-matrix products become one matrix-matrix product): the output projection Z = H V + c,
 // its two backward products dV = H^T dZ and G = dZ V^T, the recurrent weight gradient
 // dWh = Delta^T H_prev, and the dense-input projections.
 //
 // Tiling: a 256-thread workgroup (4 wavefronts as 2x2) owns a BM x BN tile of C; each
-// wavefront owns (BM/2) x (BN/2) as 32x32 MFMA blocks held in accumulation registers.
+// wavefront owns (BM/2) x (BN/2) as 16x16 MFMA blocks held in accumulation registers.
 // K advances in slabs of 16 through two LDS buffers: the next slab is fetched from global
 // memory into registers while the current one feeds the MFMAs, then parked in the other
 // buffer (one barrier per slab).  An operand whose K runs along memory keeps that order in LDS
 // ([row][16 k], 16-byte chunks XOR-swizzled by row so that both the 16-byte stores and the 16-byte
 // fragment reads are conflict-free); an operand stored K-major stays K-major ([k][row], scalar
-// fragment reads of 32 consecutive words per half-wave).  A wavefront walks the 16 k of a slab
-// in the order k = 8j + 4(lane/32) + e, the same for both operands, so that one 16-byte read
-// feeds four matrix instructions (plain k order when both operands are K-major).  Interior tiles
+// fragment reads of 16 consecutive words per quarter-wave).  A wavefront walks the 16 k of a slab
+// in the order k = 4(lane/16) + e, the same for both operands, so that one 16-byte read feeds
+// four matrix instructions.  Interior tiles
 // fetch whole slabs with one uniform base per slab and loop-invariant per-lane offsets; only edge
 // tiles and a ragged last slab take the checked path.
 #include "common.hpp"
@@ -25,7 +25,7 @@
 namespace rnn {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 16;
 constexpr int PAD = 4;
@@ -135,10 +135,10 @@ struct TileLoader {
         }
     }
 
-    // the four values k = 8j + 4g + e (e = 0..3) of tile row `row`
-    __device__ __forceinline__ static float4 fragment(const float* __restrict__ S, int row, int j, int g) {
-        if (KCONTIG) return *reinterpret_cast<const float4*>(&S[row * BK + 4 * ((2 * j + g) ^ ((row >> 1) & 3))]);
-        const float* q = S + (8 * j + 4 * g) * (R + PAD) + row;
+    // the four values k = 4g + e (e = 0..3) of tile row `row`
+    __device__ __forceinline__ static float4 fragment(const float* __restrict__ S, int row, int g) {
+        if (KCONTIG) return *reinterpret_cast<const float4*>(&S[row * BK + 4 * (g ^ ((row >> 1) & 3))]);
+        const float* q = S + 4 * g * (R + PAD) + row;
         return make_float4(q[0], q[R + PAD], q[2 * (R + PAD)], q[3 * (R + PAD)]);
     }
 };
@@ -163,7 +163,7 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
 
 template <int BM, int BN, bool AT, bool BT, bool VEC, bool STATS>
 __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
-    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA blocks per wavefront, per dim
+    constexpr int TM = BM / 32, TN = BN / 32;  // 16x16 MFMA blocks per wavefront, per dim
     __shared__ __attribute__((aligned(16))) float As[2][BK * (BM + PAD)];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * (BN + PAD)];
 
@@ -181,17 +181,19 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
     TileLoader<BM, !AT, VEC> la;
     TileLoader<BN, BT, VEC> lb;
 
-    f32x16 acc[TM][TN];
+    f32x4v acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int j = 0; j < TN; ++j) acc[i][j] = (f32x4v){0.f, 0.f, 0.f, 0.f};
 
-    const int arow = wm * (BM / 2) + lane % 32;
-    const int brow = wn * (BN / 2) + lane % 32;
-    const int ksub = lane / 32;
+    // v_mfma_f32_16x16x4_f32: lane l supplies A[row l%16][k l/16] and B[k l/16][col l%16] and
+    // receives C[row 4(l/16) + e][col l%16] in register e.  The 16 k of a slab are walked as
+    // k = 4(l/16) + e over four instructions e = 0..3, the same for both operands, so one
+    // 16-byte read of a K-ordered tile row feeds all four.
+    const int arow = wm * (BM / 2) + lane % 16;
+    const int brow = wn * (BN / 2) + lane % 16;
+    const int g = lane / 16;
 
     la.init(p.lda, m0, p.M, tid);
     lb.init(p.ldb, n0, p.N, tid);
@@ -212,45 +214,21 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         }
         const float* as = As[cur];
         const float* bs = Bs[cur];
-        if constexpr (!AT || BT) {
-            // both halves of the slab's fragments are requested before the first product
-            float4 a[2][TM], b[2][TN];
+        float4 fa[TM], fb[TN];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+        for (int i = 0; i < TM; ++i) fa[i] = TileLoader<BM, !AT, VEC>::fragment(as, arow + 16 * i, g);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a[j][i] = TileLoader<BM, !AT, VEC>::fragment(as, arow + 32 * i, j, ksub);
+        for (int j = 0; j < TN; ++j) fb[j] = TileLoader<BN, BT, VEC>::fragment(bs, brow + 16 * j, g);
 #pragma unroll
-                for (int i = 0; i < TN; ++i) b[j][i] = TileLoader<BN, BT, VEC>::fragment(bs, brow + 32 * i, j, ksub);
-            }
+        for (int e = 0; e < 4; ++e)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int jj = 0; jj < TN; ++jj) {
-                            const float av = e == 0 ? a[j][i].x : e == 1 ? a[j][i].y : e == 2 ? a[j][i].z : a[j][i].w;
-                            const float bv = e == 0 ? b[j][jj].x : e == 1 ? b[j][jj].y : e == 2 ? b[j][jj].z : b[j][jj].w;
-                            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][jj], 0, 0, 0);
-                        }
-            }
-        } else {
-            // both operands K-major in LDS: plain k order, two rows of K per product
-#pragma unroll
-            for (int kk = 0; kk < BK / 2; ++kk) {
-                float a[TM], b[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + ksub) * (BM + PAD) + arow + 32 * i];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + ksub) * (BN + PAD) + brow + 32 * j];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-            }
-        }
+                for (int j = 0; j < TN; ++j) {
+                    const float av = e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w;
+                    const float bv = e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w;
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[i][j], 0, 0, 0);
+                }
         if (more) {
             la.store(As[cur ^ 1], tid);
             lb.store(Bs[cur ^ 1], tid);
@@ -258,20 +236,18 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         __syncthreads();
     }
 
-    // Accumulator layout of the 32x32 block: lane -> column lane%32; register e -> row
-    // 8*(e/4) + 4*(lane/32) + e%4.
     float* Cout = p.C + (p.splits > 1 ? (size_t)blockIdx.z * p.M * p.ldc : 0);
     const bool final_out = p.splits == 1;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (BN / 2) + 32 * j + lane % 32;
+            const int col = n0 + wn * (BN / 2) + 16 * j + lane % 16;
             if (col >= p.N) continue;
             const float bias = (final_out && p.bias_n) ? p.bias_n[col] : 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * (BM / 2) + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
+            for (int e = 0; e < 4; ++e) {
+                const int row = m0 + wm * (BM / 2) + 16 * i + 4 * g + e;
                 if (row < p.M) {
                     float* dst = Cout + (size_t)row * p.ldc + col;
                     float v = acc[i][j][e] + bias;
@@ -282,8 +258,8 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         }
 
     // Fused row statistics of a log-sum-exp over the columns: every wavefront leaves, for each of
-    // its rows, the maximum of its 64 columns and the sum of exponentials relative to it (the 32
-    // lanes of a half-wave hold 32 columns of the same row in every accumulator register).
+    // its rows, the maximum of its 64 columns and the sum of exponentials relative to it (the 16
+    // lanes of a quarter-wave hold 16 columns of the same row in register e of every block j).
     if (STATS && final_out) {
         const int nparts = p.tiles_n * 2;
         const int part = tile_n * 2 + wn;
@@ -291,13 +267,13 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
         float bias[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            col[j] = n0 + wn * (BN / 2) + 32 * j + lane % 32;
+            col[j] = n0 + wn * (BN / 2) + 16 * j + lane % 16;
             bias[j] = (p.bias_n && col[j] < p.N) ? p.bias_n[col[j]] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
+            for (int e = 0; e < 4; ++e) {
                 float v[TN];
                 float m = -INFINITY;
 #pragma unroll
@@ -305,14 +281,14 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmParams p) {
                     v[j] = acc[i][j][e] + bias[j];
                     if (col[j] < p.N) m = fmaxf(m, v[j]);
                 }
-                m = max32(m);   // register-to-register lane exchanges: no LDS round trips in the chain
+                m = max16(m);   // register-to-register lane exchanges: no LDS round trips in the chain
                 float sum = 0.f;
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     if (col[j] < p.N) sum += __expf(v[j] - m);
-                sum = sum32(sum);
-                const int row = m0 + wm * (BM / 2) + 32 * i + 8 * (e / 4) + 4 * (lane / 32) + e % 4;
-                if (lane % 32 == 0 && row < p.M)
+                sum = sum16(sum);
+                const int row = m0 + wm * (BM / 2) + 16 * i + 4 * g + e;
+                if (lane % 16 == 0 && row < p.M)
                     *reinterpret_cast<float2*>(p.stats + ((size_t)row * nparts + part) * 2) = make_float2(m, sum);
             }
     }
