@@ -124,20 +124,20 @@ struct TileLoader {
     }
 
     // LDS tile layout: KCONTIG S[r][16] with the 4-float chunk c of row r at position
-    // c ^ ((r >> 1) & 3); otherwise S[k][r] with row stride R + PAD
+    // c ^ ((r >> 2) & 3); otherwise S[k][r] with row stride R + PAD
     __device__ __forceinline__ void store(float* __restrict__ S, int tid) const {
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
             int r, k;
             coords(i, tid, r, k);
-            if (KCONTIG) *reinterpret_cast<float4*>(&S[r * BK + 4 * ((k / 4) ^ ((r >> 1) & 3))]) = v[i];
+            if (KCONTIG) *reinterpret_cast<float4*>(&S[r * BK + 4 * ((k / 4) ^ ((r >> 2) & 3))]) = v[i];
             else *reinterpret_cast<float4*>(&S[k * (R + PAD) + r]) = v[i];
         }
     }
 
     // the four values k = 4g + e (e = 0..3) of tile row `row`
     __device__ __forceinline__ static float4 fragment(const float* __restrict__ S, int row, int g) {
-        if (KCONTIG) return *reinterpret_cast<const float4*>(&S[row * BK + 4 * (g ^ ((row >> 1) & 3))]);
+        if (KCONTIG) return *reinterpret_cast<const float4*>(&S[row * BK + 4 * (g ^ ((row >> 2) & 3))]);
         const float* q = S + 4 * g * (R + PAD) + row;
         return make_float4(q[0], q[R + PAD], q[2 * (R + PAD)], q[3 * (R + PAD)]);
     }
