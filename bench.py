@@ -341,6 +341,20 @@ def cpu_baseline(name, budget_s):
         dt = time.perf_counter() - t0
         tokens = done * cfg["seq_len"] * cfg["batch"]
         sample = f"first {done} windows of the stream (state carried), forward+loss+BPTT each"
+        # the same oracle on one thread, on a shorter sample of the same stream
+        oracle.set_num_threads(1)
+        t1 = time.perf_counter()
+        h, done1 = None, 0
+        while done1 < cap and (done1 < 4 or time.perf_counter() - t1 < min(3.0, budget_s)):
+            r = oracle.fwd_bptt(ri.window(case, done1), h0=h)
+            h = r["h_all"][-1]
+            done1 += 1
+        dt1 = time.perf_counter() - t1
+        oracle.set_num_threads(cores)
+        one = dict(value=done1 * cfg["seq_len"] * cfg["batch"] / dt1, unit="tokens/s", cores=1,
+                   sample=f"first {done1} windows", seconds=dt1)
+        return dict(value=tokens / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample,
+                    seconds=dt, one_thread=one)
     else:
         # shrink T (and B) until the estimated double-precision work fits the budget
         T, B = cfg["seq_len"], cfg["batch"]
@@ -605,6 +619,10 @@ def main():
                             avg_us_raw=round(v["avg_us_raw"], 3),
                             total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
         "event_bracket_us": round(wl.bracket_us, 3),
+        "device": (lambda pr: dict(name=pr.name, arch=getattr(pr, "gcnArchName", None),
+                                   compute_units=pr.multi_processor_count, memory_bytes=pr.total_memory,
+                                   clock_mhz=getattr(pr, "clock_rate", 0) / 1e3 or None,
+                                   l2_bytes=getattr(pr, "L2_cache_size", None)))(torch.cuda.get_device_properties(0)),
         "measured_ceilings": dict(MEASURED, note="saturating kernels of the library itself on this GPU: "
                                   "device-memory copy (read + written bytes) and read (the larger is the HBM ceiling), 32x32x2 f32 and 32x32x16 bf16 "
                                   "matrix products, 16-byte LDS reads; frac_measured in the roofline entries "
