@@ -558,6 +558,13 @@ def describe(c):
                 loss="softmax-CE" if c["loss_kind"] == 0 else "linear-MSE")
 
 
+def device_facts(torch):
+    """What the runtime reports about the GPU the numbers were taken on."""
+    pr = torch.cuda.get_device_properties(0)
+    return dict(name=pr.name, arch=getattr(pr, "gcnArchName", None), compute_units=pr.multi_processor_count,
+                memory_bytes=pr.total_memory, l2_bytes=getattr(pr, "L2_cache_size", None))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -619,10 +626,7 @@ def main():
                             avg_us_raw=round(v["avg_us_raw"], 3),
                             total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
         "event_bracket_us": round(wl.bracket_us, 3),
-        "device": (lambda pr: dict(name=pr.name, arch=getattr(pr, "gcnArchName", None),
-                                   compute_units=pr.multi_processor_count, memory_bytes=pr.total_memory,
-                                   clock_mhz=getattr(pr, "clock_rate", 0) / 1e3 or None,
-                                   l2_bytes=getattr(pr, "L2_cache_size", None)))(torch.cuda.get_device_properties(0)),
+        "device": device_facts(torch),
         "measured_ceilings": dict(MEASURED, note="saturating kernels of the library itself on this GPU: "
                                   "device-memory copy (read + written bytes) and read (the larger is the HBM ceiling), 32x32x2 f32 and 32x32x16 bf16 "
                                   "matrix products, 16-byte LDS reads; frac_measured in the roofline entries "
