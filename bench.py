@@ -470,18 +470,18 @@ def mlp_leg(n_batches=400, lr=0.01):
             n_params = sum(w.numel() + v.numel() for w, v in zip(W, b))
             entry = dict(examples_per_s=n_batches * batch / wall, us_per_batch=1e6 * wall / n_batches,
                          gpu_event_us_per_batch=1e3 * e0.elapsed_time(e1) / n_batches,
-                         launches_per_batch=3 * case["n_hidden"] + 3, parameters=n_params,
+                         launches_per_batch=2 * case["n_hidden"] + 3, parameters=n_params,
                          loss_first=float(losses[0]), loss_last=float(losses[-1]))
             if name == "MLP3" and batch == 60:
                 rnn.rnn_profile_begin(1 << 16)
                 rnn.rnn_mlp_train(dims, pr, None, X, y, 50, lr, losses, ws)
                 prof = rnn.rnn_profile_end()
                 entry["kernels"] = {k: dict(launches=c, avg_us_raw=round(1e3 * ms / c, 3)) for k, (c, ms) in sorted(prof.items())}
-                # the update pass reads and rewrites every weight once: 8 bytes per parameter per launch set
+                # the update pass reads and rewrites every weight once: 8 bytes per parameter
                 upd = prof.get("mlp_update")
                 if upd:
                     us = 1e3 * upd[1] / upd[0]
-                    nbytes = 8.0 * n_params / (case["n_hidden"] + 1)
+                    nbytes = 8.0 * n_params          # one launch updates every layer
                     entry["roofline"] = dict(kernel="mlp_update", bound="hbm", achieved=nbytes / (us * 1e-6) / 1e9,
                                              peak=HBM_PEAK_GBS, unit="GB/s", frac=nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                              traffic=None, avg_us=us, algorithmic_bytes=nbytes,
@@ -489,7 +489,7 @@ def mlp_leg(n_batches=400, lr=0.01):
                                                  "frac_measured": nbytes / (us * 1e-6) / 1e9
                                                  / max(MEASURED["hbm_read_GBps"], MEASURED["hbm_copy_GBps"])}
                                                 if MEASURED else {}),
-                                             note="average over the layers' update launches; event bracket not removed")
+                                             note="one launch per batch updates all layers; event bracket not removed")
             out[f"{name}_batch{batch}"] = entry
     return out
 

@@ -6,14 +6,17 @@
 //     W_l <- W_l - lr dloss/dW_l,  b_l <- b_l - lr dloss/db_l      after every batch.
 //
 // At these sizes a step moves a few megabytes of weights and computes almost nothing, so what it
-// costs is launches and memory round trips.  A step is 3 L + 3 launches (L hidden layers), each
+// costs is launches and memory round trips.  A step is 2 L + 3 launches (L hidden layers: L + 1
+// forward, the loss, L backward, and ONE update of all layers), each
 // built like the batched recurrence's step kernel to pay one round trip: a workgroup owns a
 // 16 x 16 tile of the result, its 16 wavefronts split the contraction in slices of 64 and request
 // their whole share of both operands at once, straight into the lane registers
 // v_mfma_f32_16x16x4_f32 reads them from; the partial tiles meet in LDS once and the epilogue is
 // fused (bias + activation forward, activation derivative backward).  The update kernel forms
 // dW = dZ^T a in matrix-core tiles over the batch and applies it in place together with the
-// bias update, so gradients never exist in memory.  No atomics: results are run-to-run identical.
+// bias update, so weight gradients never exist in memory; all layers share that launch, which
+// is why every dZ_l is kept until the backward chain has ended.  No atomics: results are
+// run-to-run identical.
 #include "../../include/rnn.h"
 
 #include "common.hpp"
@@ -144,18 +147,38 @@ __global__ __launch_bounds__(MNT) void mlp_bwd_data_kernel(const float* __restri
 
 // W[n,k] -= lr sum_m dZ[m,n] Aprev[m,k];  b[n] -= lr sum_m dZ[m,n].
 // A wavefront owns 16 rows of W by 64 columns (four 16x16 tiles sharing the dZ operand) and walks
-// the batch four rows per matrix instruction; grid (ceil(Kin/256), ceil(Nout/16)), 256 threads.
+// the batch four rows per matrix instruction; per layer (ceil(Kin/256), ceil(Nout/16)) workgroups of 256 threads.
 // MB > 0: the batch has at most 16 MB rows and every operand (and the tile of W itself) is
 // requested before the first product, one memory round trip for the whole update; MB = 0: any batch.
+struct UpdateLayers {
+    const float* dZ[RNN_MLP_MAX_LAYERS];      // [M, Nout]
+    const float* Aprev[RNN_MLP_MAX_LAYERS];   // [M, Kin]
+    float* W[RNN_MLP_MAX_LAYERS];
+    float* b[RNN_MLP_MAX_LAYERS];
+    int Nout[RNN_MLP_MAX_LAYERS], Kin[RNN_MLP_MAX_LAYERS];
+    int gx[RNN_MLP_MAX_LAYERS];               // workgroups along Kin
+    int first[RNN_MLP_MAX_LAYERS + 1];        // first workgroup of the layer in the flat grid
+    int layers;
+};
+
+// One launch updates every layer: the flat grid is the layers' (ceil(Kin/256) x ceil(Nout/16)) grids
+// one after another (all dZ_l are kept until the backward chain has ended).
 template <int MB>
-__global__ __launch_bounds__(256) void mlp_update_kernel(const float* __restrict__ dZ, const float* __restrict__ Aprev,
-                                                         float* __restrict__ W, float* __restrict__ b, int M,
-                                                         int Nout, int Kin, float lr) {
+__global__ __launch_bounds__(256) void mlp_update_kernel(const UpdateLayers ul, int M, float lr) {
+    int l = 0;
+    while (l + 1 < ul.layers && (int)blockIdx.x >= ul.first[l + 1]) ++l;
+    const int local = blockIdx.x - ul.first[l];
+    const int bx = local % ul.gx[l], by = local / ul.gx[l];
+    const float* __restrict__ dZ = ul.dZ[l];
+    const float* __restrict__ Aprev = ul.Aprev[l];
+    float* __restrict__ W = ul.W[l];
+    float* __restrict__ b = ul.b[l];
+    const int Nout = ul.Nout[l], Kin = ul.Kin[l];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int q = lane / 16, r = lane % 16;
-    const int n0 = blockIdx.y * 16;
-    const int k0 = (blockIdx.x * 4 + wave) * 64;
-    if (blockIdx.x == 0 && wave == 0) {
+    const int n0 = by * 16;
+    const int k0 = (bx * 4 + wave) * 64;
+    if (bx == 0 && wave == 0) {
         // bias: lane (q, r) sums the rows m = q, q + 4, ... of column n0 + r; the four partial sums
         // of a column meet through lane exchanges in a fixed order
         float s = 0.f;
@@ -281,7 +304,7 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 // workspace: activations of the hidden layers, logits / dZ of the output layer, two dZ buffers of
 // the hidden width
-struct MlpPlan { size_t act[RNN_MLP_MAX_LAYERS + 1], Z, d0, d1, total; };
+struct MlpPlan { size_t act[RNN_MLP_MAX_LAYERS + 1], Z, dz[RNN_MLP_MAX_LAYERS], total; };
 
 MlpPlan mlp_plan(const rnn_mlp_dims* d) {
     const Widths w = widths_of(d);
@@ -290,8 +313,9 @@ MlpPlan mlp_plan(const rnn_mlp_dims* d) {
     auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
     for (int l = 1; l < w.layers; ++l) p.act[l] = take((size_t)d->batch * w.w[l] * 4);
     p.Z = take((size_t)d->batch * d->out_dim * 4);
-    p.d0 = take((size_t)d->batch * (d->n_hidden ? d->hidden : 1) * 4);
-    p.d1 = take((size_t)d->batch * (d->n_hidden ? d->hidden : 1) * 4);
+    // dZ of layer l's outputs, l < layers - 1 (the last layer's is Z itself, in place); at least one
+    // region: it also takes the loss when the caller wants none
+    for (int l = 0; l + 1 < w.layers || l == 0; ++l) p.dz[l] = take((size_t)d->batch * w.w[l + 1] * 4);
     p.total = off;
     return p;
 }
@@ -343,10 +367,25 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
     char* ws = static_cast<char*>(workspace);
     const int B = dims->batch, L = w.layers;
     float* Z = reinterpret_cast<float*>(ws + pl.Z);
-    float* dbuf[2] = {reinterpret_cast<float*>(ws + pl.d0), reinterpret_cast<float*>(ws + pl.d1)};
-    float* scratch_loss = dbuf[0];   // when the caller wants no losses (free until backpropagation starts)
+    float* scratch_loss = reinterpret_cast<float*>(ws + pl.dz[0]);   // when the caller wants no losses (free until backpropagation starts)
+    // the one update launch of a batch: every layer's grid, one after another
+    UpdateLayers ul{};
+    ul.layers = L;
+    int total_wgs = 0;
+    for (int l = 0; l < L; ++l) {
+        ul.dZ[l] = l + 1 < L ? reinterpret_cast<const float*>(ws + pl.dz[l]) : Z;
+        ul.W[l] = params->W[l];
+        ul.b[l] = params->b[l];
+        ul.Nout[l] = w.w[l + 1];
+        ul.Kin[l] = w.w[l];
+        ul.gx[l] = (w.w[l] + 255) / 256;
+        ul.first[l] = total_wgs;
+        total_wgs += ul.gx[l] * ((w.w[l + 1] + 15) / 16);
+    }
+    ul.first[L] = total_wgs;
     for (int64_t i = 0; i < n_batches; ++i) {
-        const float* a_prev = X + (size_t)i * B * dims->in_dim;
+        const float* x_in = X + (size_t)i * B * dims->in_dim;
+        const float* a_prev = x_in;
         // forward
         for (int l = 0; l < L; ++l) {
             float* out = l + 1 < L ? reinterpret_cast<float*>(ws + pl.act[l + 1]) : Z;
@@ -361,37 +400,33 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
                                losses ? losses + i : scratch_loss, B, dims->out_dim);
             if (hipGetLastError() != hipSuccess) return RNN_EHIP;
         }
-        // backward: layer l needs dZ_l; it first sends dZ_{l-1} down (with the weights before their
-        // update), then updates W_l and b_l in place
+        // backward: dZ_{l-1} from dZ_l and the weights as they were in the forward pass, layer by
+        // layer; every dZ_l is kept, and one launch then updates all W_l and b_l in place
         const float* dz = Z;
-        for (int l = L - 1; l >= 0; --l) {
-            const float* a_in = l > 0 ? reinterpret_cast<const float*>(ws + pl.act[l])
-                                      : X + (size_t)i * B * dims->in_dim;
-            float* dz_prev = dbuf[l & 1];
-            if (l > 0) {
-                dim3 grid((w.w[l] + 15) / 16, (B + 15) / 16);
-                ProfileScope ps(K_MLP_BWD, s);
-                const bool vec = w.w[l + 1] % 4 == 0;   // dZ rows stay 16-byte aligned (workspace regions are)
+        for (int l = L - 1; l > 0; --l) {
+            const float* a_in = reinterpret_cast<const float*>(ws + pl.act[l]);
+            float* dz_prev = reinterpret_cast<float*>(ws + pl.dz[l - 1]);
+            dim3 grid((w.w[l] + 15) / 16, (B + 15) / 16);
+            ProfileScope ps(K_MLP_BWD, s);
+            const bool vec = w.w[l + 1] % 4 == 0;   // dZ rows stay 16-byte aligned (workspace regions are)
 #define RNN_MLP_BWD(ACT, VEC)                                                                              \
     hipLaunchKernelGGL((mlp_bwd_data_kernel<ACT, VEC>), grid, dim3(MNT), 0, s, dz, params->W[l], a_in, dz_prev, \
                        B, w.w[l + 1], w.w[l])
-                if (dims->act == 0) { if (vec) RNN_MLP_BWD(0, true); else RNN_MLP_BWD(0, false); }
-                else { if (vec) RNN_MLP_BWD(1, true); else RNN_MLP_BWD(1, false); }
+            if (dims->act == 0) { if (vec) RNN_MLP_BWD(0, true); else RNN_MLP_BWD(0, false); }
+            else { if (vec) RNN_MLP_BWD(1, true); else RNN_MLP_BWD(1, false); }
 #undef RNN_MLP_BWD
-                if (hipGetLastError() != hipSuccess) return RNN_EHIP;
-            }
-            {
-                dim3 grid((w.w[l] + 255) / 256, (w.w[l + 1] + 15) / 16);
-                ProfileScope ps(K_MLP_UPDATE, s);
-#define RNN_MLP_UPD(MB)                                                                                    \
-    hipLaunchKernelGGL(mlp_update_kernel<MB>, grid, dim3(256), 0, s, dz, a_in, params->W[l], params->b[l], B, \
-                       w.w[l + 1], w.w[l], lr)
-                if (B <= 16) RNN_MLP_UPD(1); else if (B <= 32) RNN_MLP_UPD(2); else if (B <= 64) RNN_MLP_UPD(4);
-                else RNN_MLP_UPD(0);
-#undef RNN_MLP_UPD
-                if (hipGetLastError() != hipSuccess) return RNN_EHIP;
-            }
+            if (hipGetLastError() != hipSuccess) return RNN_EHIP;
             dz = dz_prev;
+        }
+        {
+            for (int l = 0; l < L; ++l)
+                ul.Aprev[l] = l > 0 ? reinterpret_cast<const float*>(ws + pl.act[l]) : x_in;
+            ProfileScope ps(K_MLP_UPDATE, s);
+#define RNN_MLP_UPD(MB) hipLaunchKernelGGL(mlp_update_kernel<MB>, dim3(total_wgs), dim3(256), 0, s, ul, B, lr)
+            if (B <= 16) RNN_MLP_UPD(1); else if (B <= 32) RNN_MLP_UPD(2); else if (B <= 64) RNN_MLP_UPD(4);
+            else RNN_MLP_UPD(0);
+#undef RNN_MLP_UPD
+            if (hipGetLastError() != hipSuccess) return RNN_EHIP;
         }
     }
     if (dims->flags & RNN_FLAG_SYNC)
