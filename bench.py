@@ -470,7 +470,7 @@ def mlp_leg(n_batches=400, lr=0.01):
             n_params = sum(w.numel() + v.numel() for w, v in zip(W, b))
             entry = dict(examples_per_s=n_batches * batch / wall, us_per_batch=1e6 * wall / n_batches,
                          gpu_event_us_per_batch=1e3 * e0.elapsed_time(e1) / n_batches,
-                         launches_per_batch=2 * case["n_hidden"] + 3, parameters=n_params,
+                         launches_per_batch=2 * case["n_hidden"] + 2, parameters=n_params,
                          loss_first=float(losses[0]), loss_last=float(losses[-1]))
             if name == "MLP3" and batch == 60:
                 rnn.rnn_profile_begin(1 << 16)

@@ -6,8 +6,9 @@
 //     W_l <- W_l - lr dloss/dW_l,  b_l <- b_l - lr dloss/db_l      after every batch.
 //
 // At these sizes a step moves a few megabytes of weights and computes almost nothing, so what it
-// costs is launches and memory round trips.  A step is 2 L + 3 launches (L hidden layers: L + 1
-// forward, the loss, L backward, and ONE update of all layers), each
+// costs is launches and memory round trips.  A step is 2 L + 2 launches (L hidden layers: L + 1
+// forward, the last of them with the loss in its epilogue when there are at most 16 classes, L
+// backward, and ONE update of all layers, which also adds up the batch's loss), each
 // built like the batched recurrence's step kernel to pay one round trip: a workgroup owns a
 // 16 x 16 tile of the result, its 16 wavefronts split the contraction in slices of 64 and request
 // their whole share of both operands at once, straight into the lane registers
@@ -51,10 +52,14 @@ __device__ __forceinline__ float apply_act(float a) {
 // C[M,N] = act(A[M,K] W[N,K]^T + bias[N]);  ACT 0 sigmoid, 1 tanh, 2 none.
 // grid (ceil(N/16), ceil(M/16)), 1024 threads.  Lane (r = lane % 16, g = lane / 16) of a wavefront
 // holds k = k0 + 16 s + 4 g + e of row r of A and of row r of W: the same permuted walk of K for both.
-template <int ACT, bool VEC>
+// CE (output layer with N <= 16, ACT 2): the tile holds whole rows of logits, so the epilogue goes on
+// to the loss: C receives dZ = (softmax - onehot(y)) / M instead of the logits and losspart[blockIdx.y]
+// the sum of the workgroup's row losses lse - z[y] (rows in order).
+template <int ACT, bool VEC, bool CE = false>
 __global__ __launch_bounds__(MNT) void mlp_fwd_kernel(const float* __restrict__ A, const float* __restrict__ W,
                                                       const float* __restrict__ bias, float* __restrict__ C,
-                                                      int M, int N, int K) {
+                                                      int M, int N, int K, const int32_t* __restrict__ y,
+                                                      float* __restrict__ losspart) {
     __shared__ float red[MW][4][kWave];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int g = lane / 16, nn = lane % 16;
@@ -86,13 +91,38 @@ __global__ __launch_bounds__(MNT) void mlp_fwd_kernel(const float* __restrict__ 
 #pragma unroll
     for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc0[i] + acc1[i];
     __syncthreads();
-    if (wave >= 4) return;
-    const int row = m0 + 4 * g + wave;
-    if (row >= M || col >= N) return;
-    float v = bv;
+    if constexpr (!CE) {
+        if (wave >= 4) return;
+        const int row = m0 + 4 * g + wave;
+        if (row >= M || col >= N) return;
+        float v = bv;
 #pragma unroll
-    for (int w = 0; w < MW; ++w) v += red[w][wave][lane];
-    C[(size_t)row * N + col] = apply_act<ACT>(v);
+        for (int w = 0; w < MW; ++w) v += red[w][wave][lane];
+        C[(size_t)row * N + col] = apply_act<ACT>(v);
+    } else {
+        __shared__ float rowloss[16];
+        if (wave < 4) {
+            // the 16 lanes of a quarter-wave hold the 16 columns of row 4 g + wave
+            const int row = m0 + 4 * g + wave;
+            const bool ok = row < M && col < N;
+            float v = bv;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) v += red[w][wave][lane];
+            const int yy = row < M ? y[row] : -1;
+            const float m = max16(ok ? v : -INFINITY);
+            const float se = sum16(ok ? __expf(v - m) : 0.f);
+            const float lse = m + __logf(se);
+            const float zy = sum16((ok && col == yy) ? v : 0.f);
+            if (ok) C[(size_t)row * N + col] = (__expf(v - lse) - (col == yy ? 1.f : 0.f)) * (1.0f / (float)M);
+            if (nn == 0) rowloss[4 * g + wave] = row < M ? lse - zy : 0.f;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            float sum = 0.f;
+            for (int r = 0; r < 16; ++r) sum += rowloss[r];
+            losspart[blockIdx.y] = sum;
+        }
+    }
 }
 
 // dZprev[M,Kin] = (dZ[M,Nout] W[Nout,Kin]) * act'(Aprev[M,Kin]): the contraction runs over the rows
@@ -159,6 +189,9 @@ struct UpdateLayers {
     int gx[RNN_MLP_MAX_LAYERS];               // workgroups along Kin
     int first[RNN_MLP_MAX_LAYERS + 1];        // first workgroup of the layer in the flat grid
     int layers;
+    const float* losspart;                    // per 16-row group of the batch: sum of its row losses
+    int nparts;                               // 0: the loss was written by its own kernel
+    float* loss;
 };
 
 // One launch updates every layer: the flat grid is the layers' (ceil(Kin/256) x ceil(Nout/16)) grids
@@ -178,6 +211,11 @@ __global__ __launch_bounds__(256) void mlp_update_kernel(const UpdateLayers ul, 
     const int q = lane / 16, r = lane % 16;
     const int n0 = by * 16;
     const int k0 = (bx * 4 + wave) * 64;
+    if (blockIdx.x == 0 && tid == 64 && ul.nparts > 0) {   // the batch's mean loss, groups in order
+        float sum = 0.f;
+        for (int g = 0; g < ul.nparts; ++g) sum += ul.losspart[g];
+        *ul.loss = sum / (float)M;
+    }
     if (bx == 0 && wave == 0) {
         // bias: lane (q, r) sums the rows m = q, q + 4, ... of column n0 + r; the four partial sums
         // of a column meet through lane exchanges in a fixed order
@@ -304,7 +342,7 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 // workspace: activations of the hidden layers, logits / dZ of the output layer, two dZ buffers of
 // the hidden width
-struct MlpPlan { size_t act[RNN_MLP_MAX_LAYERS + 1], Z, dz[RNN_MLP_MAX_LAYERS], total; };
+struct MlpPlan { size_t act[RNN_MLP_MAX_LAYERS + 1], Z, dz[RNN_MLP_MAX_LAYERS], losspart, total; };
 
 MlpPlan mlp_plan(const rnn_mlp_dims* d) {
     const Widths w = widths_of(d);
@@ -313,9 +351,9 @@ MlpPlan mlp_plan(const rnn_mlp_dims* d) {
     auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
     for (int l = 1; l < w.layers; ++l) p.act[l] = take((size_t)d->batch * w.w[l] * 4);
     p.Z = take((size_t)d->batch * d->out_dim * 4);
-    // dZ of layer l's outputs, l < layers - 1 (the last layer's is Z itself, in place); at least one
-    // region: it also takes the loss when the caller wants none
-    for (int l = 0; l + 1 < w.layers || l == 0; ++l) p.dz[l] = take((size_t)d->batch * w.w[l + 1] * 4);
+    // dZ of layer l's outputs, l < layers - 1 (the last layer's is Z itself, in place)
+    for (int l = 0; l + 1 < w.layers; ++l) p.dz[l] = take((size_t)d->batch * w.w[l + 1] * 4);
+    p.losspart = take((size_t)((d->batch + 15) / 16 + 1) * 4);   // + one word that takes the loss when the caller wants none
     p.total = off;
     return p;
 }
@@ -329,11 +367,22 @@ hipError_t launch_fwd(int act, const float* A, const float* W, const float* b, f
     ProfileScope ps(K_MLP_FWD, s);
 #define RNN_MLP_FWD(ACT)                                                                              \
     do {                                                                                              \
-        if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<ACT, true>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K);  \
-        else hipLaunchKernelGGL((mlp_fwd_kernel<ACT, false>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K);     \
+        if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<ACT, true>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K, nullptr, nullptr);  \
+        else hipLaunchKernelGGL((mlp_fwd_kernel<ACT, false>), grid, dim3(MNT), 0, s, A, W, b, C, M, N, K, nullptr, nullptr);     \
     } while (0)
     if (act == 0) RNN_MLP_FWD(0); else if (act == 1) RNN_MLP_FWD(1); else RNN_MLP_FWD(2);
 #undef RNN_MLP_FWD
+    return hipGetLastError();
+}
+
+// output layer of at most 16 classes with the loss in its epilogue
+hipError_t launch_fwd_ce(const float* A, const float* W, const float* b, float* dZ, int M, int N, int K,
+                         const int32_t* y, float* losspart, hipStream_t s) {
+    dim3 grid(1, (M + 15) / 16);
+    const bool vec = K % 4 == 0 && al16(A) && al16(W);
+    ProfileScope ps(K_MLP_FWD, s);
+    if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<2, true, true>), grid, dim3(MNT), 0, s, A, W, b, dZ, M, N, K, y, losspart);
+    else hipLaunchKernelGGL((mlp_fwd_kernel<2, false, true>), grid, dim3(MNT), 0, s, A, W, b, dZ, M, N, K, y, losspart);
     return hipGetLastError();
 }
 
@@ -367,10 +416,16 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
     char* ws = static_cast<char*>(workspace);
     const int B = dims->batch, L = w.layers;
     float* Z = reinterpret_cast<float*>(ws + pl.Z);
-    float* scratch_loss = reinterpret_cast<float*>(ws + pl.dz[0]);   // when the caller wants no losses (free until backpropagation starts)
     // the one update launch of a batch: every layer's grid, one after another
+    // at most 16 classes: the output layer's tile holds whole rows, its epilogue forms the loss and
+    // dZ, and the update launch adds up the batch's loss
+    const bool fused_ce = dims->out_dim <= 16;
+    float* losspart = reinterpret_cast<float*>(ws + pl.losspart);
+    float* scratch_loss = losspart + (B + 15) / 16;   // when the caller wants no losses
     UpdateLayers ul{};
     ul.layers = L;
+    ul.losspart = losspart;
+    ul.nparts = fused_ce ? (B + 15) / 16 : 0;
     int total_wgs = 0;
     for (int l = 0; l < L; ++l) {
         ul.dZ[l] = l + 1 < L ? reinterpret_cast<const float*>(ws + pl.dz[l]) : Z;
@@ -387,17 +442,23 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
         const float* x_in = X + (size_t)i * B * dims->in_dim;
         const float* a_prev = x_in;
         // forward
+        float* loss_out = losses ? losses + i : scratch_loss;
         for (int l = 0; l < L; ++l) {
             float* out = l + 1 < L ? reinterpret_cast<float*>(ws + pl.act[l + 1]) : Z;
-            if (launch_fwd(l + 1 < L ? dims->act : 2, a_prev, params->W[l], params->b[l], out, B, w.w[l + 1],
-                           w.w[l], s) != hipSuccess)
-                return RNN_EHIP;
+            hipError_t e;
+            if (l + 1 == L && fused_ce)
+                e = launch_fwd_ce(a_prev, params->W[l], params->b[l], Z, B, w.w[l + 1], w.w[l], y + (size_t)i * B,
+                                  losspart, s);
+            else
+                e = launch_fwd(l + 1 < L ? dims->act : 2, a_prev, params->W[l], params->b[l], out, B, w.w[l + 1],
+                               w.w[l], s);
+            if (e != hipSuccess) return RNN_EHIP;
             a_prev = out;
         }
-        {
+        if (!fused_ce) {
             ProfileScope ps(K_MLP_CE, s);
-            hipLaunchKernelGGL(mlp_ce_kernel, dim3(1), dim3(1024), 0, s, Z, y + (size_t)i * B,
-                               losses ? losses + i : scratch_loss, B, dims->out_dim);
+            hipLaunchKernelGGL(mlp_ce_kernel, dim3(1), dim3(1024), 0, s, Z, y + (size_t)i * B, loss_out, B,
+                               dims->out_dim);
             if (hipGetLastError() != hipSuccess) return RNN_EHIP;
         }
         // backward: dZ_{l-1} from dZ_l and the weights as they were in the forward pass, layer by
@@ -421,6 +482,7 @@ int rnn_mlp_train(const rnn_mlp_dims* dims, const rnn_mlp_params* params, const 
         {
             for (int l = 0; l < L; ++l)
                 ul.Aprev[l] = l > 0 ? reinterpret_cast<const float*>(ws + pl.act[l]) : x_in;
+            ul.loss = loss_out;
             ProfileScope ps(K_MLP_UPDATE, s);
 #define RNN_MLP_UPD(MB) hipLaunchKernelGGL(mlp_update_kernel<MB>, dim3(total_wgs), dim3(256), 0, s, ul, B, lr)
             if (B <= 16) RNN_MLP_UPD(1); else if (B <= 32) RNN_MLP_UPD(2); else if (B <= 64) RNN_MLP_UPD(4);

@@ -47,6 +47,9 @@ SMALL = {
     "batch_one": dict(in_dim=33, hidden=64, n_hidden=2, out_dim=5, batch=1, n_batches=6),
     "wide_batch_and_tiles": dict(in_dim=300, hidden=272, n_hidden=2, out_dim=40, batch=70, n_batches=2),
     "many_classes": dict(in_dim=20, hidden=24, n_hidden=1, out_dim=200, batch=9, n_batches=2),
+    # 16 classes: the widest output layer whose launch also forms the loss; 37 rows = 3 row groups, the last ragged
+    "sixteen_classes_three_row_groups": dict(in_dim=45, hidden=40, n_hidden=1, out_dim=16, batch=37, n_batches=3),
+    "seventeen_classes": dict(in_dim=45, hidden=40, n_hidden=1, out_dim=17, batch=37, n_batches=3),
 }
 
 
