@@ -55,6 +55,7 @@ extern "C" {
 #define RNN_EWORKSPACE   (-2)  /* workspace NULL, misaligned or smaller than required */
 #define RNN_EUNSUPPORTED (-3)  /* valid request this build has no kernel for          */
 #define RNN_EHIP         (-4)  /* a HIP launch or query failed                        */
+#define RNN_ETOOLARGE    (-5)  /* problem exceeds the fixed scratch of rnn_window_static */
 
 #define RNN_INPUT_TOKENS 0     /* x is int32 [T,B], values in [0,in_dim)              */
 #define RNN_INPUT_DENSE  1     /* x is float32 [T,B,in_dim]                           */
@@ -222,6 +223,33 @@ int rnn_window(const rnn_dims *dims, const rnn_params *params, const int32_t *x,
                const int32_t *targets, const float *h0, const float *dh_last, float *h_all,
                float *h_last, float *loss, const rnn_grads *grads, float *dh0,
                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * rnn_window for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same
+ * computation, same kernels and same outputs as rnn_window; the exchange boxes live in a fixed
+ * array inside the library's code object instead (RNN_WINDOW_STATIC_BYTES = 2 MiB per GPU, held by
+ * every GPU the library runs on until the process ends).  The call allocates and frees nothing,
+ * here or in any library routine it uses.
+ *   dims .. dh0   as in rnn_window.  Sizes whose boxes exceed the array (more than
+ *                 rnn_window_workspace_bytes() = RNN_WINDOW_STATIC_BYTES) return RNN_ETOOLARGE and
+ *                 nothing is enqueued; the paper's benchmark shape (vocabulary 10000, hidden 100,
+ *                 windows of 10) needs 0.67 MB.
+ *   status        device int32[1], nullable, 4-byte aligned: set to 1 by the kernel if a bounded
+ *                 wait expired (results of that call invalid), untouched otherwise; the caller
+ *                 clears it.  NULL: the word is kept inside the array and cannot be read.
+ * The first call on a device looks the array's device address up and clears the array with a fill
+ * kernel on hip_stream, ahead of the window kernel; make that first call outside graph capture.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's words (they carry
+ * that call's tag, so a later call never mistakes them for its own): calls that overlap in time
+ * on one GPU, on whatever streams, race and give undefined results.  Calls on different GPUs are
+ * independent.
+ */
+#define RNN_WINDOW_STATIC_BYTES ((size_t)2 << 20)
+int rnn_window_static(const rnn_dims *dims, const rnn_params *params, const int32_t *x,
+                      const int32_t *targets, const float *h0, const float *dh_last, float *h_all,
+                      float *h_last, float *loss, const rnn_grads *grads, float *dh0,
+                      int32_t *status, void *hip_stream);
 
 /*
  * Gauss-Newton matrix times a vector by the R-operator (the paper's section on the R-operator:

@@ -23,7 +23,7 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
            "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
-           "rnn_window", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
+           "rnn_window", "rnn_window_static", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
            "rnn_mlp_workspace_bytes", "rnn_mlp_train", "rnn_measure_ceilings")
 MLP_MAX_LAYERS = 16
 GN_METRIC_LOSS, GN_METRIC_IDENTITY = 0, 1
@@ -118,6 +118,9 @@ def lib():
         L.rnn_window_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
         L.rnn_window.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp,
                                  ctypes.POINTER(Grads), vp, vp, sz, vp]
+        L.rnn_window_static.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp,
+                                        ctypes.POINTER(Grads), vp, vp, vp]
+        L.rnn_window_static.restype = ctypes.c_int
         L.rnn_gauss_newton_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
         L.rnn_gauss_newton_vec.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), ctypes.POINTER(Params),
                                            vp, vp, ctypes.c_int32, ctypes.POINTER(Grads), vp, vp, sz, vp]
@@ -360,6 +363,20 @@ def rnn_window(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads
     rc = lib().rnn_window(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(targets), _p(h0), _p(dh_last),
                           _p(h_all), _p(h_last), _p(loss), ctypes.byref(gr), _p(dh0), wp, wb,
                           _stream(stream))
+    if check:
+        _check(rc)
+    return rc
+
+
+WINDOW_STATIC_BYTES = 2 << 20
+
+
+def rnn_window_static(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0, status=None,
+                      stream=None, check=True):
+    pr, gr = _params(params), _grads(grads)
+    rc = lib().rnn_window_static(ctypes.byref(dims), ctypes.byref(pr), _p(x), _p(targets), _p(h0), _p(dh_last),
+                                 _p(h_all), _p(h_last), _p(loss), ctypes.byref(gr), _p(dh0), _p(status),
+                                 _stream(stream))
     if check:
         _check(rc)
     return rc

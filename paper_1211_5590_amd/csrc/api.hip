@@ -747,6 +747,7 @@ const char* rnn_strerror(int code) {
         case RNN_EWORKSPACE: return "workspace missing, misaligned or too small (see rnn_workspace_bytes)";
         case RNN_EUNSUPPORTED: return "no kernel for this shape in this build";
         case RNN_EHIP: return "HIP launch or synchronisation failed";
+        case RNN_ETOOLARGE: return "problem needs more than the fixed scratch array of rnn_window_static (use rnn_window)";
         default: return "unknown error code";
     }
 }

@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kThreads) void rec_bwd_with_strips_kernel(RecResArg
 }
 
 __global__ void zero_words_kernel(int32_t* p, int n) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
 }
 
 int pow2_floor(int v) {
@@ -566,7 +566,8 @@ hipError_t launch_rec_bwd_with_strips(RecResArgs a, const RecResPlan& pl, const 
 
 hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s) {
     ProfileScope ps(K_MISC, s);
-    hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(256), 0, s, p, n);
+    const int blocks = n <= 4096 ? 1 : (n + 4095) / 4096 < 256 ? (n + 4095) / 4096 : 256;
+    hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }
 

@@ -33,11 +33,18 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "common.hpp"
 #include "internal.hpp"
 #include "prof.hpp"
+
+// Exchange boxes of rnn_window_static, the form of the one-window call for callers that cannot
+// allocate: a fixed array in the code object instead of a caller-provided workspace.  Every GPU
+// the library runs on holds its own copy until the process ends.
+constexpr size_t kStaticScratchBytes = RNN_WINDOW_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace rnn {
 namespace {
@@ -1297,6 +1304,83 @@ uint32_t next_window_tag() {
     return e;
 }
 
+// Argument checks shared by the two forms of the one-window call.
+int window_args_ok(const rnn_dims* dims, const rnn_params* params, const int32_t* x, const int32_t* targets,
+                   const float* h0, const float* dh_last, const float* h_all, const float* h_last,
+                   const float* loss, const rnn_grads* grads, const float* dh0) {
+    const int rc = window_supported(dims);
+    if (rc != RNN_OK) return rc;
+    if (!params || !params->Wx || !params->Wh || !params->b || !params->V || !params->c || !x ||
+        !targets || !loss || !grads || !grads->dWx || !grads->dWh || !grads->db || !grads->dV || !grads->dc)
+        return RNN_EINVAL;
+    auto bad16 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); };
+    auto bad4 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 3u); };
+    if (bad16(params->Wx) || bad16(params->Wh) || bad16(params->b) || bad16(params->V) || bad16(params->c) ||
+        bad16(grads->dWx) || bad16(grads->dWh) || bad16(grads->db) || bad16(grads->dV) || bad16(grads->dc) ||
+        bad4(x) || bad4(targets) || bad4(h0) || bad4(dh_last) || bad4(h_all) || bad4(h_last) || bad4(loss) ||
+        bad4(dh0))
+        return RNN_EINVAL;
+    return RNN_OK;
+}
+
+// One window on the exchange boxes at `workspace` (checked by the caller).  status_override: where a
+// bounded wait that expires leaves its 1 instead of the workspace's own status word.
+int launch_window(const rnn_dims* dims, const rnn_params* params, const int32_t* x, const int32_t* targets,
+                  const float* h0, const float* dh_last, float* h_all, float* h_last, float* loss,
+                  const rnn_grads* grads, float* dh0, void* workspace, const StreamPlan& pl,
+                  int32_t* status_override, hipStream_t s) {
+    StreamArgs a{};
+    a.Wx = const_cast<float*>(params->Wx); a.Wh = const_cast<float*>(params->Wh);
+    a.b = const_cast<float*>(params->b); a.V = const_cast<float*>(params->V); a.c = const_cast<float*>(params->c);
+    a.ids = x; a.ys = targets; a.n_windows = 1; a.lr = 1.0f; a.tag0 = next_window_tag();
+    a.h0 = h0; a.h_last = h_last; a.losses = loss; a.h_all = h_all; a.dh_last = dh_last; a.dh0 = dh0;
+    a.dWx = grads->dWx; a.dWh = grads->dWh; a.db = grads->db; a.dV = grads->dV; a.dc = grads->dc;
+    a.beta = (dims->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
+    a.H = dims->hidden; a.NV = dims->out_dim; a.NVin = dims->in_dim; a.T = dims->seq_len;
+    bind_boxes(a, workspace, pl);
+    if (status_override) a.status = status_override;
+
+    const int nq = pick_nq(a.H);
+    const void* fn = dims->act == RNN_ACT_SIGMOID ? pick_window_kernel<0>(nq) : pick_window_kernel<1>(nq);
+    size_t lds = loop_lds_floats(a.T, nq);
+    if (strip_lds_floats(nq, a.T, a.S) > lds) lds = strip_lds_floats(nq, a.T, a.S);
+    lds *= 4;
+    if (allow_lds(fn, lds) != hipSuccess) return RNN_EHIP;
+    hipError_t e;
+    {
+        ProfileScope ps(K_WINDOW, s);
+        void* args[] = {&a};
+        e = getenv("RNN_WINDOW_COOP") ? hipLaunchCooperativeKernel(fn, dim3(1 + a.S), dim3(NT), args, (unsigned)lds, s)
+                                      : hipLaunchKernel(fn, dim3(1 + a.S), dim3(NT), args, lds, s);
+    }
+    if (e != hipSuccess) return RNN_EHIP;
+    if (dims->flags & RNN_FLAG_SYNC)
+        if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
+    return RNN_OK;
+}
+
+// Address of this device's copy of the fixed scratch array of rnn_window_static.  In host code the
+// array's name is only a handle: the address kernels can use comes from hipGetSymbolAddress, once
+// per device (every GPU holds its own copy).  The first call on a device also clears the array, on
+// the calling stream, ahead of the window kernel.
+int static_scratch(hipStream_t s, void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RNN_EHIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RNN_EHIP;
+        if (launch_zero_words(static_cast<int32_t*>(p), (int)(kStaticScratchBytes / 4), s) != hipSuccess)
+            return RNN_EHIP;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return RNN_OK;
+}
+
 }  // namespace
 }  // namespace rnn
 
@@ -1327,50 +1411,29 @@ int rnn_window(const rnn_dims* dims, const rnn_params* params, const int32_t* x,
                const rnn_grads* grads, float* dh0, void* workspace, size_t workspace_bytes,
                void* hip_stream) {
     using namespace rnn;
-    const int rc = window_supported(dims);
+    const int rc = window_args_ok(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0);
     if (rc != RNN_OK) return rc;
-    if (!params || !params->Wx || !params->Wh || !params->b || !params->V || !params->c || !x ||
-        !targets || !loss || !grads || !grads->dWx || !grads->dWh || !grads->db || !grads->dV || !grads->dc)
-        return RNN_EINVAL;
-    auto bad16 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u); };
-    auto bad4 = [](const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 3u); };
-    if (bad16(params->Wx) || bad16(params->Wh) || bad16(params->b) || bad16(params->V) || bad16(params->c) ||
-        bad16(grads->dWx) || bad16(grads->dWh) || bad16(grads->db) || bad16(grads->dV) || bad16(grads->dc) ||
-        bad4(x) || bad4(targets) || bad4(h0) || bad4(dh_last) || bad4(h_all) || bad4(h_last) || bad4(loss) ||
-        bad4(dh0))
-        return RNN_EINVAL;
     const StreamPlan pl = stream_plan(dims);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
         return RNN_EWORKSPACE;
+    return launch_window(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0, workspace,
+                         pl, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+int rnn_window_static(const rnn_dims* dims, const rnn_params* params, const int32_t* x, const int32_t* targets,
+                      const float* h0, const float* dh_last, float* h_all, float* h_last, float* loss,
+                      const rnn_grads* grads, float* dh0, int32_t* status, void* hip_stream) {
+    using namespace rnn;
+    const int rc = window_args_ok(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0);
+    if (rc != RNN_OK) return rc;
+    if (status && (reinterpret_cast<uintptr_t>(status) & 3u)) return RNN_EINVAL;
+    const StreamPlan pl = stream_plan(dims);
+    if (pl.total > kStaticScratchBytes) return RNN_ETOOLARGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-
-    StreamArgs a{};
-    a.Wx = const_cast<float*>(params->Wx); a.Wh = const_cast<float*>(params->Wh);
-    a.b = const_cast<float*>(params->b); a.V = const_cast<float*>(params->V); a.c = const_cast<float*>(params->c);
-    a.ids = x; a.ys = targets; a.n_windows = 1; a.lr = 1.0f; a.tag0 = next_window_tag();
-    a.h0 = h0; a.h_last = h_last; a.losses = loss; a.h_all = h_all; a.dh_last = dh_last; a.dh0 = dh0;
-    a.dWx = grads->dWx; a.dWh = grads->dWh; a.db = grads->db; a.dV = grads->dV; a.dc = grads->dc;
-    a.beta = (dims->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
-    a.H = dims->hidden; a.NV = dims->out_dim; a.NVin = dims->in_dim; a.T = dims->seq_len;
-    bind_boxes(a, workspace, pl);
-
-    const int nq = pick_nq(a.H);
-    const void* fn = dims->act == RNN_ACT_SIGMOID ? pick_window_kernel<0>(nq) : pick_window_kernel<1>(nq);
-    size_t lds = loop_lds_floats(a.T, nq);
-    if (strip_lds_floats(nq, a.T, a.S) > lds) lds = strip_lds_floats(nq, a.T, a.S);
-    lds *= 4;
-    if (allow_lds(fn, lds) != hipSuccess) return RNN_EHIP;
-    hipError_t e;
-    {
-        ProfileScope ps(K_WINDOW, s);
-        void* args[] = {&a};
-        e = getenv("RNN_WINDOW_COOP") ? hipLaunchCooperativeKernel(fn, dim3(1 + a.S), dim3(NT), args, (unsigned)lds, s)
-                                      : hipLaunchKernel(fn, dim3(1 + a.S), dim3(NT), args, lds, s);
-    }
-    if (e != hipSuccess) return RNN_EHIP;
-    if (dims->flags & RNN_FLAG_SYNC)
-        if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
-    return RNN_OK;
+    void* ws = nullptr;
+    const int rs = static_scratch(s, &ws);
+    if (rs != RNN_OK) return rs;
+    return launch_window(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0, ws, pl, status, s);
 }
 
 int rnn_train_stream_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
