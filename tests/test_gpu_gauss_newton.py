@@ -118,3 +118,24 @@ def test_gauss_newton_vec_with_the_split_products(name):
     r.forward()
     got = r.gauss_newton(gamma, rnn.GN_METRIC_LOSS)
     check(got, r.Rz.cpu().numpy(), oracle.gauss_newton_vec(case, gamma, metric=0, want_Rz=True))
+
+
+_config_refs = {}
+
+
+@pytest.mark.parametrize("flags", [0, rnn.FLAG_BF16X3_OUTPUT], ids=["f32", "bf16x3"])
+@pytest.mark.parametrize("name,overrides", [("C3", {}), ("C4", dict(seq_len=6))], ids=["C3_full", "C4_T6"])
+def test_gauss_newton_vec_at_configuration_size(name, overrides, flags):
+    """The product at the widths bench.py times it on: the whole larger-hidden configuration
+    (grid-resident loops, 64-row product tiles) and the minibatched one at reduced length
+    (step-wise loops, batch 64, hidden 1024, vocabulary 10000; the oracle's product is one serial
+    loop nest, about a minute for these 384 rows); the oracle runs once per shape."""
+    case = ri.make_config(name, **overrides)
+    gamma = ri.make_direction(case, 13)
+    if name not in _config_refs:
+        print(f"{name} oracle ...", flush=True)
+        _config_refs[name] = oracle.gauss_newton_vec(case, gamma, metric=0, want_Rz=True)
+    r = GnRunner(case, flags)
+    r.forward()
+    got = r.gauss_newton(gamma, rnn.GN_METRIC_LOSS)
+    check(got, r.Rz.cpu().numpy(), _config_refs[name])
