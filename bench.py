@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the Elman-RNN training path (forward recurrence -> output layer + loss -> BPTT).
 
-One "step" is one pass of the whole path over one batch of synthetic input:
-  C2 (headline, the paper's benchmark shape: batch 1, vocabulary-sized input and output layers):
-     the 100000-token Zipf stream as 10000 dependent truncated-BPTT windows of 10 steps; every
-     window is one rnn_window call (forward, loss and BPTT of the window in one launch; the same
-     outputs as rnn_forward -> rnn_loss -> rnn_bptt, whose timing is reported beside it) with the
-     hidden state carried, in stream order, exactly as if an optimiser step sat between windows.
-  C1, C3, C4, C5: one window of the named configuration.
+One "step" is one pass of the whole path (rnn_forward -> rnn_loss -> rnn_bptt) over one batch of
+synthetic input.  The headline workload is C4, the largest configuration (hidden 1024, vocabulary
+10000, 256 steps, batch 64: 16384 tokens per step); the others are reported under `per_config`
+and, in short, under `summary`:
+  C2 (the paper's benchmark shape: batch 1, vocabulary-sized input and output layers): the
+     100000-token Zipf stream as 10000 dependent truncated-BPTT windows of 10 steps; every window
+     is one rnn_window call (forward, loss and BPTT of the window in one launch; the same outputs
+     as the three calls, whose timing is reported beside it) with the hidden state carried, in
+     stream order, exactly as if an optimiser step sat between windows; plus the same stream in
+     one rnn_train_stream launch with an SGD update per window.
+  C1, C3, C5: one window of the named configuration.
 Prints ONE JSON line.  Inputs are resident in HBM before the timed region starts.
 """
 from __future__ import annotations
@@ -34,9 +38,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--windows", type=int, default=None, help="override the number of C2 windows")
-    ap.add_argument("--others", default="C3,C4,C5",
+    ap.add_argument("--others", default="C1,C2,C3,C5",
                     help="comma list of further configurations reported under 'per_config' ('none' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--three-calls", action="store_true",
@@ -47,7 +51,7 @@ def parse():
                     help="run only the feed-forward classifier workloads and print their JSON line")
     ap.add_argument("--no-mlp", action="store_true",
                     help="skip the feed-forward classifier workloads (the paper's second benchmark)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU budget of each oracle sample")
     ap.add_argument("--reference-kernels", action="store_true")
     ap.add_argument("--bf16x3", action="store_true",
                     help="opt-in output layer on the bf16 matrix cores (hi/lo split operands, three products)")
@@ -312,6 +316,8 @@ def roofline_of(prof, case):
             t = json.load(fh).get(case.get("_name", ""), {}).get(name)
         if t:
             r["traffic"] = t["bytes_per_launch"]
+            r["traffic_source"] = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                   "command, scaled by a 64 MiB copy; committed, not measured in this run")
     except (OSError, ValueError):
         pass
     return r
@@ -322,9 +328,10 @@ def all_rooflines(prof, case):
             if algorithmic_work(k, case) is not None]
 
 
-def cpu_baseline(name, budget_s):
-    """The oracle as it stands, timed on the host cores over a bounded sample of the workload."""
-    import numpy as np
+def cpu_baseline(name, budget_s, one_thread_row=True):
+    """The oracle as it stands, timed on the host cores (as many threads as it is set to use) over a
+    bounded sample of the workload: the whole configuration when a short probe says that fits the
+    budget, else the same widths at a shorter sequence, which the `sample` field states."""
     import oracle
     import rnn_inputs as ri
     cores = oracle.num_threads()
@@ -332,48 +339,54 @@ def cpu_baseline(name, budget_s):
     if cfg["windows"] > 1:
         cap = min(cfg["windows"], 4096)
         case = ri.make_config(name, windows=cap)
-        t0 = time.perf_counter()
-        h, done = None, 0
-        while done < cap and (done < 4 or time.perf_counter() - t0 < budget_s):
-            r = oracle.fwd_bptt(ri.window(case, done), h0=h)
-            h = r["h_all"][-1]
-            done += 1
-        dt = time.perf_counter() - t0
+
+        def run(limit_s):
+            t0 = time.perf_counter()
+            h, done = None, 0
+            while done < cap and (done < 4 or time.perf_counter() - t0 < limit_s):
+                r = oracle.fwd_bptt(ri.window(case, done), h0=h)
+                h = r["h_all"][-1]
+                done += 1
+            return done, time.perf_counter() - t0
+        done, dt = run(budget_s)
         tokens = done * cfg["seq_len"] * cfg["batch"]
-        sample = f"first {done} windows of the stream (state carried), forward+loss+BPTT each"
-        # the same oracle on one thread, on a shorter sample of the same stream
+        out = dict(value=tokens / dt, unit="tokens/s", cores=cores, kind="oracle", seconds=dt,
+                   sample=f"first {done} windows of the stream (state carried), forward+loss+BPTT each")
+        if one_thread_row and cores > 1:
+            oracle.set_num_threads(1)
+            try:
+                done1, dt1 = run(min(3.0, budget_s))
+            finally:
+                oracle.set_num_threads(cores)
+            out["one_thread"] = dict(value=done1 * cfg["seq_len"] * cfg["batch"] / dt1, unit="tokens/s", cores=1,
+                                     sample=f"first {done1} windows", seconds=dt1)
+        return out
+    T, B = cfg["seq_len"], cfg["batch"]
+    # probe: a few steps of the full batch give the oracle's seconds per row on these threads
+    Tp = min(T, 2 if B >= 16 else 16)
+    probe = ri.make_config(name, seq_len=Tp)
+    t0 = time.perf_counter()
+    oracle.fwd_bptt(probe)
+    per_row = (time.perf_counter() - t0) / (Tp * B)
+    rows = max(1.0, budget_s / per_row)
+    while T * B > rows and T > 1:
+        T = max(1, T // 2)
+    case = probe if T == Tp else ri.make_config(name, seq_len=T)
+    t0 = time.perf_counter()
+    oracle.fwd_bptt(case)
+    dt = time.perf_counter() - t0
+    whole = T == cfg["seq_len"]
+    sample = ("the whole configuration, once" if whole else
+              f"one window with seq_len {T} instead of {cfg['seq_len']} (same widths and batch)") + ", forward+loss+BPTT"
+    out = dict(value=T * B / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample, seconds=dt)
+    if one_thread_row and cores > 1:
         oracle.set_num_threads(1)
-        t1 = time.perf_counter()
-        h, done1 = None, 0
-        while done1 < cap and (done1 < 4 or time.perf_counter() - t1 < min(3.0, budget_s)):
-            r = oracle.fwd_bptt(ri.window(case, done1), h0=h)
-            h = r["h_all"][-1]
-            done1 += 1
-        dt1 = time.perf_counter() - t1
-        oracle.set_num_threads(cores)
-        one = dict(value=done1 * cfg["seq_len"] * cfg["batch"] / dt1, unit="tokens/s", cores=1,
-                   sample=f"first {done1} windows", seconds=dt1)
-        return dict(value=tokens / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample,
-                    seconds=dt, one_thread=one)
-    else:
-        # shrink T (and B) until the estimated double-precision work fits the budget
-        T, B = cfg["seq_len"], cfg["batch"]
-        H, O, I = cfg["hidden"], cfg["out_dim"], cfg["in_dim"]
-        per_row = 6.0 * H * O + 6.0 * H * H + (0 if cfg["input_kind"] == 0 else 4.0 * H * I)
-        rate = 1.0e9 * cores                     # conservative plain-loop estimate, flop/s
-        rows = max(1, int(budget_s * rate / per_row))
-        while T * B > rows and T > 1:
-            T = max(1, T // 2)
-        while T * B > rows and B > 1:
-            B = max(1, B // 2)
-        case = ri.make_config(name, seq_len=T, batch=B)
-        t0 = time.perf_counter()
-        oracle.fwd_bptt(case)
-        dt = time.perf_counter() - t0
-        tokens = T * B
-        sample = f"one window with seq_len {T}, batch {B} (same widths), forward+loss+BPTT"
-    return dict(value=tokens / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample,
-                seconds=dt)
+        try:
+            one = cpu_baseline(name, min(6.0, budget_s), one_thread_row=False)
+        finally:
+            oracle.set_num_threads(cores)
+        out["one_thread"] = {k: one[k] for k in ("value", "unit", "cores", "sample", "seconds")}
+    return out
 
 
 def train_stream_leg(windows, reps=3, lr=0.1):
@@ -565,6 +578,76 @@ def device_facts(torch):
                 memory_bytes=pr.total_memory, l2_bytes=getattr(pr, "L2_cache_size", None))
 
 
+def oracle_rows(names, budget_s):
+    """The oracle on the host cores for each named configuration: a row on all cores and a row on
+    one thread (cpu_baseline says what each was timed on)."""
+    return {name: cpu_baseline(name, budget_s) for name in names}
+
+
+def sig(x, digits=5):
+    """Floats of the output line rounded to a few significant digits (keeps the line short)."""
+    if isinstance(x, float):
+        return float(f"{x:.{digits}g}") if x == x and abs(x) != float("inf") else None
+    if isinstance(x, dict):
+        return {k: sig(v, digits) for k, v in x.items()}
+    if isinstance(x, (list, tuple)):
+        return [sig(v, digits) for v in x]
+    return x
+
+
+def run_config(name, flags, windows=None, three_calls=False, steps=None, warm=None, all_kernels=False):
+    """Time one configuration and profile one more step of it per kernel."""
+    import torch
+    import paper_1211_5590_amd as rnn
+    w = Workload(name, flags, windows, three_calls)
+    steps = steps if steps is not None else DEFAULT_STEPS[name]
+    warm = warm if warm is not None else DEFAULT_WARM[name]
+    wall, gpu_s = w.time_steps(steps, warm)
+    prof = w.profile(1)
+    if w.fused and rnn.rnn_train_stream_status(w.wws) != 0:
+        print("bench.py: a bounded wait of rnn_window expired; results invalid", file=sys.stderr)
+        sys.exit(4)
+    res = dict(workload=name, steps=steps, warmup=warm, wall_s=wall, gpu_s=gpu_s,
+               tokens_per_s=w.tokens_per_step * steps / wall,
+               timesteps_per_s=w.timesteps_per_step * steps / wall,
+               ms_per_step=1e3 * wall / steps, gpu_event_ms_per_step=1e3 * gpu_s / steps,
+               entry_points="rnn_window" if w.fused else "rnn_forward,rnn_loss,rnn_bptt",
+               recurrence_variant=rnn.rnn_recurrence_variant(w.dims),
+               describe=describe(w.case), roofline=roofline_of(prof, w.case),
+               kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3),
+                                total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
+               bracket_us=w.bracket_us)
+    if all_kernels:
+        res["rooflines_all_kernels"] = all_rooflines(prof, w.case)
+    if name == "C2" and res["roofline"] and res["roofline"]["kernel"] == "window":
+        # what the method must move per window: V in and dV out (8.0 MB); the dense token-gradient
+        # buffer the overwrite convention fills adds 4 MB
+        H, O, I = w.case["hidden"], w.case["out_dim"], w.case["in_dim"]
+        us = res["roofline"]["avg_us"]
+        core = 4.0 * 2 * H * O
+        res["roofline"]["algorithmic_bytes_without_dWx_fill"] = core
+        res["roofline"]["frac_without_dWx_fill"] = core / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    del w
+    torch.cuda.empty_cache()
+    return res
+
+
+def per_config_entry(r):
+    return dict(tokens_per_s=r["tokens_per_s"], timesteps_per_s=r["timesteps_per_s"], ms_per_step=r["ms_per_step"],
+                entry_points=r["entry_points"], recurrence_variant=r["recurrence_variant"],
+                roofline=r["roofline"], kernels=r["kernels"])
+
+
+def summary_row(r):
+    rf = r.get("roofline") or {}
+    return [round(r["ms_per_step"], 4), round(r["tokens_per_s"], 1), rf.get("kernel"),
+            None if rf.get("frac") is None else round(rf["frac"], 4)]
+
+
+DEFAULT_STEPS = {"C1": 200, "C2": 3, "C3": 50, "C4": 10, "C5": 5}
+DEFAULT_WARM = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -587,10 +670,7 @@ def main():
     flags = rnn.FLAG_REFERENCE_KERNELS if a.reference_kernels else 0
     if a.bf16x3:
         flags |= rnn.FLAG_BF16X3_OUTPUT
-    default_steps = {"C1": 200, "C2": 3, "C3": 50, "C4": 10, "C5": 5}
-    default_warm = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
-    steps = a.steps if a.steps is not None else default_steps[a.workload]
-    warm = a.warmup if a.warmup is not None else default_warm[a.workload]
+    plain = not a.reference_kernels and not a.bf16x3
 
     if a.calibration_copy:
         src = torch.ones(16 << 20, device="cuda")          # 64 MiB read + 64 MiB written per copy
@@ -600,103 +680,76 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    wl = Workload(a.workload, flags, a.windows, a.three_calls)
-    wall, gpu_s = wl.time_steps(steps, warm)
-    prof = wl.profile(1)
-    if wl.fused and wl.rnn.rnn_train_stream_status(wl.wws) != 0:
-        print("bench.py: a bounded wait of rnn_window expired; results invalid", file=sys.stderr)
-        sys.exit(4)
+    head = run_config(a.workload, flags, a.windows, a.three_calls, a.steps, a.warmup, all_kernels=True)
+    summary = {a.workload: summary_row(head)}
+
+    per = {}
+    others = [s for s in a.others.split(",") if s and s != "none" and s != a.workload]
+    for name in others:
+        r = run_config(name, flags, a.windows if name == "C2" else None)
+        per[name] = per_config_entry(r)
+        summary[name] = summary_row(r)
+    extra = {}
+    if "C2" in [a.workload] + others and plain:
+        # the same stream through the three separate calls, and through the one-launch SGD driver
+        if not a.three_calls:
+            r3 = run_config("C2", flags, a.windows, three_calls=True, steps=1, warm=1)
+            extra["C2_three_calls"] = per_config_entry(r3)
+            summary["C2_three_calls"] = summary_row(r3)
+        if not a.no_train_stream:
+            ts = train_stream_leg(a.windows)
+            extra["C2_train_stream"] = ts
+            summary["C2_train_stream"] = [round(ts["ms_per_stream"], 4), round(ts["tokens_per_s"], 1),
+                                          "train_stream", round(ts["roofline"]["frac"], 4)]
+    if "C4" in [a.workload] + others and plain:
+        # the same configuration with the opt-in bf16 hi/lo split output layer
+        rb = run_config("C4", flags | rnn.FLAG_BF16X3_OUTPUT)
+        e = per_config_entry(rb)
+        e["flag"] = "RNN_FLAG_BF16X3_OUTPUT"
+        extra["C4_bf16x3_output"] = e
+        summary["C4_bf16x3_output"] = summary_row(rb)
+
     out = {
         "metric": "fwd+BPTT tokens/sec",
-        "value": wl.tokens_per_step * steps / wall,
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warm,
-        "ms_per_step": 1e3 * wall / steps,
+        "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 (output-layer products: bf16 hi/lo split, f32 accumulate)" if a.bf16x3 else "f32",
         "data": "synthetic",
-        "config": dict(workload=a.workload, **describe(wl.case),
-                       entry_points="rnn_window" if wl.fused else "rnn_forward,rnn_loss,rnn_bptt",
-                       recurrence_variant=rnn.rnn_recurrence_variant(wl.dims)),
-        "timesteps_per_s": wl.timesteps_per_step * steps / wall,
-        "gpu_event_ms_per_step": 1e3 * gpu_s / steps,
-        "roofline": roofline_of(prof, wl.case),
-        "rooflines_all_kernels": all_rooflines(prof, wl.case),
-        "kernels": {k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3),
-                            avg_us_raw=round(v["avg_us_raw"], 3),
-                            total_ms=round(v["total_ms"], 4)) for k, v in sorted(prof.items())},
-        "event_bracket_us": round(wl.bracket_us, 3),
-        "device": device_facts(torch),
-        "measured_ceilings": dict(MEASURED, note="saturating kernels of the library itself on this GPU: "
-                                  "device-memory copy (read + written bytes) and read (the larger is the HBM ceiling), 32x32x2 f32 and 32x32x16 bf16 "
-                                  "matrix products, 16-byte LDS reads; frac_measured in the roofline entries "
-                                  "is stated against these, frac against the published peaks"),
+        "config": dict(workload=a.workload, **head["describe"], entry_points=head["entry_points"],
+                       recurrence_variant=head["recurrence_variant"]),
+        # every configuration in one place: [ms per step, tokens/s, dominant kernel, its roofline fraction]
+        "summary": summary,
+        "timesteps_per_s": head["timesteps_per_s"],
+        "gpu_event_ms_per_step": head["gpu_event_ms_per_step"],
+        "roofline": head["roofline"],
     }
-    fused_headline = wl.fused
-    del wl
-    torch.cuda.empty_cache()
-
-    if fused_headline:
-        # the same workload through the three separate calls, for comparison
-        w3 = Workload(a.workload, flags, a.windows, three_calls=True)
-        wall3, _ = w3.time_steps(max(1, steps // 3), 1)
-        n3 = max(1, steps // 3)
-        pr3 = w3.profile(1)
-        out["three_call_path"] = dict(entry_points="rnn_forward,rnn_loss,rnn_bptt",
-                                      tokens_per_s=w3.tokens_per_step * n3 / wall3,
-                                      ms_per_step=1e3 * wall3 / n3,
-                                      roofline=roofline_of(pr3, w3.case),
-                                      kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
-                                               for k, v in sorted(pr3.items())})
-        del w3
-        torch.cuda.empty_cache()
-
-    per = {}
-    for name in [s for s in a.others.split(",") if s and s != "none" and s != a.workload]:
-        w = Workload(name, flags)
-        wall_o, _ = w.time_steps(default_steps[name], default_warm[name])
-        pr = w.profile(1)
-        per[name] = dict(tokens_per_s=w.tokens_per_step * default_steps[name] / wall_o,
-                         timesteps_per_s=w.timesteps_per_step * default_steps[name] / wall_o,
-                         ms_per_step=1e3 * wall_o / default_steps[name],
-                         recurrence_variant=rnn.rnn_recurrence_variant(w.dims),
-                         roofline=roofline_of(pr, w.case),
-                         kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
-                                  for k, v in sorted(pr.items())})
-        del w
-        torch.cuda.empty_cache()
-    if "C4" in per and not a.bf16x3 and not a.reference_kernels:
-        # the same configuration with the opt-in bf16 hi/lo split output layer
-        name = "C4"
-        w = Workload(name, flags | rnn.FLAG_BF16X3_OUTPUT)
-        wall_o, _ = w.time_steps(default_steps[name], default_warm[name])
-        pr = w.profile(1)
-        per["C4_bf16x3_output"] = dict(tokens_per_s=w.tokens_per_step * default_steps[name] / wall_o,
-                                       ms_per_step=1e3 * wall_o / default_steps[name],
-                                       flag="RNN_FLAG_BF16X3_OUTPUT",
-                                       roofline=roofline_of(pr, w.case),
-                                       kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 3))
-                                                for k, v in sorted(pr.items())})
-        del w
-        torch.cuda.empty_cache()
-    if per:
-        out["per_config"] = per
-
-    if a.workload == "C2" and not a.reference_kernels and not a.no_train_stream:
-        out["train_stream"] = train_stream_leg(a.windows)
-
-    if a.workload == "C2" and not a.no_mlp and not a.reference_kernels and not a.bf16x3:
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)
+    out["kernels"] = head["kernels"]
+    out["rooflines_all_kernels"] = head["rooflines_all_kernels"]
+    out["event_bracket_us"] = round(head["bracket_us"], 3)
+    if per or extra:
+        out["per_config"] = dict(per, **extra)
+    if not a.no_cpu_baseline and others:
+        out["oracle_timing"] = oracle_rows([n for n in others if n in ("C2", "C3", "C5")], a.cpu_seconds)
+    if plain and not a.no_mlp and others:
         out["mlp_workloads"] = mlp_leg()
         if not a.no_cpu_baseline:
             out["mlp_workloads"]["cpu_baseline"] = mlp_cpu_baseline()
-    if a.workload == "C2" and per and not a.reference_kernels and not a.bf16x3:
-        out["gauss_newton_vec"] = gauss_newton_leg([n for n in ("C3", "C4", "C5") if n in per])
-        if "C4" in per:
+    if plain and others:
+        gn = [n for n in ("C3", "C4", "C5") if n in [a.workload] + others]
+        out["gauss_newton_vec"] = gauss_newton_leg(gn)
+        if "C4" in gn:
             out["gauss_newton_vec"]["C4_bf16x3_output"] = gauss_newton_leg(["C4"], flags=rnn.FLAG_BF16X3_OUTPUT)["C4"]
-
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(a.workload, a.cpu_seconds)
-    print(json.dumps(out))
+    out["device"] = device_facts(torch)
+    out["measured_ceilings"] = dict(MEASURED, note="saturating kernels of the library itself on this GPU: "
+                                    "device-memory copy (read + written bytes) and read (the larger is the HBM ceiling), 32x32x2 f32 and 32x32x16 bf16 "
+                                    "matrix products, 16-byte LDS reads; frac_measured in the roofline entries "
+                                    "is stated against these, frac against the published peaks")
+    print(json.dumps(sig(out)))
 
 
 if __name__ == "__main__":

@@ -77,6 +77,10 @@ extern "C" {
  * sequence serve the output layer; rnn_gauss_newton_vec takes it too (its five output-layer
  * products); rejected by rnn_window and rnn_train_stream. */
 #define RNN_FLAG_BF16X3_OUTPUT 16u
+/* rnn_window only: launch cooperatively (the runtime then guarantees that all workgroups of the
+ * launch are resident together, at about 18 us more per launch) instead of the plain launch that
+ * relies on the precondition stated at rnn_window. */
+#define RNN_FLAG_COOPERATIVE 32u
 
 typedef struct {
     int32_t in_dim;     /* vocabulary size NV for token input, feature count D for dense input */
@@ -150,15 +154,25 @@ int rnn_check_tokens(const void *ids, int64_t n, int32_t limit, int32_t *bad_cou
  * rnn_workspace_init must be called once on a newly allocated workspace (and again whenever
  * the memory has been used for anything else) before the first rnn_forward / rnn_loss /
  * rnn_bptt with these dims: kernels of one launch pass small results to each other as words
- * that carry a per-call tag, and a cleared word is what "not written yet" looks like.  The call
- * is asynchronous on hip_stream and also clears the status word.
+ * that carry a per-launch tag, and a cleared word is what "not written yet" looks like.  The tag
+ * itself is a word of the workspace that the kernels advance (device state, nothing of it is
+ * baked into a launch's arguments), so calls captured into a HIP graph may be replayed.  The call
+ * is asynchronous on hip_stream and also clears the status word.  One workspace serves one stream
+ * at a time.
  *
  * Status word: the kernels that wait for other workgroups of their launch do so with a bounded
  * spin; if a wait ever expires (which needs the GPU to be shared in a way that keeps those
  * workgroups from running together) the kernel sets the word to 1, stops waiting, and the
- * results of that call are invalid.  rnn_workspace_status copies the word to *status_host and
- * synchronises the stream.
+ * results of that call are invalid, as are those of later calls until rnn_workspace_init has run
+ * on the workspace again.  rnn_workspace_status copies the word to *status_host and synchronises
+ * the stream.
+ *
+ * rnn_set_wait_limit sets the number of polls such a wait makes before it gives up (host state of
+ * the process, read when a call is enqueued; default 2^22, about a second; polls <= 0 restores the
+ * default).  For callers that share the GPU and prefer an early status 1 to a long spin, and for
+ * tests of the failure path.
  */
+int rnn_set_wait_limit(int polls);
 int rnn_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
                        void *hip_stream);
 int rnn_workspace_status(const rnn_dims *dims, const void *workspace, size_t workspace_bytes,
@@ -189,9 +203,10 @@ int rnn_workspace_status(const rnn_dims *dims, const void *workspace, size_t wor
  *            call clears what it uses) and may be shared with the other calls of this library
  *            on the same stream
  * Asynchronous like the other calls.  The launch is cooperative (1 + ceil(out_dim/128)
- * workgroups that wait for each other with bounded spins); rnn_train_stream_status copies the
- * workspace's status word to *status_host after synchronising the stream: 0 = every wait was
- * met, 1 = a wait expired and the results of that call are invalid.
+ * workgroups that wait for each other with bounded spins; the runtime guarantees that they are
+ * resident together); rnn_train_stream_status copies the workspace's status word to *status_host
+ * after synchronising the stream: 0 = every wait was met, 1 = a wait expired and the results of
+ * that call are invalid.
  */
 typedef struct { float *Wx, *Wh, *b, *V, *c; } rnn_params_inout; /* device pointers */
 int rnn_train_stream_workspace_bytes(const rnn_dims *dims, size_t *bytes);
@@ -212,9 +227,19 @@ int rnn_train_stream_status(const void *workspace, void *hip_stream, int32_t *st
  *   loss        device float32[1];  grads as in rnn_bptt (RNN_FLAG_ACCUMULATE adds)
  *   workspace   rnn_window_workspace_bytes() bytes, 16-byte aligned, cleared ONCE with
  *               rnn_window_workspace_init before its first use (the workgroups of the launch
- *               exchange words that carry a per-call tag; cleared memory is "not written yet")
- * The launch is cooperative (1 + ceil(out_dim/128) workgroups with bounded waits);
- * rnn_train_stream_status reads the status word of this workspace as well.
+ *               exchange words that carry a per-launch tag; cleared memory is "not written yet";
+ *               the tag is a word of the workspace that the kernel advances, so a captured call
+ *               may be replayed, and a workspace rnn_train_stream has used needs no new set-up)
+ * Launch form and its precondition: 1 + ceil(out_dim/128) workgroups that wait for each other
+ * with bounded spins.  By default this is a PLAIN launch (a cooperative one costs about 18 us more,
+ * the time of a whole window at the benchmark shape), used only when the whole grid fits the chip
+ * by itself (checked on the host; otherwise the launch is cooperative): it is correct as long as
+ * no other kernel occupies the GPU's compute units while the call runs -- other streams of the
+ * process must be idle or hold only kernels that leave room for the grid.  A caller that cannot
+ * promise that sets RNN_FLAG_COOPERATIVE.  If the precondition is broken the waits expire
+ * (rnn_set_wait_limit), the status word becomes 1 and the outputs of that call are invalid:
+ * callers that share the GPU must read rnn_train_stream_status (which reads the status word of
+ * this workspace as well) before they trust a window's results.
  */
 int rnn_window_workspace_bytes(const rnn_dims *dims, size_t *bytes);
 int rnn_window_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
@@ -294,7 +319,8 @@ int rnn_gauss_newton_vec(const rnn_dims *dims, const rnn_params *params, const r
  *
  * rnn_mlp_train runs n_batches consecutive batches in one call (the paper's function objects
  * offer the same as a repeat count, "several iterations at once"): nothing returns to the host
- * between batches, every batch is 3 n_hidden + 3 launches on hip_stream.
+ * between batches, every batch is 2 n_hidden + 2 launches on hip_stream (one more with more than
+ * 16 classes).
  *   dims     host struct; act = RNN_ACT_* of the hidden layers; flags: RNN_FLAG_SYNC only;
  *            n_hidden + 1 <= RNN_MLP_MAX_LAYERS; batch <= 1024 (else RNN_EUNSUPPORTED)
  *   params   host struct of device pointers, layer l = 0..n_hidden (input side first):

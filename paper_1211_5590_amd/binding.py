@@ -17,10 +17,11 @@ ACT_SIGMOID, ACT_TANH = 0, 1
 LOSS_SOFTMAX_CE, LOSS_LINEAR_MSE = 0, 1
 FLAG_ACCUMULATE, FLAG_SYNC, FLAG_BPTT_RECOMPUTE, FLAG_REFERENCE_KERNELS = 1, 2, 4, 8
 FLAG_BF16X3_OUTPUT = 16
+FLAG_COOPERATIVE = 32
 
 EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_check_tokens",
            "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",
-           "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init",
+           "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init", "rnn_set_wait_limit",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
            "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
            "rnn_window", "rnn_window_static", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
@@ -102,6 +103,8 @@ def lib():
         L.rnn_recurrence_workgroups.restype = ctypes.c_int
         L.rnn_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
         L.rnn_workspace_status.argtypes = [ctypes.POINTER(Dims), vp, sz, vp, ctypes.POINTER(ctypes.c_int32)]
+        L.rnn_set_wait_limit.argtypes = [ctypes.c_int]
+        L.rnn_set_wait_limit.restype = ctypes.c_int
         L.rnn_workspace_init.restype = ctypes.c_int
         L.rnn_workspace_status.restype = ctypes.c_int
         L.rnn_profile_begin.argtypes = [ctypes.c_int]
@@ -307,6 +310,10 @@ def rnn_profile_end() -> dict:
     _check(L.rnn_profile_end(n, counts, ms))
     return {L.rnn_profile_kernel_name(k).decode(): (int(counts[k]), float(ms[k]))
             for k in range(n) if counts[k] > 0}
+
+
+def rnn_set_wait_limit(polls: int) -> None:
+    _check(lib().rnn_set_wait_limit(int(polls)))
 
 
 def rnn_workspace_init(dims, workspace, stream=None) -> None:

@@ -13,14 +13,7 @@ namespace {
 
 using namespace rnn;
 
-// Tag of the self-validating words one call exchanges between its workgroups: unique per call
-// in this process, never 0 (the value of a cleared workspace).
-uint32_t next_epoch() {
-    static std::atomic<uint32_t> counter{0};
-    uint32_t e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
-    if (e == 0) e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
-    return e;
-}
+std::atomic<int> g_wait_limit{1 << 22};
 
 constexpr size_t kAlign = 256;
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -54,7 +47,7 @@ bool dims_valid(const rnn_dims* d) {
     if (d->act != RNN_ACT_SIGMOID && d->act != RNN_ACT_TANH) return false;
     if (d->loss_kind != RNN_LOSS_SOFTMAX_CE && d->loss_kind != RNN_LOSS_LINEAR_MSE) return false;
     if (d->flags & ~(RNN_FLAG_ACCUMULATE | RNN_FLAG_SYNC | RNN_FLAG_BPTT_RECOMPUTE |
-                     RNN_FLAG_REFERENCE_KERNELS | RNN_FLAG_BF16X3_OUTPUT))
+                     RNN_FLAG_REFERENCE_KERNELS | RNN_FLAG_BF16X3_OUTPUT))   // RNN_FLAG_COOPERATIVE: rnn_window only
         return false;
     const long long N = (long long)d->seq_len * d->batch;
     // keep every row index and every N*width product the kernels form inside int32 / size_t
@@ -249,6 +242,8 @@ SkinnyArgs skinny_args(const rnn_dims* d, const rnn_params* P, const float* h_al
     k.y = static_cast<const int32_t*>(targets);
     k.Z = at<float>(ws, pl.Z); k.stat_box = at<unsigned long long>(ws, pl.statbox);
     k.status = at<int32_t>(ws, pl.scratch) + 1;
+    k.epoch_word = at<uint32_t>(ws, pl.scratch) + 2;   // the launches' tags are device state
+    k.spin_limit = wait_limit();
     k.lse = at<float>(ws, pl.lse); k.gpart = at<float>(ws, pl.gpart); k.vy = at<float>(ws, pl.vy);
     k.H = z.H; k.O = z.O; k.N = (int)z.N; k.NV = z.NVin;
     return k;
@@ -260,7 +255,6 @@ hipError_t run_loss(const rnn_dims* d, const rnn_params* P, const float* h_all, 
     const int N = (int)z.N;
     if (pick_variant(d).skinny) {
         SkinnyArgs k = skinny_args(d, P, h_all, targets, ws, pl);
-        k.epoch = next_epoch();
         k.loss = loss;
         return launch_skinny_logits(k, s);
     }
@@ -491,9 +485,8 @@ hipError_t run_bptt(const rnn_dims* d, const rnn_params* P, const void* x, const
         k.dWx_zero = beta ? nullptr : Gr->dWx;
         k.xids = static_cast<const int32_t*>(x);
         r.gpart = k.gpart; r.gstrips = skinny_strips(O); r.Gw = G;
-        k.epoch = next_epoch();
         k.g_box = at<unsigned long long>(ws, pl.gbox);
-        r.g_box = k.g_box; r.epoch = k.epoch;
+        r.g_box = k.g_box;
         r.fuse_post = 1; r.x = static_cast<const int32_t*>(x);
         r.dWh = Gr->dWh; r.db = Gr->db; r.dWx = Gr->dWx; r.beta = beta;
         return launch_rec_bwd_with_strips(r, v.bwd, k, s);
@@ -652,7 +645,16 @@ bool reference_supported(const rnn_dims* d) { return d->hidden <= 8192; }
 
 }  // namespace
 
+namespace rnn {
+int wait_limit() { return g_wait_limit.load(std::memory_order_relaxed); }
+}  // namespace rnn
+
 extern "C" {
+
+int rnn_set_wait_limit(int polls) {
+    g_wait_limit.store(polls > 0 ? polls : (1 << 22), std::memory_order_relaxed);
+    return RNN_OK;
+}
 
 int rnn_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
     if (!dims_valid(dims) || !bytes) return RNN_EINVAL;

@@ -118,6 +118,21 @@ __device__ __forceinline__ bool tagged_ok(unsigned long long w, unsigned tag) {
 __device__ __forceinline__ float tagged_value(unsigned long long w) {
     return __uint_as_float((unsigned)w);
 }
+// Tags of consecutive launches on one set of boxes are device state: a word next to the boxes holds
+// the tag the previous launch used; every workgroup of a launch reads it on entry, uses the next
+// tag, and one workgroup that can only finish after all the others have started stores the new
+// value at its end.  (A tag drawn on the host would be baked into the launch's arguments, and a
+// replayed HIP graph would then meet its own tag in the words its previous replay left behind.)
+__device__ __forceinline__ unsigned next_tag(unsigned previous) {
+    const unsigned t = previous + 1u;
+    return t ? t : 1u;           // 0 is what cleared memory holds: never a tag
+}
+__device__ __forceinline__ unsigned tag_word_load(const unsigned* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void tag_word_store(unsigned* p, unsigned tag) {
+    __hip_atomic_store(p, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 // polls until the tag shows up; false when the bounded wait expires
 __device__ __forceinline__ bool tagged_wait(const unsigned long long* p, unsigned tag, int spin_limit,
                                             float& v) {

@@ -109,7 +109,8 @@ struct RecResArgs {
     // Short single sequence (fuse_post): G is produced by the other workgroups of the launch
     // (gpart non-NULL marks this mode; otherwise G is given)
     const float* gpart; int gstrips; float* Gw;
-    const unsigned long long* g_box; uint32_t epoch;   // G arrives as tagged words [T][H]
+    const unsigned long long* g_box; uint32_t epoch;   // G arrives as tagged words [T][H]; the fused
+                                                       // launch fills epoch from the tag word
 };
 struct RecResPlan { int P, R, L, ldw, w_floats, nq4, hpad; size_t smem; };
 // strips: column strips of the short-sequence output layer (fuse_post only, else 0)
@@ -144,6 +145,8 @@ hipError_t launch_gather_input(const int32_t* x, const float* Wx, const float* b
 hipError_t launch_rec_batch_mfma(const RecMfmaArgs& a, bool bwd, hipStream_t s);
 
 hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s);
+// polls a bounded wait between workgroups makes before it gives up (host state, rnn_set_wait_limit)
+int wait_limit();
 hipError_t launch_transpose(const float* src, float* dst, int rows, int cols, hipStream_t s);
 hipError_t launch_rec_fwd_reference(const RecFwdArgs& a, hipStream_t s);
 hipError_t launch_rec_bwd_reference(const RecBwdArgs& a, hipStream_t s);
@@ -177,7 +180,9 @@ struct SkinnyArgs {
     float* Z;             // [N,O] logits (workspace)
     unsigned long long* stat_box;  // tagged words: [N][strips][2] strip max / sum exp, then [N] target logits
     unsigned long long* g_box;     // tagged words: [N][H] G, from the backward strips to the reverse loop
-    uint32_t epoch;       // tag of this call's words (never 0)
+    uint32_t epoch;       // tag of this launch's words (never 0): filled in by the kernel from *epoch_word
+    uint32_t* epoch_word; // device word: tag of the last launch on these boxes (see next_tag)
+    int spin_limit;       // polls a bounded wait makes before it gives up
     int32_t* status;      // device status word: set to 1 when a bounded wait expires
     float* loss;          // device scalar written by the merging workgroup (logits kernel)
     float* lse;           // [N]

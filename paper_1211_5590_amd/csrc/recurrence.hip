@@ -520,13 +520,23 @@ __global__ __launch_bounds__(kThreads) void rec_resident_kernel(RecResArgs a) {
 
 // Backward pass of a short single sequence in one launch: workgroup 0 runs the reverse time loop
 // with the fused weight gradients, workgroups 1.. run the backward strips of the output layer
-// (dV, dc, zero fill of dWx).  The two parts share no data inside the launch.
+// (their slices of G first, then dV, dc, zero fill of dWx).  Workgroup 0 waits, with a bounded
+// spin, for the slices of G the strip workgroups of this same launch publish as tagged words; it
+// therefore ends after every strip that publishes anything has read the launch's tag, and records
+// that tag for the next launch on these boxes.
 template <int ACT>
 __global__ __launch_bounds__(kThreads) void rec_bwd_with_strips_kernel(RecResArgs a, SkinnyArgs k) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     static_assert(skinny::NTH == kThreads, "both parts use the same workgroup size");
-    if (blockIdx.x == 0) rec_resident_body<ACT, true>(a, 0, 0, smem);
-    else skinny::back_body(k, (int)blockIdx.x - 1, (int)gridDim.x - 1, smem);
+    const unsigned tag = next_tag(tag_word_load(k.epoch_word));
+    a.epoch = tag;
+    k.epoch = tag;
+    if (blockIdx.x == 0) {
+        rec_resident_body<ACT, true>(a, 0, 0, smem);
+        if (threadIdx.x == 0) tag_word_store(k.epoch_word, tag);
+    } else {
+        skinny::back_body(k, (int)blockIdx.x - 1, (int)gridDim.x - 1, smem);
+    }
 }
 
 __global__ void zero_words_kernel(int32_t* p, int n) {
@@ -545,7 +555,7 @@ hipError_t launch_rec_bwd_with_strips(RecResArgs a, const RecResPlan& pl, const 
     if (pl.P != 1 || a.B != 1 || !a.fuse_post) return hipErrorInvalidValue;
     a.P = pl.P; a.R = pl.R; a.L = pl.L; a.ldw = pl.ldw; a.w_floats = pl.w_floats;
     a.nq4 = pl.nq4; a.hpad = pl.hpad;
-    if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
+    if (a.spin_limit <= 0) a.spin_limit = wait_limit();
     const void* fn = a.act == 0 ? (const void*)rec_bwd_with_strips_kernel<0>
                                 : (const void*)rec_bwd_with_strips_kernel<1>;
     size_t smem = pl.smem;
@@ -612,7 +622,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s) {
     a.P = pl.P; a.R = pl.R; a.L = pl.L; a.ldw = pl.ldw; a.w_floats = pl.w_floats;
     a.nq4 = pl.nq4; a.hpad = pl.hpad;
-    if (a.spin_limit <= 0) a.spin_limit = 1 << 22;
+    if (a.spin_limit <= 0) a.spin_limit = wait_limit();
     if (pl.P > 1) {
         // exchange boxes: 2 parities x B rows x H words of 64 bits
         hipError_t e = launch_zero_words(a.flags, 4 * a.B * a.H, s);

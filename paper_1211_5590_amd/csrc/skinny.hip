@@ -33,6 +33,7 @@ constexpr int ES = CW + 4;   // padded LDS row of 128 columns
 
 __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
+    a.epoch = next_tag(tag_word_load(a.epoch_word));   // requested first, needed at the first publish
     const int H = a.H, O = a.O, N = a.N;
     float* hs = smem;                 // [H][NR]
     float* red = hs + H * NR;         // [NWV][NR][CW] partial logits; later a stage for the merge
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
     if (tid == 0) s_fail = 0;
     __syncthreads();                     // also: `red` is free from here on
     const int strips = gridDim.x;
-    const int spin_limit = 1 << 22;
+    const int spin_limit = a.spin_limit;
     const unsigned epoch = a.epoch;
     // All words of a group of rows are requested at once (four per thread in flight), parked in
     // LDS, and merged from there: the waiting costs about one memory round trip in total.
@@ -254,6 +255,8 @@ __global__ __launch_bounds__(NTH) void skinny_logits_kernel(SkinnyArgs a) {
         float t = 0.f;
         for (int n = 0; n < N; ++n) t += rl[n];
         *a.loss = t / (float)N;
+        // this workgroup has seen every strip's words, so every strip has read the tag: record it
+        tag_word_store(a.epoch_word, epoch);
     }
 }
 

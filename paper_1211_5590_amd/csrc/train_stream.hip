@@ -63,7 +63,9 @@ struct StreamArgs {
     const int32_t* ids;                   // inputs: [n_windows*T (+ 1)]
     const int32_t* ys;                    // targets, same stride (stream mode: ids + 1)
     long long n_windows;
-    unsigned tag0;                        // tag of the first window's words (never 0)
+    unsigned tag0;                        // tag of the first window's words (never 0); the one-window
+                                          // kernel takes it from *tagword instead
+    unsigned* tagword;                    // device word: tag of the last window run on these boxes
     // gradient mode (one window, parameters untouched)
     float *dWx, *dWh, *db, *dV, *dc;
     int beta, NVin;                       // beta: add to the gradient buffers; NVin: rows of Wx
@@ -1180,18 +1182,30 @@ __device__ __forceinline__ void loop_body_grad(const StreamArgs& a, float* smem)
     TS_FLUSH;
 }
 
+// The loop workgroup cannot finish a window before every strip has started (each element of G needs
+// every strip's share), so it is the one that records the last tag used on these boxes, for the
+// next launch on them.
 template <int ACT, int NQ>
 __global__ __launch_bounds__(NT) void train_stream_kernel(StreamArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    if (blockIdx.x == 0) loop_body<ACT, NQ>(a, smem);
-    else strip_body<NQ, 0>(a, (int)blockIdx.x - 1, smem);
+    if (blockIdx.x == 0) {
+        loop_body<ACT, NQ>(a, smem);
+        if (threadIdx.x == 0) tag_word_store(a.tagword, a.tag0 + (unsigned)(a.n_windows - 1));
+    } else {
+        strip_body<NQ, 0>(a, (int)blockIdx.x - 1, smem);
+    }
 }
 
 template <int ACT, int NQ>
 __global__ __launch_bounds__(NT) void window_kernel(StreamArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    if (blockIdx.x == 0) loop_body_grad<ACT, NQ>(a, smem);
-    else strip_body<NQ, 1>(a, (int)blockIdx.x - 1, smem);
+    a.tag0 = next_tag(tag_word_load(a.tagword));   // requested first; needed at the first exchange
+    if (blockIdx.x == 0) {
+        loop_body_grad<ACT, NQ>(a, smem);
+        if (threadIdx.x == 0) tag_word_store(a.tagword, a.tag0);
+    } else {
+        strip_body<NQ, 1>(a, (int)blockIdx.x - 1, smem);
+    }
 }
 
 template <int ACT>
@@ -1260,7 +1274,7 @@ int stream_supported(const rnn_dims* d) {
 int window_supported(const rnn_dims* d) {
     if (!d) return RNN_EINVAL;
     rnn_dims t = *d;
-    if (t.flags & ~(RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE)) return RNN_EINVAL;
+    if (t.flags & ~(RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE | RNN_FLAG_COOPERATIVE)) return RNN_EINVAL;
     t.flags &= RNN_FLAG_SYNC;
     if (t.in_dim <= 0) return RNN_EINVAL;
     t.in_dim = t.out_dim;
@@ -1271,17 +1285,14 @@ void bind_boxes(StreamArgs& a, void* workspace, const StreamPlan& pl) {
     char* ws = static_cast<char*>(workspace);
     a.S = pl.S;
     a.status = reinterpret_cast<int32_t*>(ws + pl.status);
+    a.tagword = reinterpret_cast<unsigned*>(ws + pl.status) + 1;
     a.hbox = reinterpret_cast<unsigned long long*>(ws + pl.hbox);
     a.gbox = reinterpret_cast<unsigned long long*>(ws + pl.gbox);
     a.vybox = reinterpret_cast<unsigned long long*>(ws + pl.vybox);
     a.zybox = reinterpret_cast<unsigned long long*>(ws + pl.zybox);
     a.statbox = reinterpret_cast<unsigned long long*>(ws + pl.statbox);
     a.pbox = reinterpret_cast<unsigned long long*>(ws + pl.pbox);
-    a.spin_limit = 1 << 22;
-    if (const char* env = getenv("RNN_STREAM_SPIN_LIMIT")) {   // failure-path tests: make waits expire
-        const long v = strtol(env, nullptr, 10);
-        if (v > 0 && v < (1L << 30)) a.spin_limit = (int)v;
-    }
+    a.spin_limit = wait_limit();
 }
 
 // dynamic LDS above 64 KB has to be allowed once per kernel
@@ -1297,11 +1308,26 @@ hipError_t allow_lds(const void* fn, size_t bytes) {
     return e;
 }
 
-uint32_t next_window_tag() {
-    static std::atomic<uint32_t> counter{0};
-    uint32_t e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
-    if (e == 0) e = counter.fetch_add(1, std::memory_order_relaxed) + 1;
-    return e;
+// Can `blocks` workgroups of this kernel be resident at once on the current device?  The
+// one-window kernels wait for each other inside the launch, so a plain launch is only used when
+// the whole grid fits the chip by itself; otherwise the launch is cooperative (the runtime then
+// refuses what cannot be co-resident instead of letting it spin).  Asked once per kernel and size.
+bool fits_the_chip(const void* fn, size_t lds, int blocks) {
+    struct Seen { const void* fn; size_t lds; int dev; int capacity; };
+    static Seen seen[32];
+    static int n_seen = 0;
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < n_seen; ++i)
+        if (seen[i].fn == fn && seen[i].lds == lds && seen[i].dev == dev) return blocks <= seen[i].capacity;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, NT, lds) != hipSuccess) return false;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+    const int capacity = per_cu * cus;
+    if (n_seen < 32) seen[n_seen++] = Seen{fn, lds, dev, capacity};
+    return blocks <= capacity;
 }
 
 // Argument checks shared by the two forms of the one-window call.
@@ -1332,7 +1358,7 @@ int launch_window(const rnn_dims* dims, const rnn_params* params, const int32_t*
     StreamArgs a{};
     a.Wx = const_cast<float*>(params->Wx); a.Wh = const_cast<float*>(params->Wh);
     a.b = const_cast<float*>(params->b); a.V = const_cast<float*>(params->V); a.c = const_cast<float*>(params->c);
-    a.ids = x; a.ys = targets; a.n_windows = 1; a.lr = 1.0f; a.tag0 = next_window_tag();
+    a.ids = x; a.ys = targets; a.n_windows = 1; a.lr = 1.0f; a.tag0 = 0u;   // the kernel reads the tag word
     a.h0 = h0; a.h_last = h_last; a.losses = loss; a.h_all = h_all; a.dh_last = dh_last; a.dh0 = dh0;
     a.dWx = grads->dWx; a.dWh = grads->dWh; a.db = grads->db; a.dV = grads->dV; a.dc = grads->dc;
     a.beta = (dims->flags & RNN_FLAG_ACCUMULATE) ? 1 : 0;
@@ -1350,8 +1376,9 @@ int launch_window(const rnn_dims* dims, const rnn_params* params, const int32_t*
     {
         ProfileScope ps(K_WINDOW, s);
         void* args[] = {&a};
-        e = getenv("RNN_WINDOW_COOP") ? hipLaunchCooperativeKernel(fn, dim3(1 + a.S), dim3(NT), args, (unsigned)lds, s)
-                                      : hipLaunchKernel(fn, dim3(1 + a.S), dim3(NT), args, lds, s);
+        const bool coop = (dims->flags & RNN_FLAG_COOPERATIVE) || !fits_the_chip(fn, lds, 1 + a.S);
+        e = coop ? hipLaunchCooperativeKernel(fn, dim3(1 + a.S), dim3(NT), args, (unsigned)lds, s)
+                 : hipLaunchKernel(fn, dim3(1 + a.S), dim3(NT), args, lds, s);
     }
     if (e != hipSuccess) return RNN_EHIP;
     if (dims->flags & RNN_FLAG_SYNC)

@@ -120,18 +120,20 @@ def test_zero_windows_and_unsupported_shapes():
         assert torch.equal(params[k], before[k])
 
 
-def test_expired_wait_sets_the_status_word_and_the_grid_drains(monkeypatch):
+def test_expired_wait_sets_the_status_word_and_the_grid_drains():
     # failure handling forced from the host: with a spin limit of one poll the waits between the
     # workgroups expire at once; every workgroup must leave, and the status word must say so
-    monkeypatch.setenv("RNN_STREAM_SPIN_LIMIT", "1")
+    rnn.rnn_set_wait_limit(1)
     case = ri.make_config("C2", windows=4)
     dims = rnn.Dims.of(case)
     params = {k: dev(case[k]) for k in PNAMES}
     ws = torch.zeros(rnn.rnn_train_stream_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
-    rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 4, 0.1, None, None, None, ws)
-    torch.cuda.synchronize()
+    try:
+        rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 4, 0.1, None, None, None, ws)
+        torch.cuda.synchronize()
+    finally:
+        rnn.rnn_set_wait_limit(0)
     assert rnn.rnn_train_stream_status(ws) == 1
-    monkeypatch.delenv("RNN_STREAM_SPIN_LIMIT")
     params = {k: dev(case[k]) for k in PNAMES}     # and the next call on the same workspace is fine
     losses = torch.zeros(4, device="cuda")
     rnn.rnn_train_stream(dims, params, dev(ri.stream_ids(case).reshape(-1)), 4, 0.1, None, None, losses, ws)
