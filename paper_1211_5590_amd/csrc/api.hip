@@ -31,6 +31,8 @@ struct Variant {
     bool stepwise;        // batched recurrence as one fused MFMA launch per step
     bool batch_mfma;      // batched persistent loop, weights in registers (H <= 256)
     RecResPlan fwd, bwd;  // plans of the two loops when resident
+    bool grid;            // several workgroups per sequence, role-split form (recurrence_grid.hip)
+    RecGridPlan gplan;
 };
 
 struct Sizes {
@@ -93,6 +95,7 @@ Variant pick_variant(const rnn_dims* d) {
         v.stepwise = !v.batch_mfma && s.B > 4;
         return v;
     }
+    v.grid = (v.fwd.P > 1 || v.bwd.P > 1) && rec_grid_plan(s.H, s.B, &v.gplan);
     RecResPlan fused;
     if (s.tokens && s.ce && s.B == 1 && skinny_supported((int)s.N, s.H, s.O) &&
         rec_resident_plan(s.H, s.B, s.T, true, true, skinny_strips(s.O), &fused)) {
@@ -220,6 +223,7 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         r.flags = at<int32_t>(ws, pl.flags); r.status = at<int32_t>(ws, pl.scratch) + 1;
         r.Wx = P->Wx; r.b = P->b; r.x = a.x; r.U = a.U; r.h0 = h0;
         r.hist = a.hist; r.h_last = h_last; r.ring = a.ring;
+        if (v.grid) return launch_rec_grid(r, v.gplan, false, s);
         return launch_rec_resident(r, v.fwd, false, s);
     }
     if (v.batch_mfma) {
@@ -333,6 +337,7 @@ hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT
         r.Wh = Wh; r.H = H; r.T = z.T; r.B = z.B; r.act = d->act;
         r.flags = at<int32_t>(ws, pl.flags); r.status = at<int32_t>(ws, pl.scratch) + 1;
         r.G = G; r.h_all = h_all; r.dh_last = dh_last; r.Delta = Delta; r.dh0 = dh0;
+        if (v.grid) return launch_rec_grid(r, v.gplan, true, s);
         return launch_rec_resident(r, v.bwd, true, s);
     }
     if (v.batch_mfma) {
@@ -760,7 +765,7 @@ const char* rnn_recurrence_variant(const rnn_dims* dims) {
     if (v.batch_mfma) return "batch_mfma";
     if (v.stepwise) return "step_mfma";
     if (!v.resident) return "reference";
-    return v.fwd.P == 1 ? "wg_resident" : "grid_resident";
+    return (v.fwd.P == 1 && !v.grid) ? "wg_resident" : "grid_resident";
 }
 
 int rnn_recurrence_workgroups(const rnn_dims* dims) {
@@ -770,6 +775,7 @@ int rnn_recurrence_workgroups(const rnn_dims* dims) {
     if (v.batch_mfma) return (s.B + 3) / 4;
     if (v.stepwise) return ((s.H + 15) / 16) * ((s.B + 15) / 16);   // tiles of one step launch
     if (!v.resident) return s.B;
+    if (v.grid) return v.gplan.P * s.B;
     return v.fwd.P * s.B;
 }
 

@@ -99,6 +99,7 @@ struct RecResArgs {
     int32_t* status;             // device status word: set to 1 when a bounded wait expires
     int spin_limit;              // <= 0: default
     int xcd_pack;                // set by the launcher: workgroup p of a sequence is blockIdx.x / 8 (see the kernel)
+    int poll_sleep;              // role-split loop: pauses of 64 clocks between a workgroup's own stores and its first poll
     // forward
     const float* Wx; const float* b; const int32_t* x; const float* U; const float* h0;
     float* hist; float* h_last; int ring;
@@ -116,6 +117,12 @@ struct RecResPlan { int P, R, L, ldw, w_floats, nq4, hpad; size_t smem; };
 // strips: column strips of the short-sequence output layer (fuse_post only, else 0)
 bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips, RecResPlan* out);
 hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hipStream_t s);
+// The same loop for sequences whose matrix needs several compute units, with the wavefronts of a
+// workgroup split into computing and polling ones (recurrence_grid.hip).  Serves what the resident
+// plan gives more than one workgroup, as long as the slice fits the registers of four wavefronts.
+struct RecGridPlan { int P, R, OPW, hpad; size_t smem; };
+bool rec_grid_plan(int H, int B, RecGridPlan* out);
+hipError_t launch_rec_grid(RecResArgs a, const RecGridPlan& pl, bool bwd, hipStream_t s);
 struct SkinnyArgs;
 // reverse loop with fused weight gradients (workgroup 0) and the output layer's backward strips
 // (one workgroup per strip) in one launch; a must have fuse_post set

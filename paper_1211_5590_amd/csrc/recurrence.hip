@@ -39,6 +39,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int NL = 20;         // independent global loads in flight per thread during setup
 
+// Optional phase timing for tuning (-DRNN_REC_TRACE): two threads of the first workgroup (a polling
+// one and a publishing one) sum the shader-clock cycles between consecutive marks over all steps.
+#ifdef RNN_REC_TRACE
+__device__ long long g_rec_trace[4 * 8];
+#define RT_DECL long long rt_prev = clock64(); long long rt_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define RT(k) do { const long long rt_n = clock64(); rt_acc[k] += rt_n - rt_prev; rt_prev = rt_n; } while (0)
+#define RT_FLUSH(bwd) do { if (p == 0 && bb == 0 && (tid == 0 || tid == kThreads - kWave)) \
+        for (int k_ = 0; k_ < 8; ++k_) g_rec_trace[((bwd ? 2 : 0) + (tid == 0 ? 0 : 1)) * 8 + k_] = rt_acc[k_]; } while (0)
+#else
+#define RT_DECL
+#define RT(k)
+#define RT_FLUSH(bwd)
+#endif
+
 // The time loops use lds_barrier() (common.hpp): __syncthreads() also waits for every outstanding
 // global load and store, which would put a DRAM round trip on each step; the steps exchange the
 // state vector through LDS, so LDS ordering is enough.
@@ -61,8 +75,8 @@ __device__ __forceinline__ float group_sum(float v, int L) {
     if (L >= 4) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
     if (L >= 8) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
     if (L >= 16) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
-    if (L >= 32) v += __shfl_xor(v, 16, kWave);
-    if (L >= 64) v += __shfl_xor(v, 32, kWave);
+    if (L >= 32) v = swap16_sum(v);     // rows of 16 lanes swapped between two registers: no LDS trip
+    if (L >= 64) v = swap32_sum(v);
     return v;
 }
 
@@ -344,7 +358,9 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
                          : a.hist + ((size_t)B + bb) * H;          // slot 1 = result of step 0
     float* const out_even = BWD ? nullptr : a.hist + (size_t)bb * H;               // ring slot 0
     float* const out_odd = BWD ? nullptr : a.hist + ((size_t)B + bb) * H;          // ring slot 1
+    RT_DECL;
     for (int s = 0; s < nsteps; ++s) {
+        RT(0);
         const int chunk = s / TC, su = s - chunk * TC;
         float* st = stash + (size_t)(chunk & 1) * TC * 2 * R;
         if (su == 0 && lead) {
@@ -369,7 +385,9 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
                 x0 = (BWD && a.gpart) ? Gl[t * H + j] : st[(su * 2) * R + own];
                 if (BWD) x1 = st[(su * 2 + 1) * R + own];
             }
+            RT(5);
             const float acc = slice_dot(v);
+            RT(6);
             if (lead) {
                 val = BWD ? (x0 + acc) * act_grad<ACT>(x1) : activate<ACT>(acc + x0);
                 if (P == 1) out_row[j] = val;   // P > 1: after the exchange, off its critical path
@@ -381,17 +399,19 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
             // Exchange of the new state between the P workgroups of this sequence.  Every value
             // travels as one 64-bit word {step tag, value}, written and polled with relaxed
             // device-scope atomics: the tag makes each word self-validating, so there is no
-            // separate flag, no fence and a single memory round trip per step.  Two boxes
-            // alternate by step parity; a box is overwritten two steps later, and by then every
-            // workgroup has read it (nobody publishes step s+1 before its own barrier below,
+            // separate flag, no fence and a single memory round trip per step.  Two sets of boxes
+            // alternate by step parity; a box is overwritten two steps later, and by then its
+            // reader has read it (nobody publishes step s+1 before its own barrier below,
             // and step s+2 needs everybody's step s+1).  The boxes start zeroed: tags are >= 1.
             const unsigned tag = (unsigned)(s + 1);
             unsigned long long* box = reinterpret_cast<unsigned long long*>(a.flags) +
                                       ((size_t)(s & 1) * B + bb) * H;
+            RT(1);
             // The last wavefront publishes the slice (and writes the history row); the others
             // poll.  A wavefront that polls right after storing would first wait for its own
             // stores to be acknowledged, once per step.
             lds_barrier();                        // the slice's new values are in vnext
+            RT(2);
             if (tid >= kThreads - kWave) {
                 for (int o = tid - (kThreads - kWave); o < rows; o += kWave) {
                     const float v = vnext[r0 + o];
@@ -399,18 +419,26 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
                     out_row[r0 + o] = v;
                 }
             } else {
-                for (int j = tid; j < H; j += kThreads - kWave) {
-                    if (j >= r0 && j < r0 + rows) continue;   // own slice: already in LDS
-                    int spins = 0;
-                    unsigned long long w;
-                    while ((unsigned)((w = __hip_atomic_load(box + j, __ATOMIC_RELAXED,
-                                                             __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tag) {
-                        if (++spins > a.spin_limit) { s_abort = 1; break; }
+                // all of a thread's words are requested before the first one is examined, and the
+                // stale ones are requested again together: one memory round trip however many
+                // words a thread collects (one poll after the other would cost a round trip each)
+                for (int j0 = tid; j0 < H; j0 += 4 * (kThreads - kWave)) {
+                    long long idx[4];
+                    unsigned long long w[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u * (kThreads - kWave);
+                        idx[u] = (j < H && (j < r0 || j >= r0 + rows)) ? j : -1;   // own slice: already in LDS
                     }
-                    vnext[j] = __uint_as_float((unsigned)w);
+                    if (!wait4(box, idx, tag, a.spin_limit, w)) s_abort = 1;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (idx[u] >= 0) vnext[idx[u]] = tagged_value(w[u]);
                 }
             }
+            RT(3);
             lds_barrier();
+            RT(4);
             if (s_abort) {
                 if (tid == 0) atomicExch(a.status, 1);
                 return;  // uniform: the whole workgroup leaves
@@ -420,6 +448,7 @@ __device__ __forceinline__ void rec_resident_body(const RecResArgs& a, const int
         }
         cur ^= 1;
     }
+    RT_FLUSH(BWD);
     __syncthreads();
 
     const float* vfin = vbuf + cur * Hp;
@@ -611,7 +640,11 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips
             found = true;
             // A single workgroup pays no exchange; once the state is exchanged anyway, more
             // workgroups are cheap, so keep splitting until the slice fits in registers.
+#ifdef RNN_FORCE_P
+            if (P == 1 || (pl.nq4 <= 8 && P >= RNN_FORCE_P)) return true;
+#else
             if (P == 1 || pl.nq4 <= 8) return true;
+#endif
             continue;
         }
         if (fuse_post) return false;  // the fused tail needs the single-workgroup form
@@ -660,3 +693,9 @@ hipError_t launch_rec_resident(RecResArgs a, const RecResPlan& pl, bool bwd, hip
 }
 
 }  // namespace rnn
+
+#ifdef RNN_REC_TRACE
+extern "C" int rnn_rec_trace(long long* host_out, int n) {
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(rnn::g_rec_trace), (size_t)n * 8) == hipSuccess ? 0 : -4;
+}
+#endif
