@@ -234,6 +234,16 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         m.U = U; m.h0 = h0; m.hist = a.hist; m.h_last = h_last; m.ring = a.ring;
         return launch_rec_batch_mfma(m, false, s);
     }
+    if (v.stepwise && h_all && rec_xcd_supported(z.H, z.B) && rec_xcd_ready(z.H, d->act, false)) {
+        // one persistent launch for all steps (one batch group per XCD)
+        float* U = at<float>(ws, pl.U);
+        if (z.tokens) RNN_TRY(launch_gather_input(a.x, P->Wx, P->b, U, (int)z.N, z.H, s));
+        RecXcdArgs m{};
+        m.Wh = P->Wh; m.H = z.H; m.T = z.T; m.B = z.B; m.act = d->act;
+        m.U = U; m.h0 = h0; m.hist = h_all; m.h_last = h_last;
+        m.counters = at<int32_t>(ws, pl.flags); m.status = at<int32_t>(ws, pl.scratch) + 1;
+        return launch_rec_xcd(m, false, s);
+    }
     if (v.stepwise) return run_rec_fwd_stepwise(a, s);
     return launch_rec_fwd_reference(a, s);
 }
@@ -345,6 +355,13 @@ hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT
         m.Wh = Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
         m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
         return launch_rec_batch_mfma(m, true, s);
+    }
+    if (v.stepwise && rec_xcd_supported(z.H, z.B) && rec_xcd_ready(z.H, d->act, true)) {
+        RecXcdArgs m{};
+        m.Wh = Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
+        m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
+        m.counters = at<int32_t>(ws, pl.flags); m.status = at<int32_t>(ws, pl.scratch) + 1;
+        return launch_rec_xcd(m, true, s);
     }
     // the remaining families read the matrix transposed: one copy per call
     const float* WhT = WhT_or_null;
@@ -763,7 +780,7 @@ const char* rnn_recurrence_variant(const rnn_dims* dims) {
     if (!dims_valid(dims)) return "invalid";
     const Variant v = pick_variant(dims);
     if (v.batch_mfma) return "batch_mfma";
-    if (v.stepwise) return "step_mfma";
+    if (v.stepwise) return rec_xcd_supported(dims->hidden, dims->batch) ? "xcd_mfma" : "step_mfma";
     if (!v.resident) return "reference";
     return (v.fwd.P == 1 && !v.grid) ? "wg_resident" : "grid_resident";
 }
@@ -773,6 +790,7 @@ int rnn_recurrence_workgroups(const rnn_dims* dims) {
     const Variant v = pick_variant(dims);
     const Sizes s = sizes_of(dims);
     if (v.batch_mfma) return (s.B + 3) / 4;
+    if (v.stepwise && rec_xcd_supported(s.H, s.B)) return ((s.B + 7) / 8) * ((s.H + 31) / 32);
     if (v.stepwise) return ((s.H + 15) / 16) * ((s.B + 15) / 16);   // tiles of one step launch
     if (!v.resident) return s.B;
     if (v.grid) return v.gplan.P * s.B;

@@ -151,6 +151,27 @@ hipError_t launch_gather_input(const int32_t* x, const float* Wx, const float* b
                                int H, hipStream_t s);
 hipError_t launch_rec_batch_mfma(const RecMfmaArgs& a, bool bwd, hipStream_t s);
 
+// Persistent batched loop for 256 < H <= 1024 (recurrence_xcd.hip): one batch group per XCD, the state
+// handed over through that XCD's L2.  Needs the full history (no ring) and the input term U.
+struct RecXcdArgs {
+    const float* Wh;
+    int H, T, B, act;
+    // forward
+    const float* U;       // [T,B,H] input term including the bias
+    const float* h0;      // nullable
+    float* hist;          // [T+1,B,H]
+    float* h_last;        // nullable
+    // reverse
+    const float* G; const float* h_all; const float* dh_last; float* Delta; float* dh0;
+    int32_t* counters;    // 8 words of workspace (cleared by the launcher)
+    int32_t* status;      // device status word: set to 1 when a bounded wait expires
+    int spin_limit;       // <= 0: default
+    int first_look_pause; // pauses of 64 clocks between the own tile's store and the first look (<= 0: default)
+};
+bool rec_xcd_supported(int H, int B);                       // shape only (host)
+bool rec_xcd_ready(int H, int act, bool bwd);               // and the current device can hold the grid at once
+hipError_t launch_rec_xcd(const RecXcdArgs& a, bool bwd, hipStream_t s);
+
 hipError_t launch_zero_words(int32_t* p, int n, hipStream_t s);
 // polls a bounded wait between workgroups makes before it gives up (host state, rnn_set_wait_limit)
 int wait_limit();

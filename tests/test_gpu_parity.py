@@ -33,6 +33,10 @@ SMALL_CASES = {
     "lm_batch5_stepwise": (200, 70, 200, 6, 5, dict(LM, wdist=("normal", 0.3), bias_std=0.2, with_h0=True, with_dh_last=True)),
     "dense_batched_stepwise": (48, 160, 40, 12, 40, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True)),
     "lm_batched_wide_stepwise": (300, 320, 300, 5, 24, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
+    # the per-XCD persistent loop: ragged batch groups and column slices, both K widths, one step, dense/tanh
+    "lm_xcd_ragged_groups": (260, 600, 260, 7, 13, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
+    "dense_xcd_tanh": (48, 388, 40, 4, 61, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
+    "lm_xcd_one_step": (120, 1024, 120, 1, 9, dict(LM, wdist=("normal_fan", None), with_h0=True)),
     "lm_batched_ragged_mfma": (150, 100, 150, 7, 21, dict(LM, wdist=("normal", 0.2), bias_std=0.2, with_h0=True, with_dh_last=True)),
     "lm_long_id_list_chunked_scatter": (500, 64, 500, 128, 20, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
@@ -134,7 +138,7 @@ def test_results_are_bit_identical_run_to_run():
         assert first["loss"] == again["loss"]
 
 
-@pytest.mark.parametrize("name", ["lm_hidden_500", "lm_hidden_300_two_groups", "lm_batched_wide_stepwise",
+@pytest.mark.parametrize("name", ["lm_hidden_500", "lm_hidden_300_two_groups", "lm_batched_wide_stepwise", "lm_xcd_ragged_groups",
                                   "lm_batched_mfma_shape"])
 def test_multi_workgroup_loops_repeat_exactly_100_times(name):
     """A broken exchange or barrier between the workgroups of a time loop shows up as run-to-run
