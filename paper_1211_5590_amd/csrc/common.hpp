@@ -26,6 +26,15 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Four consecutive 16-byte aligned LDS words, read with an LDS instruction and waited for through the
+// LDS counter alone.  A volatile read through an ordinary pointer becomes a flat load, whose wait is
+// vmcnt(0): a spin on an LDS flag would then also wait for every global store and prefetch in flight.
+__device__ __forceinline__ int4 lds_peek4(const int* p) {
+    int4 v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"((unsigned)(size_t)p) : "memory");
+    return v;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));

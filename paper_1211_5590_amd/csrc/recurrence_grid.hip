@@ -313,10 +313,9 @@ __global__ __launch_bounds__(kThreads) void rec_grid_kernel(RecResArgs a) {
             // their stores, which they signal through LDS (a pause between looks: a tight spin of four
             // wavefronts would crowd the compute wavefronts' own LDS traffic).
             {
-                const volatile int* flag = s_stored;
-                for (int spins = 0; spins < (1 << 16); ++spins) {
-                    const int f0 = flag[0], f1 = flag[1], f2 = flag[2], f3 = flag[3];
-                    if (f0 == (int)tag && f1 == (int)tag && f2 == (int)tag && f3 == (int)tag) break;
+                                for (int spins = 0; spins < (1 << 16); ++spins) {
+                    const int4 f = lds_peek4(s_stored);
+                    if (f.x == (int)tag && f.y == (int)tag && f.z == (int)tag && f.w == (int)tag) break;
                     __builtin_amdgcn_s_sleep(1);
                 }
                 for (int k = 0; k < a.poll_sleep; ++k) __builtin_amdgcn_s_sleep(1);

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(XT) void rec_xcd_kernel(RecXcdArgs a) {
     constexpr int LDH = KP + 16;           // LDS row stride: the 4 rows of a read land 16 banks apart
     extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ int s_abort, s_grp, s_slot;
-    __shared__ int s_stored[4];
+    __shared__ __attribute__((aligned(16))) int s_stored[4];
     float* hs = smem;                      // [RB][LDH] state, zero padded; columns KW w .. belong to wavefront w alone
     float* part = smem + RB * LDH;         // [2][8 wavefronts][RB][CWD] partial tiles, by step parity
 
@@ -323,10 +323,9 @@ __global__ __launch_bounds__(XT) void rec_xcd_kernel(RecXcdArgs a) {
         if (fetch_next) {
             // The other workgroups are in step with this one: look for their tiles a short pause after
             // this workgroup's own tile has been stored.
-            const volatile int* flag = s_stored;
-            for (int spins = 0; spins < (1 << 16); ++spins) {
-                const int f0 = flag[0], f1 = flag[1], f2 = flag[2], f3 = flag[3];
-                if (f0 == s + 1 && f1 == s + 1 && f2 == s + 1 && f3 == s + 1) break;
+                        for (int spins = 0; spins < (1 << 16); ++spins) {
+                const int4 f = lds_peek4(s_stored);
+                if (f.x == s + 1 && f.y == s + 1 && f.z == s + 1 && f.w == s + 1) break;
                 __builtin_amdgcn_s_sleep(1);
             }
             for (int k = 0; k < a.first_look_pause; ++k) __builtin_amdgcn_s_sleep(1);
