@@ -640,11 +640,7 @@ bool rec_resident_plan(int H, int B, int T, bool bwd, bool fuse_post, int strips
             found = true;
             // A single workgroup pays no exchange; once the state is exchanged anyway, more
             // workgroups are cheap, so keep splitting until the slice fits in registers.
-#ifdef RNN_FORCE_P
-            if (P == 1 || (pl.nq4 <= 8 && P >= RNN_FORCE_P)) return true;
-#else
             if (P == 1 || pl.nq4 <= 8) return true;
-#endif
             continue;
         }
         if (fuse_post) return false;  // the fused tail needs the single-workgroup form
