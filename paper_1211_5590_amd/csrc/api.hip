@@ -790,7 +790,7 @@ int rnn_recurrence_workgroups(const rnn_dims* dims) {
     const Variant v = pick_variant(dims);
     const Sizes s = sizes_of(dims);
     if (v.batch_mfma) return (s.B + 3) / 4;
-    if (v.stepwise && rec_xcd_supported(s.H, s.B)) return ((s.B + 7) / 8) * ((s.H + 31) / 32);
+    if (v.stepwise && rec_xcd_supported(s.H, s.B)) return ((s.B + 3) / 4) * ((s.H + 63) / 64);
     if (v.stepwise) return ((s.H + 15) / 16) * ((s.B + 15) / 16);   // tiles of one step launch
     if (!v.resident) return s.B;
     if (v.grid) return v.gplan.P * s.B;
