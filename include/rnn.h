@@ -191,15 +191,20 @@ int rnn_workspace_status(const rnn_dims *dims, const void *workspace, size_t wor
  *               from later windows, none is sent to earlier ones)
  *     h <- h_{T-1} of this window (computed with the parameters before the update)
  *
- *   dims     token input, softmax-CE, batch 1, in_dim == out_dim, hidden <= 128, seq_len <= 32,
- *            out_dim <= 32640 (else RNN_EUNSUPPORTED); flags: RNN_FLAG_SYNC only
+ *   dims     token input, softmax-CE, in_dim == out_dim (else RNN_EUNSUPPORTED); flags:
+ *            RNN_FLAG_SYNC only.  ONE persistent launch for batch 1, hidden <= 128, seq_len <= 32,
+ *            out_dim <= 32640 (the paper's benchmark shape).  Every other size is served by the
+ *            same call as, per window, the launches of rnn_forward, rnn_loss and rnn_bptt plus one
+ *            update launch, all enqueued by this call (same results; ids is then int32
+ *            [n_windows*T + 1, B], h0 and h_last [B,H], and the parameters are up to date after
+ *            every window)
  *   params   device pointers, 16-byte aligned, UPDATED IN PLACE; while the call runs the
  *            buffers are in an intermediate state (the model lives in on-chip memory and is
  *            written back when the last window is done)
  *   ids      device int32[n_windows*T + 1], values in [0, in_dim) (not checked)
  *   h0       [H] initial state, NULL = zeros;  h_last [H] final state, NULL = not wanted
  *   losses   device float32[n_windows], NULL = not wanted
- *   workspace  rnn_train_stream_workspace_bytes() bytes, 16-byte aligned; needs no set-up (the
+ *   workspace  rnn_train_stream_workspace_bytes() bytes, 256-byte aligned; needs no set-up (the
  *            call clears what it uses) and may be shared with the other calls of this library
  *            on the same stream
  * Asynchronous like the other calls.  The launch is cooperative (1 + ceil(out_dim/128)
@@ -218,20 +223,22 @@ int rnn_train_stream_status(const void *workspace, void *hip_stream, int32_t *st
 /*
  * One truncated-BPTT window in ONE launch: what rnn_forward -> rnn_loss -> rnn_bptt compute
  * together (same equations, same outputs), for callers that step through a stream window by
- * window and would otherwise pay three launches per window.  Serves the paper's benchmark shape
- * (its recurrent-network benchmark section: batch 1, vocabulary-sized output layer, short
- * windows): token input, softmax-CE, batch 1, hidden <= 128, seq_len <= 32, out_dim <= 32640;
- * anything else returns RNN_EUNSUPPORTED and the three calls above serve it.
- *   x, targets  device int32[T] (4-byte aligned; a window may start anywhere in a stream)
- *   h0, dh_last [H], NULL = zeros;  h_all [T+1][H], h_last [H], dh0 [H]: NULL = not wanted
+ * window and would otherwise pay three launches per window.  The one-launch kernel serves the
+ * paper's benchmark shape (its recurrent-network benchmark section: batch 1, vocabulary-sized
+ * output layer, short windows): token input, softmax-CE, batch 1, hidden <= 128, seq_len <= 32,
+ * out_dim <= 32640.  Every other token / softmax-CE size is served by the same call as the
+ * launches of the three calls above on a workspace of its own layout (same results, any batch);
+ * dense input or the MSE loss return RNN_EUNSUPPORTED.
+ *   x, targets  device int32[T,B] (4-byte aligned; a window may start anywhere in a stream)
+ *   h0, dh_last [B,H], NULL = zeros;  h_all [T+1,B,H], h_last [B,H], dh0 [B,H]: NULL = not wanted
  *   loss        device float32[1];  grads as in rnn_bptt (RNN_FLAG_ACCUMULATE adds)
- *   workspace   rnn_window_workspace_bytes() bytes, 16-byte aligned, cleared ONCE with
+ *   workspace   rnn_window_workspace_bytes() bytes, 256-byte aligned, cleared ONCE with
  *               rnn_window_workspace_init before its first use (the workgroups of the launch
  *               exchange words that carry a per-launch tag; cleared memory is "not written yet";
  *               the tag is a word of the workspace that the kernel advances, so a captured call
  *               may be replayed, and a workspace rnn_train_stream has used needs no new set-up)
- * Launch form and its precondition: 1 + ceil(out_dim/128) workgroups that wait for each other
- * with bounded spins.  By default this is a PLAIN launch (a cooperative one costs about 18 us more,
+ * Launch form of the one-launch kernel and its precondition: 1 + ceil(out_dim/128) workgroups that
+ * wait for each other with bounded spins.  By default this is a PLAIN launch (a cooperative one costs about 18 us more,
  * the time of a whole window at the benchmark shape), used only when the whole grid fits the chip
  * by itself (checked on the host; otherwise the launch is cooperative): it is correct as long as
  * no other kernel occupies the GPU's compute units while the call runs -- other streams of the

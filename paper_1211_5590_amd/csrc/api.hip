@@ -671,6 +671,16 @@ namespace rnn {
 int wait_limit() { return g_wait_limit.load(std::memory_order_relaxed); }
 }  // namespace rnn
 
+namespace rnn {
+// device address of the status word inside a three-call workspace (checked by the caller)
+int32_t* three_call_status_word(const rnn_dims* dims, void* workspace) {
+    Plan pl;
+    size_t bytes = 0;
+    if (rnn_workspace_bytes(dims, &bytes) != RNN_OK || check_ws(dims, workspace, bytes, &pl) != RNN_OK) return nullptr;
+    return at<int32_t>(workspace, pl.scratch) + 1;
+}
+}  // namespace rnn
+
 extern "C" {
 
 int rnn_set_wait_limit(int polls) {

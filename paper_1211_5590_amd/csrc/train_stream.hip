@@ -47,6 +47,7 @@ constexpr size_t kStaticScratchBytes = RNN_WINDOW_STATIC_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace rnn {
+int32_t* three_call_status_word(const rnn_dims* dims, void* workspace);   // api.hip
 namespace {
 
 constexpr int NT = 512;          // threads per workgroup (both roles)
@@ -1386,6 +1387,86 @@ int launch_window(const rnn_dims* dims, const rnn_params* params, const int32_t*
     return RNN_OK;
 }
 
+
+// ---- the general forms: shapes outside the one-launch kernels --------------------------------------
+// rnn_window and rnn_train_stream accept every token / softmax-CE shape.  Where the one-launch
+// kernels do not reach (hidden > 128, seq_len > 32, batch > 1, very wide vocabularies) the same
+// calls enqueue the launches of rnn_forward -> rnn_loss -> rnn_bptt (and, for the stream, one update
+// launch per window) on the caller's stream: same results, same arguments, no host work per step.
+// Workspace: a 256-byte header (status word first, as in the one-launch form), then what the
+// general form keeps itself, then the three calls' own workspace.
+constexpr size_t kHeaderBytes = 256;
+
+struct GeneralPlan {
+    rnn_dims d3;                       // the dims the three calls see
+    size_t hall, state, grads[5], ws3, ws3_bytes, total;
+    size_t n_param[5];
+};
+
+size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// valid for the general form?  (token ids in, softmax cross-entropy out)
+int general_supported(const rnn_dims* d, unsigned allowed_flags) {
+    if (!d) return RNN_EINVAL;
+    if (d->in_dim <= 0 || d->hidden <= 0 || d->out_dim <= 0 || d->seq_len <= 0 || d->batch <= 0) return RNN_EINVAL;
+    if (d->act != RNN_ACT_SIGMOID && d->act != RNN_ACT_TANH) return RNN_EINVAL;
+    if (d->flags & ~allowed_flags) return RNN_EINVAL;
+    if (d->input_kind != RNN_INPUT_TOKENS || d->loss_kind != RNN_LOSS_SOFTMAX_CE) return RNN_EUNSUPPORTED;
+    return RNN_OK;
+}
+
+int general_plan(const rnn_dims* d, bool stream, GeneralPlan* out) {
+    GeneralPlan g{};
+    g.d3 = *d;
+    g.d3.flags = d->flags & (RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE);
+    if (stream) g.d3.flags = 0;
+    if (rnn_workspace_bytes(&g.d3, &g.ws3_bytes) != RNN_OK) return RNN_EUNSUPPORTED;
+    const size_t H = d->hidden, B = d->batch, T = d->seq_len;
+    size_t off = kHeaderBytes;
+    g.hall = off; off += round256((T + 1) * B * H * 4);
+    g.state = off; off += round256(2 * B * H * 4);              // stream: the carried state, two slots
+    g.n_param[0] = (size_t)d->in_dim * H; g.n_param[1] = H * H; g.n_param[2] = H;
+    g.n_param[3] = H * (size_t)d->out_dim; g.n_param[4] = (size_t)d->out_dim;
+    for (int i = 0; i < 5; ++i) {
+        g.grads[i] = off;
+        if (stream) off += round256(g.n_param[i] * 4);
+    }
+    g.ws3 = off; off += round256(g.ws3_bytes);
+    g.total = off;
+    *out = g;
+    return RNN_OK;
+}
+
+// status word of the header |= status word of the three calls' workspace
+__global__ void merge_status_kernel(int32_t* __restrict__ header, const int32_t* __restrict__ inner) {
+    if (threadIdx.x == 0 && blockIdx.x == 0 && *inner != 0) *header = 1;
+}
+
+// params <- params - lr * grads for the five tensors, one launch
+struct SgdArgs { float* p[5]; const float* g[5]; size_t n[5]; float lr; };
+__global__ __launch_bounds__(256) void sgd_update_kernel(SgdArgs a) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+#pragma unroll
+    for (int t = 0; t < 5; ++t)
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.n[t]; i += stride)
+            a.p[t][i] -= a.lr * a.g[t][i];
+}
+
+int general_window(const rnn_dims* dims, const rnn_params* params, const int32_t* x, const int32_t* targets,
+                   const float* h0, const float* dh_last, float* h_all, float* h_last, float* loss,
+                   const rnn_grads* grads, float* dh0, void* workspace, const GeneralPlan& g, hipStream_t s) {
+    char* ws = static_cast<char*>(workspace);
+    float* hall = h_all ? h_all : reinterpret_cast<float*>(ws + g.hall);
+    void* ws3 = ws + g.ws3;
+    int rc = rnn_forward(&g.d3, params, x, h0, hall, h_last, ws3, g.ws3_bytes, s);
+    if (rc == RNN_OK) rc = rnn_loss(&g.d3, params, hall, targets, loss, ws3, g.ws3_bytes, s);
+    if (rc == RNN_OK) rc = rnn_bptt(&g.d3, params, x, targets, hall, dh_last, grads, dh0, ws3, g.ws3_bytes, s);
+    if (rc != RNN_OK) return rc;
+    hipLaunchKernelGGL(merge_status_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(ws),
+                       three_call_status_word(&g.d3, ws3));
+    return hipGetLastError() == hipSuccess ? RNN_OK : RNN_EHIP;
+}
+
 // Address of this device's copy of the fixed scratch array of rnn_window_static.  In host code the
 // array's name is only a handle: the address kernels can use comes from hipGetSymbolAddress, once
 // per device (every GPU holds its own copy).  The first call on a device also clears the array, on
@@ -1417,6 +1498,14 @@ int rnn_window_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
     using namespace rnn;
     if (!bytes) return RNN_EINVAL;
     const int rc = window_supported(dims);
+    if (rc == RNN_EUNSUPPORTED) {
+        GeneralPlan g;
+        int rg = general_supported(dims, RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE | RNN_FLAG_COOPERATIVE);
+        if (rg == RNN_OK) rg = general_plan(dims, false, &g);
+        if (rg != RNN_OK) return rg;
+        *bytes = g.total;
+        return RNN_OK;
+    }
     if (rc != RNN_OK) return rc;
     *bytes = stream_plan(dims).total;
     return RNN_OK;
@@ -1425,6 +1514,17 @@ int rnn_window_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
 int rnn_window_workspace_init(const rnn_dims* dims, void* workspace, size_t workspace_bytes, void* hip_stream) {
     using namespace rnn;
     const int rc = window_supported(dims);
+    if (rc == RNN_EUNSUPPORTED) {
+        GeneralPlan g;
+        int rg = general_supported(dims, RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE | RNN_FLAG_COOPERATIVE);
+        if (rg == RNN_OK) rg = general_plan(dims, false, &g);
+        if (rg != RNN_OK) return rg;
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total)
+            return RNN_EWORKSPACE;
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
+        if (launch_zero_words(static_cast<int32_t*>(workspace), (int)(kHeaderBytes / 4), s) != hipSuccess) return RNN_EHIP;
+        return rnn_workspace_init(&g.d3, static_cast<char*>(workspace) + g.ws3, g.ws3_bytes, hip_stream);
+    }
     if (rc != RNN_OK) return rc;
     const StreamPlan pl = stream_plan(dims);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
@@ -1439,6 +1539,17 @@ int rnn_window(const rnn_dims* dims, const rnn_params* params, const int32_t* x,
                void* hip_stream) {
     using namespace rnn;
     const int rc = window_args_ok(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0);
+    if (rc == RNN_EUNSUPPORTED) {      // outside the one-launch kernel: the launches of the three calls
+        GeneralPlan g;
+        int rg = general_supported(dims, RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE | RNN_FLAG_COOPERATIVE);
+        if (rg == RNN_OK) rg = general_plan(dims, false, &g);
+        if (rg != RNN_OK) return rg;
+        if (!params || !x || !targets || !loss || !grads) return RNN_EINVAL;
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total)
+            return RNN_EWORKSPACE;
+        return general_window(dims, params, x, targets, h0, dh_last, h_all, h_last, loss, grads, dh0, workspace, g,
+                              static_cast<hipStream_t>(hip_stream));
+    }
     if (rc != RNN_OK) return rc;
     const StreamPlan pl = stream_plan(dims);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || workspace_bytes < pl.total)
@@ -1467,6 +1578,15 @@ int rnn_train_stream_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
     using namespace rnn;
     if (!bytes) return RNN_EINVAL;
     const int rc = stream_supported(dims);
+    if (rc == RNN_EUNSUPPORTED) {
+        GeneralPlan g;
+        int rg = general_supported(dims, RNN_FLAG_SYNC);
+        if (rg == RNN_OK && dims->in_dim != dims->out_dim) rg = RNN_EUNSUPPORTED;   // targets are the next ids
+        if (rg == RNN_OK) rg = general_plan(dims, true, &g);
+        if (rg != RNN_OK) return rg;
+        *bytes = g.total;
+        return RNN_OK;
+    }
     if (rc != RNN_OK) return rc;
     *bytes = stream_plan(dims).total;
     return RNN_OK;
@@ -1477,6 +1597,64 @@ int rnn_train_stream(const rnn_dims* dims, const rnn_params_inout* params, const
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
     using namespace rnn;
     const int rc = stream_supported(dims);
+    if (rc == RNN_EUNSUPPORTED) {
+        // Outside the one-launch kernel: per window the launches of the three calls and one update
+        // launch, all enqueued here; the state is carried through two slots of the workspace.
+        GeneralPlan g;
+        int rg = general_supported(dims, RNN_FLAG_SYNC);
+        if (rg == RNN_OK && dims->in_dim != dims->out_dim) rg = RNN_EUNSUPPORTED;   // targets are the next ids
+        if (rg == RNN_OK) rg = general_plan(dims, true, &g);
+        if (rg != RNN_OK) return rg;
+        if (!params || !params->Wx || !params->Wh || !params->b || !params->V || !params->c || !ids) return RNN_EINVAL;
+        if (n_windows < 0 || n_windows > (int64_t)0x7fffffff || !(lr == lr)) return RNN_EINVAL;
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < g.total)
+            return RNN_EWORKSPACE;
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
+        char* ws = static_cast<char*>(workspace);
+        if (launch_zero_words(reinterpret_cast<int32_t*>(ws), (int)(kHeaderBytes / 4), s) != hipSuccess) return RNN_EHIP;
+        int rw = rnn_workspace_init(&g.d3, ws + g.ws3, g.ws3_bytes, hip_stream);
+        if (rw != RNN_OK) return rw;
+        const size_t bh = (size_t)dims->batch * dims->hidden, tb = (size_t)dims->seq_len * dims->batch;
+        float* slot[2] = {reinterpret_cast<float*>(ws + g.state), reinterpret_cast<float*>(ws + g.state) + bh};
+        float* hall = reinterpret_cast<float*>(ws + g.hall);
+        rnn_params rp{params->Wx, params->Wh, params->b, params->V, params->c};
+        rnn_grads gr{reinterpret_cast<float*>(ws + g.grads[0]), reinterpret_cast<float*>(ws + g.grads[1]),
+                     reinterpret_cast<float*>(ws + g.grads[2]), reinterpret_cast<float*>(ws + g.grads[3]),
+                     reinterpret_cast<float*>(ws + g.grads[4])};
+        SgdArgs up{};
+        up.p[0] = params->Wx; up.p[1] = params->Wh; up.p[2] = params->b; up.p[3] = params->V; up.p[4] = params->c;
+        up.g[0] = gr.dWx; up.g[1] = gr.dWh; up.g[2] = gr.db; up.g[3] = gr.dV; up.g[4] = gr.dc;
+        size_t most = 0;
+        for (int i = 0; i < 5; ++i) { up.n[i] = g.n_param[i]; if (up.n[i] > most) most = up.n[i]; }
+        up.lr = lr;
+        const unsigned blocks = (unsigned)((most + 255) / 256 < 2048 ? (most + 255) / 256 : 2048);
+        // losses == NULL: the per-window loss still has to land somewhere
+        float* loss_sink = reinterpret_cast<float*>(ws) + 8;
+        const float* h_prev = h0;
+        for (int64_t w = 0; w < n_windows; ++w) {
+            const int32_t* xw = ids + (size_t)w * tb;
+            float* h_next = (w == n_windows - 1 && h_last) ? h_last : slot[w & 1];
+            rw = rnn_forward(&g.d3, &rp, xw, h_prev, hall, h_next, ws + g.ws3, g.ws3_bytes, s);
+            if (rw == RNN_OK) rw = rnn_loss(&g.d3, &rp, hall, xw + dims->batch, losses ? losses + w : loss_sink,
+                                            ws + g.ws3, g.ws3_bytes, s);
+            if (rw == RNN_OK) rw = rnn_bptt(&g.d3, &rp, xw, xw + dims->batch, hall, nullptr, &gr, nullptr,
+                                            ws + g.ws3, g.ws3_bytes, s);
+            if (rw != RNN_OK) return rw;
+            hipLaunchKernelGGL(sgd_update_kernel, dim3(blocks), dim3(256), 0, s, up);
+            if (hipGetLastError() != hipSuccess) return RNN_EHIP;
+            h_prev = h_next;
+        }
+        if (n_windows > 0) {
+            hipLaunchKernelGGL(merge_status_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(ws),
+                               three_call_status_word(&g.d3, ws + g.ws3));
+            if (hipGetLastError() != hipSuccess) return RNN_EHIP;
+        } else if (h_last && h0) {
+            if (hipMemcpyAsync(h_last, h0, bh * 4, hipMemcpyDeviceToDevice, s) != hipSuccess) return RNN_EHIP;
+        }
+        if (dims->flags & RNN_FLAG_SYNC)
+            if (hipStreamSynchronize(s) != hipSuccess) return RNN_EHIP;
+        return RNN_OK;
+    }
     if (rc != RNN_OK) return rc;
     if (!params || !params->Wx || !params->Wh || !params->b || !params->V || !params->c || !ids)
         return RNN_EINVAL;

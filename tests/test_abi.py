@@ -85,11 +85,13 @@ def test_strerror_and_variant_names():
 
 def test_train_stream_rejects_what_it_cannot_run_without_a_gpu():
     ok = good_dims(seq_len=10, hidden=100, in_dim=10000, out_dim=10000)
-    assert rnn.rnn_train_stream_workspace_bytes(ok) > 0
-    for bad, code in ((dict(batch=2), -3), (dict(hidden=129), -3), (dict(seq_len=33), -3),
-                      (dict(out_dim=128), -3), (dict(input_kind=1), -3), (dict(loss_kind=1), -3),
-                      (dict(in_dim=40000, out_dim=40000), -3), (dict(hidden=0), -1), (dict(act=7), -1),
-                      (dict(flags=1), -1)):
+    need_of_ok = rnn.rnn_train_stream_workspace_bytes(ok)
+    assert need_of_ok > 0
+    # shapes beyond the one-launch kernel are served by the launches of the three calls
+    for wider in (dict(batch=2), dict(hidden=129), dict(seq_len=33), dict(in_dim=40000, out_dim=40000)):
+        assert rnn.rnn_train_stream_workspace_bytes(good_dims(**wider)) > 0, wider
+    for bad, code in ((dict(out_dim=128), -3), (dict(input_kind=1), -3), (dict(loss_kind=1), -3),
+                      (dict(hidden=0), -1), (dict(act=7), -1), (dict(flags=1), -1)):
         with pytest.raises(rnn.RnnError) as e:
             rnn.rnn_train_stream_workspace_bytes(good_dims(**bad))
         assert e.value.code == code, bad
