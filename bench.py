@@ -645,8 +645,9 @@ def summary_row(r):
             None if rf.get("frac") is None else round(rf["frac"], 4)]
 
 
-DEFAULT_STEPS = {"C1": 200, "C2": 3, "C3": 50, "C4": 10, "C5": 5}
-DEFAULT_WARM = {"C1": 20, "C2": 1, "C3": 5, "C4": 2, "C5": 1}
+# at least 20 timed steps after at least 3 warm-ups, except the 10000-window stream (0.24 s per pass)
+DEFAULT_STEPS = {"C1": 200, "C2": 3, "C3": 50, "C4": 20, "C5": 20}
+DEFAULT_WARM = {"C1": 20, "C2": 1, "C3": 5, "C4": 3, "C5": 3}
 
 
 def main():
