@@ -188,3 +188,34 @@ def test_window_beside_a_long_kernel_on_another_stream():
     got = b.results()
     assert rnn.rnn_train_stream_status(b.ws) == 0
     compare(got, ref)
+
+
+@pytest.mark.parametrize("shape", ["wide_batched_loop", "batch_1_loop_of_several_workgroups"])
+def test_smallest_wait_limit_on_the_multi_workgroup_loops_never_hangs(shape):
+    """The time loops whose workgroups hand the state to each other wait with a bound.  With the
+    bound set to a single poll from the host a wait may expire (status 1, results invalid) or not
+    (status 0, results as the oracle's); either way every kernel ends, and after a new set-up of
+    the workspace with the normal bound the next call is good."""
+    from gpu_harness import Runner
+    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=7, batch=13) if shape == "wide_batched_loop"
+            else dict(in_dim=200, hidden=300, out_dim=200, seq_len=9, batch=1))
+    case = ri.make_case(wdist=("normal", 0.2), bias_std=0.1, seed=31, **spec)
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case)
+    print("variant", rnn.rnn_recurrence_variant(r.dims), flush=True)
+    rnn.rnn_set_wait_limit(1)
+    try:
+        for rep in range(3):
+            rnn.rnn_workspace_init(r.dims, r.ws)
+            r.step()
+            status = rnn.rnn_workspace_status(r.dims, r.ws)
+            print(f"rep {rep}: status {status}", flush=True)
+            assert status in (0, 1)
+            if status == 0:
+                compare(r.results(), ref)
+    finally:
+        rnn.rnn_set_wait_limit(0)
+    rnn.rnn_workspace_init(r.dims, r.ws)
+    r.step()
+    assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
+    compare(r.results(), ref)
