@@ -78,7 +78,7 @@ def test_strerror_and_variant_names():
     assert rnn.rnn_strerror(0) == "ok"
     for code in (-1, -2, -3, -4, -99):
         assert len(rnn.rnn_strerror(code)) > 0
-    assert rnn.rnn_recurrence_variant(good_dims()) in ("wg_resident", "grid_resident", "batch_mfma", "step_mfma", "reference")
+    assert rnn.rnn_recurrence_variant(good_dims()) in ("wg_resident", "grid_resident", "batch_mfma", "xcd_mfma", "step_mfma", "reference")
     assert rnn.rnn_recurrence_workgroups(good_dims()) >= 1
     assert rnn.rnn_recurrence_workgroups(good_dims(hidden=256, batch=128)) == 32   # 4 rows each
 
