@@ -88,9 +88,10 @@ class Workload:
         self.loss = torch.zeros((max(self.windows, 1),), device="cuda")
         self.ws = torch.empty(rnn.rnn_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
         rnn.rnn_workspace_init(self.dims, self.ws)
-        # one launch per window (rnn_window) where the library serves the shape, else the three calls
+        # one launch per window (rnn_window) where its one-launch kernel serves the shape, else the three calls
         self.fused = False
-        if not three_calls and not flags:
+        if (not three_calls and not flags and case["input_kind"] == 0 and case["loss_kind"] == 0
+                and rnn.rnn_window_one_launch(self.dims)):
             try:
                 self.wws = torch.empty(rnn.rnn_window_workspace_bytes(self.dims), dtype=torch.uint8, device="cuda")
                 rnn.rnn_window_workspace_init(self.dims, self.wws)

@@ -248,6 +248,9 @@ int rnn_train_stream_status(const void *workspace, void *hip_stream, int32_t *st
  * callers that share the GPU must read rnn_train_stream_status (which reads the status word of
  * this workspace as well) before they trust a window's results.
  */
+/* 1: rnn_window serves these sizes with its one-launch kernel; 0: with the launches of the three
+ * calls; negative: an error code (sizes it does not serve at all).  Host-only. */
+int rnn_window_one_launch(const rnn_dims *dims);
 int rnn_window_workspace_bytes(const rnn_dims *dims, size_t *bytes);
 int rnn_window_workspace_init(const rnn_dims *dims, void *workspace, size_t workspace_bytes,
                               void *hip_stream);

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     rnn_profile_begin, rnn_profile_end, rnn_recurrence_variant, rnn_recurrence_workgroups, rnn_strerror,
     rnn_workspace_bytes, rnn_workspace_init, rnn_workspace_status, rnn_set_wait_limit,
     rnn_train_stream, rnn_train_stream_status, rnn_train_stream_workspace_bytes,
-    rnn_window, rnn_window_workspace_bytes, rnn_window_workspace_init, rnn_window_static, WINDOW_STATIC_BYTES,
+    rnn_window, rnn_window_one_launch, rnn_window_workspace_bytes, rnn_window_workspace_init, rnn_window_static, WINDOW_STATIC_BYTES,
     GN_METRIC_IDENTITY, GN_METRIC_LOSS, rnn_gauss_newton_vec, rnn_gauss_newton_workspace_bytes,
     MlpDims, MlpParams, mlp_params, rnn_mlp_train, rnn_mlp_workspace_bytes,
 )

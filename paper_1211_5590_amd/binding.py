@@ -23,7 +23,7 @@ EXPORTS = ("rnn_workspace_bytes", "rnn_forward", "rnn_loss", "rnn_bptt", "rnn_ch
            "rnn_strerror", "rnn_recurrence_variant", "rnn_recurrence_workgroups", "rnn_profile_begin", "rnn_profile_end",
            "rnn_profile_kernel_count", "rnn_profile_kernel_name", "rnn_workspace_init", "rnn_set_wait_limit",
            "rnn_workspace_status", "rnn_train_stream_workspace_bytes", "rnn_train_stream",
-           "rnn_train_stream_status", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
+           "rnn_train_stream_status", "rnn_window_one_launch", "rnn_window_workspace_bytes", "rnn_window_workspace_init",
            "rnn_window", "rnn_window_static", "rnn_gauss_newton_workspace_bytes", "rnn_gauss_newton_vec",
            "rnn_mlp_workspace_bytes", "rnn_mlp_train", "rnn_measure_ceilings")
 MLP_MAX_LAYERS = 16
@@ -117,6 +117,8 @@ def lib():
         L.rnn_train_stream.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Grads), vp, ctypes.c_int64,
                                        ctypes.c_float, vp, vp, vp, vp, sz, vp]
         L.rnn_train_stream_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        L.rnn_window_one_launch.argtypes = [ctypes.POINTER(Dims)]
+        L.rnn_window_one_launch.restype = ctypes.c_int
         L.rnn_window_workspace_bytes.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
         L.rnn_window_workspace_init.argtypes = [ctypes.POINTER(Dims), vp, sz, vp]
         L.rnn_window.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp,
@@ -350,6 +352,14 @@ def rnn_train_stream_status(workspace, stream=None) -> int:
     out = ctypes.c_int32(-1)
     _check(lib().rnn_train_stream_status(_p(workspace), _stream(stream), ctypes.byref(out)))
     return int(out.value)
+
+
+def rnn_window_one_launch(dims: Dims) -> bool:
+    """True: rnn_window runs these sizes as one launch; False: as the launches of the three calls."""
+    rc = lib().rnn_window_one_launch(ctypes.byref(dims))
+    if rc < 0:
+        _check(rc)
+    return rc == 1
 
 
 def rnn_window_workspace_bytes(dims: Dims) -> int:

@@ -1494,6 +1494,15 @@ int static_scratch(hipStream_t s, void** out) {
 
 extern "C" {
 
+int rnn_window_one_launch(const rnn_dims* dims) {
+    using namespace rnn;
+    const int rc = window_supported(dims);
+    if (rc == RNN_OK) return 1;
+    if (rc != RNN_EUNSUPPORTED) return rc;
+    const int rg = general_supported(dims, RNN_FLAG_SYNC | RNN_FLAG_ACCUMULATE | RNN_FLAG_COOPERATIVE);
+    return rg == RNN_OK ? 0 : rg;
+}
+
 int rnn_window_workspace_bytes(const rnn_dims* dims, size_t* bytes) {
     using namespace rnn;
     if (!bytes) return RNN_EINVAL;

@@ -83,6 +83,16 @@ def test_strerror_and_variant_names():
     assert rnn.rnn_recurrence_workgroups(good_dims(hidden=256, batch=128)) == 32   # 4 rows each
 
 
+def test_which_sizes_the_one_window_call_runs_as_one_launch():
+    lm = good_dims(seq_len=10, hidden=100, in_dim=10000, out_dim=10000)
+    assert rnn.rnn_window_one_launch(lm) is True
+    for wider in (dict(batch=2), dict(hidden=129), dict(seq_len=33), dict(in_dim=40000, out_dim=40000)):
+        assert rnn.rnn_window_one_launch(good_dims(**wider)) is False, wider
+    with pytest.raises(rnn.RnnError) as e:
+        rnn.rnn_window_one_launch(good_dims(loss_kind=1))
+    assert e.value.code == -3
+
+
 def test_train_stream_rejects_what_it_cannot_run_without_a_gpu():
     ok = good_dims(seq_len=10, hidden=100, in_dim=10000, out_dim=10000)
     need_of_ok = rnn.rnn_train_stream_workspace_bytes(ok)
