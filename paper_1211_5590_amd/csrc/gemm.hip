@@ -417,10 +417,52 @@ size_t gemm_splitk_floats(int M, int N, int K) {
     return sp.splits > 1 ? (size_t)sp.splits * M * N : 0;
 }
 
+// The same sum for rows of whole float4 groups: one thread per four consecutive outputs, the
+// partials of the K slices added in slice order (eight 16-byte requests in flight per thread), one
+// pass over the partial buffer at the rate memory delivers it.
+__global__ __launch_bounds__(256) void splitk_reduce_rows4_kernel(const float4* __restrict__ part, float* __restrict__ C,
+                                                                  const float* __restrict__ bias, size_t total4,
+                                                                  int N4, int ldc, int splits, int beta) {
+    constexpr int U = 8;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total4; i += (size_t)gridDim.x * blockDim.x) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < splits; s0 += U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = part[(size_t)min(s0 + u, splits - 1) * total4 + i];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (s0 + u < splits) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+        }
+        const size_t m = i / N4;
+        const int n = (int)(i - m * N4) * 4;
+        if (bias) {
+            const float4 b = *reinterpret_cast<const float4*>(bias + n);
+            acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+        }
+        float4* dst = reinterpret_cast<float4*>(C + m * (size_t)ldc + n);
+        if (beta) {
+            const float4 c = *dst;
+            acc.x += c.x; acc.y += c.y; acc.z += c.z; acc.w += c.w;
+        }
+        *dst = acc;
+    }
+}
+
 hipError_t launch_splitk_reduce(const float* part, float* C, const float* bias_n, int M, int N, int ldc,
                                 int splits, int beta, hipStream_t s) {
     const size_t total = (size_t)M * N;
     ProfileScope ps(K_SPLITK_REDUCE, s);
+    // few slices of a large result: stream them; many slices of a small one: the kernel that also
+    // spreads the slices over lanes
+    if (splits <= 32 && total >= ((size_t)1 << 20) && N % 4 == 0 && ldc % 4 == 0 && aligned16(part) && aligned16(C) &&
+        (!bias_n || aligned16(bias_n))) {
+        const size_t total4 = total / 4;
+        const unsigned blocks = (unsigned)((total4 + 255) / 256 < 4096 ? (total4 + 255) / 256 : 4096);
+        hipLaunchKernelGGL(splitk_reduce_rows4_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const float4*>(part),
+                           C, bias_n, total4, N / 4, ldc, splits, beta);
+        return hipGetLastError();
+    }
     if (total % 4 == 0) {  // the partial buffer is 16-byte aligned workspace
         const unsigned blocks = (unsigned)((total / 4 + 15) / 16);
         hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3(blocks), dim3(256), 0, s, part, C, bias_n, M, N, ldc,
