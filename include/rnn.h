@@ -266,7 +266,9 @@ int rnn_window(const rnn_dims *dims, const rnn_params *params, const int32_t *x,
  * array inside the library's code object instead (RNN_WINDOW_STATIC_BYTES = 2 MiB per GPU, held by
  * every GPU the library runs on until the process ends).  The call allocates and frees nothing,
  * here or in any library routine it uses.
- *   dims .. dh0   as in rnn_window.  Sizes whose boxes exceed the array (more than
+ *   dims .. dh0   as in rnn_window, for the sizes its one-launch kernel serves
+ *                 (rnn_window_one_launch() == 1; others return RNN_EUNSUPPORTED: the launches of the
+ *                 three calls need a workspace).  Sizes whose boxes exceed the array (more than
  *                 rnn_window_workspace_bytes() = RNN_WINDOW_STATIC_BYTES) return RNN_ETOOLARGE and
  *                 nothing is enqueued; the paper's benchmark shape (vocabulary 10000, hidden 100,
  *                 windows of 10) needs 0.67 MB.
