@@ -380,14 +380,24 @@ SplitPlan plan_split(int M, int N, int K) {
         // runs about 2.5 times faster (measured: 1024 tiles take 1.4 rounds, not 2).
         const double slots = 768.0, flops = 2.0 * M * N * (double)K, out_bytes = 4.0 * M * (double)N;
         const double t_full = flops / 100e12;                      // at a typical achieved rate
-        double best = 1e30;
+        double best = 1e30, t_of[9];
         for (int sp = 1; sp <= 8; ++sp) {
             const long units = (long)tiles * sp, whole = units / 768, rem = units % 768;
             const double last = rem == 0 ? 0.0 : (sp == 1 && rem <= 256) ? 0.4 : 1.0;
             const double rounds = ((double)whole + last) / sp;      // in units of one full-K round
-            const double t = t_full * rounds * slots / tiles + (sp > 1 ? 2.0 * sp * out_bytes / 3e12 : 0.0);
-            if (t < best * 0.97) { best = t; splits = sp; }         // a cut has to pay for itself
+            // the slices' partial results are written once more than an uncut result and read back
+            // by the reduction, which streams them at about the rate of a copy
+            t_of[sp] = t_full * rounds * slots / tiles + (sp > 1 ? (2.0 * sp + 1.0) * out_bytes / 4.5e12 : 0.0);
+            if (t_of[sp] < best * 0.97) { best = t_of[sp]; splits = sp; }   // a cut has to pay for itself
         }
+        // Among near-equal plans prefer a cut that fills whole rounds exactly.  Measured on the
+        // largest such product (16384 x 1024 x 10000): uncut it has two states, 2.64 and 3.17 ms,
+        // which differ in how often the workgroups of an XCD share their operand panels through its
+        // L2 and which a launch falls into by chance; cut three ways (exactly four rounds) it takes
+        // 2.61 ms + 0.04 ms of reduction in either, also under a probe that forces the slow state.
+        if (splits == 1)
+            for (int sp = 2; sp <= 8; ++sp)
+                if ((long)tiles * sp % 768 == 0 && t_of[sp] <= 1.03 * t_of[1]) { splits = sp; break; }
     }
     int kchunk = (K + splits - 1) / splits;
     kchunk = (kchunk + BK - 1) / BK * BK;
