@@ -219,3 +219,29 @@ def test_smallest_wait_limit_on_the_multi_workgroup_loops_never_hangs(shape):
     r.step()
     assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
     compare(r.results(), ref)
+
+
+@pytest.mark.parametrize("shape", ["wide_batched_loop", "batch_1_loop_of_several_workgroups"])
+def test_replays_of_the_three_captured_calls_with_a_multi_workgroup_loop(shape):
+    """The cooperative launches of the multi-workgroup time loops inside a captured graph: every
+    replay (with the program's own eager work between replays) gives the oracle's results."""
+    from gpu_harness import Runner
+    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=7, batch=13) if shape == "wide_batched_loop"
+            else dict(in_dim=200, hidden=300, out_dim=200, seq_len=9, batch=1))
+    case = ri.make_case(wdist=("normal", 0.2), bias_std=0.1, seed=31, **spec)
+    ref = oracle.fwd_bptt(case)
+    r = Runner(case)
+    r.step()                                      # warm-up outside the capture (one-time attribute calls)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        r.forward(); r.loss_(); r.bptt()
+    for rep in range(3):
+        print(f"replay {rep}", flush=True)
+        for g in r.grads.values():
+            g.fill_(float("nan"))
+        r.h_all.fill_(float("nan"))
+        graph.replay()
+        got = r.results()
+        assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
+        compare(got, ref)
