@@ -234,7 +234,7 @@ hipError_t run_forward(const rnn_dims* d, const rnn_params* P, const void* x, co
         m.U = U; m.h0 = h0; m.hist = a.hist; m.h_last = h_last; m.ring = a.ring;
         return launch_rec_batch_mfma(m, false, s);
     }
-    if (v.stepwise && h_all && rec_xcd_supported(z.H, z.B) && rec_xcd_ready(z.H, d->act, false)) {
+    if (v.stepwise && h_all && rec_xcd_supported(z.H, z.B, z.T) && rec_xcd_ready(z.H, d->act, false)) {
         // one persistent launch for all steps (one batch group per XCD)
         float* U = at<float>(ws, pl.U);
         if (z.tokens) RNN_TRY(launch_gather_input(a.x, P->Wx, P->b, U, (int)z.N, z.H, s));
@@ -356,7 +356,7 @@ hipError_t run_reverse_loop(const rnn_dims* d, const float* Wh, const float* WhT
         m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
         return launch_rec_batch_mfma(m, true, s);
     }
-    if (v.stepwise && rec_xcd_supported(z.H, z.B) && rec_xcd_ready(z.H, d->act, true)) {
+    if (v.stepwise && rec_xcd_supported(z.H, z.B, z.T) && rec_xcd_ready(z.H, d->act, true)) {
         RecXcdArgs m{};
         m.Wh = Wh; m.H = H; m.T = z.T; m.B = z.B; m.act = d->act;
         m.G = G; m.h_all = h_all; m.dh_last = dh_last; m.Delta = Delta; m.dh0 = dh0;
@@ -790,7 +790,7 @@ const char* rnn_recurrence_variant(const rnn_dims* dims) {
     if (!dims_valid(dims)) return "invalid";
     const Variant v = pick_variant(dims);
     if (v.batch_mfma) return "batch_mfma";
-    if (v.stepwise) return rec_xcd_supported(dims->hidden, dims->batch) ? "xcd_mfma" : "step_mfma";
+    if (v.stepwise) return rec_xcd_supported(dims->hidden, dims->batch, dims->seq_len) ? "xcd_mfma" : "step_mfma";
     if (!v.resident) return "reference";
     return (v.fwd.P == 1 && !v.grid) ? "wg_resident" : "grid_resident";
 }
@@ -800,7 +800,7 @@ int rnn_recurrence_workgroups(const rnn_dims* dims) {
     const Variant v = pick_variant(dims);
     const Sizes s = sizes_of(dims);
     if (v.batch_mfma) return (s.B + 3) / 4;
-    if (v.stepwise && rec_xcd_supported(s.H, s.B)) return ((s.B + 3) / 4) * ((s.H + 63) / 64);
+    if (v.stepwise && rec_xcd_supported(s.H, s.B, s.T)) return ((s.B + 3) / 4) * ((s.H + 63) / 64);
     if (v.stepwise) return ((s.H + 15) / 16) * ((s.B + 15) / 16);   // tiles of one step launch
     if (!v.resident) return s.B;
     if (v.grid) return v.gplan.P * s.B;

@@ -168,7 +168,7 @@ struct RecXcdArgs {
     int spin_limit;       // <= 0: default
     int first_look_pause; // pauses of 64 clocks between the own tile's store and the first look (<= 0: default)
 };
-bool rec_xcd_supported(int H, int B);                       // shape only (host)
+bool rec_xcd_supported(int H, int B, int T);                       // shape only (host)
 bool rec_xcd_ready(int H, int act, bool bwd);               // and the current device can hold the grid at once
 hipError_t launch_rec_xcd(const RecXcdArgs& a, bool bwd, hipStream_t s);
 

@@ -339,8 +339,12 @@ size_t xcd_lds_bytes() { return (size_t)2 * 8 * RB * CWD * 4; }
 
 }  // namespace
 
-bool rec_xcd_supported(int H, int B) {
-    return B > 4 && B <= NGRP * RB && H > 256 && H <= NSLOT * CWD && H % 4 == 0;
+// Shapes the one-launch loop serves and is the faster choice for.  The launch has a fixed cost (a
+// cooperative launch, every workgroup loading its 256 KB of the matrix: about 90 us forward, 60 us in
+// reverse) and then takes 2.2 us per step, against 5.5 us per step for a launch per step, so short
+// sequences stay with the latter (measured cross-over at H = 1024, batch 64: 16 to 20 steps).
+bool rec_xcd_supported(int H, int B, int T) {
+    return T >= 20 && B > 4 && B <= NGRP * RB && H > 256 && H <= NSLOT * CWD && H % 4 == 0;
 }
 
 template <bool BWD>
@@ -373,7 +377,7 @@ bool rec_xcd_ready(int H, int act, bool bwd) {
 }
 
 hipError_t launch_rec_xcd(const RecXcdArgs& a, bool bwd, hipStream_t s) {
-    if (!rec_xcd_supported(a.H, a.B) || a.T < 1) return hipErrorInvalidValue;
+    if (!rec_xcd_supported(a.H, a.B, a.T)) return hipErrorInvalidValue;
     if (!rec_xcd_ready(a.H, a.act, bwd)) return hipErrorNotSupported;
     const void* fn = bwd ? xcd_kernel_for<true>(a.H, a.act) : xcd_kernel_for<false>(a.H, a.act);
     const size_t lds = xcd_lds_bytes();

@@ -38,3 +38,20 @@ def test_every_batch_size_at_this_hidden_size(H):
         assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
         compare(r.results(), oracle.fwd_bptt(case, h0=case.get("h0"), dh_last=case.get("dh_last")))
     assert len(seen) >= 2, seen        # every hidden size crosses at least one family boundary over these batches
+
+
+@pytest.mark.parametrize("H", (260, 512, 516, 1020, 1024))
+def test_the_one_launch_wide_loop_at_its_edges(H):
+    """Batch 5 and 64 (the smallest and the largest the one-launch wide loop takes), 20 steps (its
+    shortest sequence) and 19 (one launch per step), batch 65 (beyond it)."""
+    for n, (B, T, want) in enumerate(((5, 20, "xcd_mfma"), (64, 21, "xcd_mfma"), (64, 19, "step_mfma"),
+                                      (65, 20, "step_mfma"))):
+        case = ri.make_case(in_dim=90, hidden=H, out_dim=70, seq_len=T, batch=B, act=n % 2, with_h0=bool(n % 2),
+                            with_dh_last=n >= 2, wdist=("normal", 0.5 / np.sqrt(H)), bias_std=0.1, seed=9000 + 11 * H + n)
+        r = Runner(case)
+        variant = rnn.rnn_recurrence_variant(r.dims)
+        print(f"H={H} B={B} T={T} variant={variant}", flush=True)
+        assert variant == want
+        r.step()
+        assert rnn.rnn_workspace_status(r.dims, r.ws) == 0
+        compare(r.results(), oracle.fwd_bptt(case, h0=case.get("h0"), dh_last=case.get("dh_last")))

@@ -41,7 +41,7 @@ WINDOWS = {
     "hidden_200": dict(in_dim=300, hidden=200, out_dim=300, seq_len=12, batch=1, with_h0=True),
     "long_window": dict(in_dim=120, hidden=64, out_dim=120, seq_len=45, batch=1, act=ri.ACT_TANH, with_dh_last=True),
     "batch_of_three": dict(in_dim=90, hidden=40, out_dim=70, seq_len=5, batch=3, with_h0=True, with_dh_last=True),
-    "wide_batched": dict(in_dim=260, hidden=600, out_dim=260, seq_len=7, batch=13),
+    "wide_batched": dict(in_dim=260, hidden=600, out_dim=260, seq_len=22, batch=13),
 }
 
 

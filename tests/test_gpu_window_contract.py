@@ -197,7 +197,7 @@ def test_smallest_wait_limit_on_the_multi_workgroup_loops_never_hangs(shape):
     (status 0, results as the oracle's); either way every kernel ends, and after a new set-up of
     the workspace with the normal bound the next call is good."""
     from gpu_harness import Runner
-    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=7, batch=13) if shape == "wide_batched_loop"
+    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=22, batch=13) if shape == "wide_batched_loop"
             else dict(in_dim=200, hidden=300, out_dim=200, seq_len=9, batch=1))
     case = ri.make_case(wdist=("normal", 0.2), bias_std=0.1, seed=31, **spec)
     ref = oracle.fwd_bptt(case)
@@ -226,7 +226,7 @@ def test_replays_of_the_three_captured_calls_with_a_multi_workgroup_loop(shape):
     """The cooperative launches of the multi-workgroup time loops inside a captured graph: every
     replay (with the program's own eager work between replays) gives the oracle's results."""
     from gpu_harness import Runner
-    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=7, batch=13) if shape == "wide_batched_loop"
+    spec = (dict(in_dim=260, hidden=600, out_dim=260, seq_len=22, batch=13) if shape == "wide_batched_loop"
             else dict(in_dim=200, hidden=300, out_dim=200, seq_len=9, batch=1))
     case = ri.make_case(wdist=("normal", 0.2), bias_std=0.1, seed=31, **spec)
     ref = oracle.fwd_bptt(case)
