@@ -368,7 +368,7 @@ const char *rnn_strerror(int code);
  * reports and tests): "wg_resident" (one workgroup per sequence, weights in LDS),
  * "grid_resident" (several cooperating workgroups per sequence), "batch_mfma" (batched,
  * hidden <= 256: one persistent matrix-core workgroup per 4 batch rows, weights in registers),
- * "xcd_mfma" (batched, 256 < hidden <= 1024, batch <= 64, hidden % 4 == 0, at least 20 steps, on
+ * "xcd_mfma" (batched, 256 < hidden <= 1024, batch <= 64, hidden % 4 == 0, at least 10 steps, on
  * a device of 8 x 32 compute units: one persistent launch, 16 groups of 4 batch rows, two groups
  * per XCD),
  * "step_mfma" (other batched sizes: one fused matrix-core launch per step) or "reference". */

@@ -135,12 +135,56 @@ __global__ __launch_bounds__(XT) void rec_xcd_kernel(RecXcdArgs a) {
     //      outside the matrix ----------------------------------------------------------------------
     const int kb = KW * wave;
     float wreg[KW];
+    if (BWD) {
+        // M[k][col] = Wh[k][col]: a lane's values lie along a column of Wh.  Fetched as 16-byte pieces
+        // along the rows (a request covers four k of 256 bytes) into a wavefront-private LDS tile
+        // [64 k][64 columns], 64 k at a time, from which every lane takes its column.
+        float* stg = smem + wave * 64 * 65;
+        const int r4 = lane >> 4, c4 = 4 * (lane & 15);
 #pragma unroll
-    for (int j = 0; j < KW; ++j) {
-        const int kc = min(kb + j, H - 1);
-        const float w = BWD ? a.Wh[(size_t)kc * H + colc] : a.Wh[(size_t)colc * H + kc];
-        wreg[j] = (kb + j < H && col < H) ? w : 0.f;
-        if (j % 16 == 15) asm volatile("" ::: "memory");    // 16 requests at a time: their addresses need registers too
+        for (int q = 0; q < NQ; ++q) {
+            float4 v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int k = kb + 64 * q + r4 + 4 * i, cc = c0 + c4;
+                const bool on = k < H && cc < H;                     // H % 4 == 0: a piece is inside or outside
+                v[i] = on ? *reinterpret_cast<const float4*>(a.Wh + (size_t)k * H + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) *reinterpret_cast<float4*>(stg + (r4 + 4 * i) * 64 + c4) = v[i];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the tile is this wavefront's own
+#pragma unroll
+            for (int j = 0; j < 64; ++j) wreg[64 * q + j] = stg[j * 64 + lane];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __syncthreads();                                             // the partial tiles reuse this memory
+    } else {
+        // M[k][col] = Wh[col][k]: a lane's values lie along a row of Wh.  Fetched as 16-byte pieces
+        // along the rows (a request covers four rows of 256 bytes) and turned through a
+        // wavefront-private LDS tile [64 columns][64 k], 64 k at a time.
+        constexpr int PITCH = 65;                 // odd: the transposed reads fall into distinct banks
+        float* stg = smem + wave * 64 * PITCH;
+        const int r4 = lane >> 4, k4 = 4 * (lane & 15);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            float4 v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = c0 + r4 + 4 * i, k = kb + 64 * q + k4;
+                const bool on = row < H && k < H;                    // H % 4 == 0: a piece is inside or outside
+                v[i] = on ? *reinterpret_cast<const float4*>(a.Wh + (size_t)row * H + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float* d = stg + (r4 + 4 * i) * PITCH + k4;
+                d[0] = v[i].x; d[1] = v[i].y; d[2] = v[i].z; d[3] = v[i].w;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the tile is this wavefront's own
+#pragma unroll
+            for (int j = 0; j < 64; ++j) wreg[64 * q + j] = stg[lane * PITCH + j];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __syncthreads();                                             // the partial tiles reuse this memory
     }
 
     // ---- the state pieces of this lane: row ri, columns kb + 64 q + 4 kg .. + 3; pieces outside
@@ -335,16 +379,17 @@ const void* pick_xcd_kernel(int kw) {
     return kw == 64 ? (const void*)rec_xcd_kernel<ACT, BWD, 64> : (const void*)rec_xcd_kernel<ACT, BWD, 128>;
 }
 
-size_t xcd_lds_bytes() { return (size_t)2 * 8 * RB * CWD * 4; }
+// partial tiles of a step; the forward kernel first stages its matrix slice there
+size_t xcd_lds_bytes() { return (size_t)8 * 64 * 65 * 4; }
 
 }  // namespace
 
 // Shapes the one-launch loop serves and is the faster choice for.  The launch has a fixed cost (a
-// cooperative launch, every workgroup loading its 256 KB of the matrix: about 90 us forward, 60 us in
-// reverse) and then takes 2.2 us per step, against 5.5 us per step for a launch per step, so short
-// sequences stay with the latter (measured cross-over at H = 1024, batch 64: 16 to 20 steps).
+// cooperative launch, every workgroup loading its 256 KB of the matrix: about 28 us) and then takes
+// 2.1 us per step, against 5.5 us per step for a launch per step, so the shortest sequences stay with
+// the latter (cross-over at H = 1024, batch 64: 8 to 10 steps).
 bool rec_xcd_supported(int H, int B, int T) {
-    return T >= 20 && B > 4 && B <= NGRP * RB && H > 256 && H <= NSLOT * CWD && H % 4 == 0;
+    return T >= 10 && B > 4 && B <= NGRP * RB && H > 256 && H <= NSLOT * CWD && H % 4 == 0;
 }
 
 template <bool BWD>

@@ -42,9 +42,9 @@ def test_every_batch_size_at_this_hidden_size(H):
 
 @pytest.mark.parametrize("H", (260, 512, 516, 1020, 1024))
 def test_the_one_launch_wide_loop_at_its_edges(H):
-    """Batch 5 and 64 (the smallest and the largest the one-launch wide loop takes), 20 steps (its
-    shortest sequence) and 19 (one launch per step), batch 65 (beyond it)."""
-    for n, (B, T, want) in enumerate(((5, 20, "xcd_mfma"), (64, 21, "xcd_mfma"), (64, 19, "step_mfma"),
+    """Batch 5 and 64 (the smallest and the largest the one-launch wide loop takes), 10 steps (its
+    shortest sequence) and 9 (one launch per step), batch 65 (beyond it)."""
+    for n, (B, T, want) in enumerate(((5, 10, "xcd_mfma"), (64, 21, "xcd_mfma"), (64, 9, "step_mfma"),
                                       (65, 20, "step_mfma"))):
         case = ri.make_case(in_dim=90, hidden=H, out_dim=70, seq_len=T, batch=B, act=n % 2, with_h0=bool(n % 2),
                             with_dh_last=n >= 2, wdist=("normal", 0.5 / np.sqrt(H)), bias_std=0.1, seed=9000 + 11 * H + n)

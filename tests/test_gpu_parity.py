@@ -33,13 +33,13 @@ SMALL_CASES = {
     "lm_batch5_stepwise": (200, 70, 200, 6, 5, dict(LM, wdist=("normal", 0.3), bias_std=0.2, with_h0=True, with_dh_last=True)),
     "dense_batched_stepwise": (48, 160, 40, 12, 40, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True)),
     "lm_batched_wide_stepwise": (300, 320, 300, 5, 24, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
-    # the per-XCD persistent loop (20 steps and more): ragged batch groups and column slices, both K widths,
-    # the shortest sequence it takes, dense/tanh; and the same widths below 20 steps (one launch per step)
+    # the per-XCD persistent loop (10 steps and more): ragged batch groups and column slices, both K widths,
+    # the shortest sequence it takes, dense/tanh; and the same widths below 10 steps (one launch per step)
     "lm_xcd_ragged_groups": (260, 600, 260, 23, 13, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
     "dense_xcd_tanh": (48, 388, 40, 21, 61, dict(DENSE, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
-    "lm_xcd_shortest": (120, 1024, 120, 20, 9, dict(LM, wdist=("normal_fan", None), with_h0=True)),
+    "lm_xcd_shortest": (120, 1024, 120, 10, 9, dict(LM, wdist=("normal_fan", None), with_h0=True)),
     "lm_wide_one_step": (120, 1024, 120, 1, 9, dict(LM, wdist=("normal_fan", None), with_h0=True)),
-    "lm_wide_19_steps": (260, 600, 260, 19, 13, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
+    "lm_wide_9_steps": (260, 600, 260, 9, 13, dict(LM, wdist=("normal_fan", None), bias_std=0.1, with_h0=True, with_dh_last=True)),
     "lm_batched_ragged_mfma": (150, 100, 150, 7, 21, dict(LM, wdist=("normal", 0.2), bias_std=0.2, with_h0=True, with_dh_last=True)),
     "lm_long_id_list_chunked_scatter": (500, 64, 500, 128, 20, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
     "lm_multi_tile": (1000, 132, 1000, 40, 4, dict(LM, wdist=("normal", 0.2), bias_std=0.1)),
